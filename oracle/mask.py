@@ -1,0 +1,85 @@
+"""Mask predicate and 64-bit per-token bitfield (paper section 4.2, bitfield
+attention mask; App. C mask families).
+
+Per token t the layout gives
+  sample(t)  index of the packed sample holding t (App. C, multimodal packing)
+  span(t)    0 for text, else the 1-based id of the bidirectional span
+  causal(t)  1 if the token attends to all of its previous tokens (the
+             bitfield's most-significant "causal" bit, section 4.2)
+  modality(t) 0 text / 1 image / 2 audio ...
+and the predicate is
+  vis(q,k) = [sample(q)=sample(k)] and
+             ( [causal(q) and k<=q]  or  [span(q)!=0 and span(q)=span(k)] ).
+Text is causal, a modality span is bidirectional within itself (and causal
+to what precedes it when its causal bit is set), packed samples never see
+each other.
+
+Word layout (LSB first, section 4.2: low bits = LLM and modality encoders,
+bit 63 = causal bit):
+  bits 0-7   attend-set, bit m set = may attend modality m   (all set here)
+  bits 8-11  own modality index
+  bits 12-27 span id (0 = none)
+  bits 28-43 sample id
+  bit 63     causal bit
+
+Pins: tests/test_oracle_mask.py -- closed-form pair totals
+sum L(L+1)/2 + sum n(n-1)/2, all-text = lower triangle, one span covering
+everything = all ones, packed = block diagonal, the section-4.2 worked example
+(encoder tokens without the causal bit see only their own encoder's tokens;
+text tokens see every earlier token), encode/decode round trip.
+"""
+import numpy as np
+
+ATTEND_ALL = 0xFF
+CAUSAL_BIT = 63
+
+
+def token_fields(S, spans, sample_off, noncausal=None):
+    """Expand a layout into per-token arrays (sample, span, causal, modality).
+
+    spans: iterable of (start, len, modality) in increasing start order.
+    sample_off: n_samples+1 offsets with [0]=0 and [-1]=S.
+    noncausal: optional per-span flag; 1 clears the causal bit of that span.
+    """
+    sample = np.zeros(S, dtype=np.int64)
+    span = np.zeros(S, dtype=np.int64)
+    causal = np.ones(S, dtype=np.int64)
+    modality = np.zeros(S, dtype=np.int64)
+    for i in range(len(sample_off) - 1):
+        sample[sample_off[i]:sample_off[i + 1]] = i
+    for j, (start, n, mod) in enumerate(spans):
+        span[start:start + n] = j + 1
+        modality[start:start + n] = mod
+        if noncausal is not None and noncausal[j]:
+            causal[start:start + n] = 0
+    return sample, span, causal, modality
+
+
+def visible(q_idx, k_idx, sample, span, causal):
+    """Boolean matrix vis[q,k] for global token index arrays q_idx, k_idx."""
+    q = np.asarray(q_idx)[:, None]
+    k = np.asarray(k_idx)[None, :]
+    same_sample = sample[q] == sample[k]
+    back = (causal[q] == 1) & (k <= q)
+    same_span = (span[q] != 0) & (span[q] == span[k])
+    return same_sample & (back | same_span)
+
+
+def encode(sample, span, causal, modality):
+    """Per-token 64-bit word from the fields, as uint64."""
+    w = np.full(sample.shape, ATTEND_ALL, dtype=np.uint64)
+    w |= modality.astype(np.uint64) << np.uint64(8)
+    w |= span.astype(np.uint64) << np.uint64(12)
+    w |= sample.astype(np.uint64) << np.uint64(28)
+    w |= causal.astype(np.uint64) << np.uint64(CAUSAL_BIT)
+    return w
+
+
+def decode(bits):
+    """Inverse of encode: (sample, span, causal, modality)."""
+    b = np.asarray(bits, dtype=np.uint64)
+    modality = ((b >> np.uint64(8)) & np.uint64(0xF)).astype(np.int64)
+    span = ((b >> np.uint64(12)) & np.uint64(0xFFFF)).astype(np.int64)
+    sample = ((b >> np.uint64(28)) & np.uint64(0xFFFF)).astype(np.int64)
+    causal = ((b >> np.uint64(CAUSAL_BIT)) & np.uint64(1)).astype(np.int64)
+    return sample, span, causal, modality

@@ -1,0 +1,154 @@
+"""Pins for oracle/mask.py and oracle/tilemap.py (CPU only)."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import mask as om
+from oracle import tilemap as ot
+from paper_2503_11367_amd import workloads as wl
+
+
+def fields(lay):
+    return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal)
+
+
+def dense(lay):
+    sample, span, causal, _ = fields(lay)
+    idx = np.arange(lay.S)
+    return om.visible(idx, idx, sample, span, causal)
+
+
+def closed_form_pairs(lay):
+    """sum over samples L(L+1)/2 + sum over spans n(n-1)/2 (causal bit set)."""
+    tot = 0
+    for a, b in zip(lay.sample_off[:-1], lay.sample_off[1:]):
+        L = b - a
+        tot += L * (L + 1) // 2
+    for _, n, _ in lay.spans:
+        tot += n * (n - 1) // 2
+    return tot
+
+
+def test_all_text_is_lower_triangle():
+    lay = wl.Layout(96, [], [0, 96])
+    assert np.array_equal(dense(lay), np.tril(np.ones((96, 96), dtype=bool)))
+
+
+def test_single_span_is_full():
+    lay = wl.Layout(80, [(0, 80, wl.IMAGE)], [0, 80])
+    assert dense(lay).all()
+
+
+def test_packed_is_block_diagonal():
+    lay = wl.Layout(100, [], [0, 30, 100])
+    v = dense(lay)
+    assert not v[30:, :30].any() and not v[:30, 30:].any()
+    assert np.array_equal(v[:30, :30], np.tril(np.ones((30, 30), dtype=bool)))
+    assert np.array_equal(v[30:, 30:], np.tril(np.ones((70, 70), dtype=bool)))
+
+
+def test_span_rows_by_hand():
+    # text[0:2] image[2:5] text[5:7]
+    lay = wl.Layout(7, [(2, 3, wl.IMAGE)], [0, 7])
+    expect = np.array([
+        [1, 0, 0, 0, 0, 0, 0],
+        [1, 1, 0, 0, 0, 0, 0],
+        [1, 1, 1, 1, 1, 0, 0],
+        [1, 1, 1, 1, 1, 0, 0],
+        [1, 1, 1, 1, 1, 0, 0],
+        [1, 1, 1, 1, 1, 1, 0],
+        [1, 1, 1, 1, 1, 1, 1]], dtype=bool)
+    assert np.array_equal(dense(lay), expect)
+
+
+def test_paper_bitfield_example():
+    """Section 4.2: t2,t3 come from encoder A and carry no causal bit, so they
+    attend only to encoder-A tokens; t4,t5 are text with the causal bit and
+    attend to every earlier token whatever its modality."""
+    lay = wl.Layout(6, [(2, 2, wl.IMAGE)], [0, 6], noncausal=[1])
+    v = dense(lay)
+    assert v[2].tolist() == [False, False, True, True, False, False]
+    assert v[3].tolist() == [False, False, True, True, False, False]
+    assert v[4].tolist() == [True, True, True, True, True, False]
+    assert v[5].tolist() == [True] * 6
+    sample, span, causal, modality = fields(lay)
+    bits = om.encode(sample, span, causal, modality)
+    assert (int(bits[2]) >> 63) == 0 and (int(bits[4]) >> 63) == 1
+    assert (int(bits[2]) >> 8) & 0xF == wl.IMAGE and (int(bits[4]) >> 8) & 0xF == wl.TEXT
+    assert int(bits[4]) & 0xFF == 0xFF        # text attends all modalities
+
+
+def test_encode_decode_round_trip():
+    lay = wl.layout_packed(seed=7, S=4096, n_samples=5, span_lo=40, span_hi=300)
+    f = fields(lay)
+    bits = om.encode(*f)
+    assert bits.dtype == np.uint64
+    for a, b in zip(om.decode(bits), f):
+        assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_total_pairs_closed_form_random(seed):
+    lay = wl.layout_random(seed, S=384, n_samples=1 + seed % 3)
+    assert int(dense(lay).sum()) == closed_form_pairs(lay)
+
+
+def test_tiny_golden(golden_dir):
+    W, rows = None, []
+    for line in open(os.path.join(golden_dir, "tiny_tilemap.txt")):
+        if line.startswith("W "):
+            W = [int(x) for x in line.split()[1:]]
+        elif line.startswith("C "):
+            rows.append(line.split()[1])
+    lay = wl.layout_tiny()
+    sample, span, causal, _ = fields(lay)
+    cls, cnt, Wo = ot.tile_map(sample, span, causal, 64, 64)
+    assert Wo.tolist() == W and sum(W) == 163968 == closed_form_pairs(lay)
+    sym = {ot.EMPTY: "E", ot.FULL: "F", ot.PARTIAL: "P"}
+    assert ["".join(sym[c] for c in r) for r in cls.tolist()] == rows
+    assert (cnt[cls == ot.PARTIAL] == 2080).all()
+    assert ot.tile_count_workload(cls).tolist() == [1, 5, 5, 5, 5, 6, 7, 8]
+
+
+def test_all_text_tile_classes():
+    lay = wl.Layout(256, [], [0, 256])
+    sample, span, causal, _ = fields(lay)
+    cls, cnt, W = ot.tile_map(sample, span, causal, 32, 32)
+    for i in range(8):
+        for j in range(8):
+            want = ot.FULL if j < i else (ot.PARTIAL if j == i else ot.EMPTY)
+            assert cls[i, j] == want
+    assert (np.diag(cnt) == 32 * 33 // 2).all()
+
+
+def test_rect_tiles_and_dense_agree():
+    lay = wl.layout_random(11, S=512, n_samples=2)
+    sample, span, causal, _ = fields(lay)
+    v = dense(lay)
+    cls, cnt, W = ot.tile_map(sample, span, causal, 128, 64)
+    ref = v.reshape(4, 128, 8, 64).sum(axis=(1, 3))
+    assert np.array_equal(cnt, ref)
+    assert np.array_equal(W, v.sum(axis=1).reshape(4, 128).sum(axis=1))
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_c_tilemap_matches_numpy(seed):
+    lay = wl.layout_random(100 + seed, S=1024, n_samples=1 + seed, noncausal_prob=0.3)
+    f = fields(lay)
+    a = ot.tile_map(f[0], f[1], f[2], 64, 128)
+    b = ot.tile_map_c(f[0], f[1], f[2], 64, 128)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("c", [2, 3, 5])
+def test_workload_totals_closed_form(c):
+    w = wl.workload(c)
+    sample, span, causal, _ = fields(w.layout)
+    cls, cnt, W = ot.tile_map_c(sample, span, causal, w.N_B, w.N_B)
+    assert int(W.sum()) == closed_form_pairs(w.layout)
+    if c == 2:
+        assert int(W.sum()) == 35653632
+    if c == 3:
+        assert int(W.sum()) == 553961064
