@@ -1,0 +1,161 @@
+/* mmattn -- multimodal-masked attention for workload-balanced context
+ * parallelism on AMD MI355X (gfx950).  C ABI; all pointers are plain device
+ * or host pointers as stated per argument; no C++ or framework types.
+ *
+ * The five calls follow the paper's statement of the problem:
+ *   section 4.2  (bitfield attention mask: one 64-bit word per token)
+ *   section 3.2.1 (blocks whose mask block is all zeros are skipped; per-block
+ *                  workload counted row-wise; Alg. 1 LPT assignment)
+ *   section 4.3  (each rank computes row-wise attention for its local queries
+ *                  against all gathered keys and values)
+ *
+ * Conventions
+ *   S        sequence length (tokens), K/V cover all S tokens
+ *   block    balancer block size N_B (tokens); a rank owns a list of blocks
+ *   local row r of a rank  <->  global token blocks[r / block]*block + r % block
+ *   Hq, Hkv  query / key-value heads, Hq % Hkv == 0, Q head h uses KV head
+ *            h / (Hq/Hkv)
+ *   layouts  q_loc, o_loc, do_loc, dq_loc : [n_loc, Hq, D]   bf16, D contiguous
+ *            k, v, dk, dv                 : [S, Hkv, D]      bf16
+ *            lse                          : [Hq, n_loc]      fp32, natural log
+ *            bits                         : [S]              uint64
+ *
+ * Mask word (LSB first): bits 0-7 attend-set (bit m = may attend modality m),
+ * bits 8-11 own modality, bits 12-27 span id (0 = not in a bidirectional
+ * span), bits 28-43 sample id, bit 63 causal bit.  Visibility of key k to
+ * query q:
+ *   sample(q)==sample(k) && ( (causal(q) && k<=q) ||
+ *                             (span(q)!=0 && span(q)==span(k)) )
+ * The attend-set and modality fields are carried but not consulted.
+ *
+ * Ownership: the caller owns every buffer and the stream.  The library
+ * allocates no device memory, keeps no state between calls and never
+ * synchronises the stream; scratch comes in through `ws` (size from
+ * mmattn_workspace_size, 256-byte aligned).  Host pointers are read before
+ * the call returns.
+ *
+ * Errors: every call returns MMATTN_OK (0) or a negative mmattn_status.  All
+ * argument checks run on the host before any GPU work is enqueued; nothing is
+ * launched when a check fails.  Launch/runtime failures give MMATTN_ERR_HIP.
+ */
+#ifndef MMATTN_H
+#define MMATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MMATTN_OK = 0,
+    MMATTN_ERR_NULL = -1,        /* a required pointer is null */
+    MMATTN_ERR_SHAPE = -2,       /* sizes inconsistent (divisibility, ranges) */
+    MMATTN_ERR_UNSUPPORTED = -3, /* valid but not built (head_dim, dtype, limits) */
+    MMATTN_ERR_WORKSPACE = -4,   /* ws null/misaligned/too small */
+    MMATTN_ERR_LAYOUT = -5,      /* span/sample list malformed */
+    MMATTN_ERR_HIP = -6          /* HIP runtime reported an error */
+} mmattn_status;
+
+typedef enum { MMATTN_BF16 = 0 } mmattn_dtype;
+
+typedef enum {
+    MMATTN_OP_ENCODE = 0, MMATTN_OP_TILE_MAP = 1, MMATTN_OP_BALANCE = 2,
+    MMATTN_OP_FWD = 3, MMATTN_OP_BWD = 4
+} mmattn_op;
+
+enum { MMATTN_TILE_EMPTY = 0, MMATTN_TILE_FULL = 1, MMATTN_TILE_PARTIAL = 2 };
+
+/* A bidirectional (image/audio/...) span.  Tokens outside every span are
+ * causal text.  flags bit 0 (MMATTN_SPAN_NONCAUSAL) clears the causal bit of
+ * the span's tokens: they then see only their own span (section 4.2's
+ * encoder tokens "without the causal bit"). */
+typedef struct { int64_t start, len; int32_t modality, flags; } mmattn_span;
+#define MMATTN_SPAN_NONCAUSAL 1
+#define MMATTN_MAX_SPANS   65535
+#define MMATTN_MAX_SAMPLES 65535
+#define MMATTN_MAX_BLOCKS  16384   /* nB accepted by mmattn_balance */
+#define MMATTN_MAX_RANKS   1024    /* P accepted by mmattn_balance */
+
+/* Bytes of scratch the given call needs for these sizes (0 if none).  For
+ * ENCODE pass n_blocks = n_spans and block = n_samples; for TILE_MAP and
+ * BALANCE the result is 0.  Returns 0 for invalid sizes as well; the call
+ * itself reports the error. */
+size_t mmattn_workspace_size(int op, int64_t S, int32_t n_blocks, int32_t block,
+                             int32_t Hq, int32_t Hkv, int32_t D);
+
+/* Section 4.2: build the per-token 64-bit mask words.
+ *   spans      host, n_spans entries sorted by start, disjoint, inside one
+ *              sample each, modality in 1..15; span id = index+1
+ *   sample_off host, n_samples+1 increasing offsets, [0]=0, [n_samples]=S
+ *   d_bits     device, S words, overwritten
+ *   ws         device scratch (staging of the two host lists)
+ * MMATTN_ERR_LAYOUT for unsorted/overlapping/out-of-range spans, a span that
+ * crosses a sample boundary, or bad offsets. */
+int mmattn_mask_encode(const mmattn_span* spans, int32_t n_spans,
+                       const int64_t* sample_off, int32_t n_samples,
+                       int64_t S, uint64_t* d_bits,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* Section 3.2.1: classify every (q-tile, k-tile) of the S x S mask and count
+ * its unmasked pairs; a tile whose mask block is all zeros is EMPTY (skipped
+ * by the attention kernels).
+ *   d_bits     device, S words
+ *   tq, tk     tile shape in tokens; S % tq == 0, S % tk == 0,
+ *              tq*tk <= 2^31
+ *   d_cls      device uint8  [S/tq][S/tk]  MMATTN_TILE_*           (may be null)
+ *   d_cnt      device uint32 [S/tq][S/tk]  unmasked pairs per tile
+ *   d_rowpairs device uint64 [S/tq]        W_b = pairs of q-tile b (may be null)
+ */
+int mmattn_tile_map(const uint64_t* d_bits, int64_t S, int32_t tq, int32_t tk,
+                    uint8_t* d_cls, uint32_t* d_cnt, uint64_t* d_rowpairs,
+                    void* stream);
+
+/* Alg. 1 (section 3.2.1), LPT: visit blocks by (W descending, index
+ * ascending); give each to the rank with (load ascending, rank ascending).
+ * Integer-only and deterministic.
+ *   d_W            device uint64 [nB] workloads
+ *   d_rank_of_block device int32 [nB]
+ *   d_load         device uint64 [P]   sum of W per rank
+ *   d_rank_off     device int32 [P+1]  CSR offsets into d_rank_blocks
+ *   d_rank_blocks  device int32 [nB]   each rank's blocks, ascending index
+ * 1 <= nB <= MMATTN_MAX_BLOCKS, 1 <= P <= MMATTN_MAX_RANKS. */
+int mmattn_balance(const uint64_t* d_W, int32_t nB, int32_t P,
+                   int32_t* d_rank_of_block, uint64_t* d_load,
+                   int32_t* d_rank_off, int32_t* d_rank_blocks, void* stream);
+
+/* Section 4.3 / 4.2: attention forward for one rank's query blocks against
+ * all S keys/values under the bitfield mask; fully masked tiles are skipped.
+ *   q_loc,k,v,bits,blocks  device inputs (layouts above); blocks[n_blocks]
+ *                          int32 block indices in [0, S/block), distinct
+ *   o_loc, lse             device outputs, overwritten; a row with no visible
+ *                          key gets O = 0 and LSE = -inf
+ *   scale                  softmax scale (1/sqrt(D) usually), > 0
+ * Requires S % 128 == 0, block % 16 == 0, S % block == 0, D in {64,128},
+ * 16-byte aligned tensors. */
+int mmattn_fwd(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
+               const int32_t* blocks, int32_t n_blocks, int32_t block,
+               int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,
+               void* o_loc, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of mmattn_fwd for the same rank share.
+ *   o_loc, lse   what mmattn_fwd wrote;  do_loc upstream gradient
+ *   dq_loc       [n_loc,Hq,D] overwritten
+ *   dk, dv       [S,Hkv,D] overwritten with THIS rank's partial sums over its
+ *                rows and over the Hq/Hkv query heads of each KV head (rows
+ *                of keys no query of the rank sees become 0)
+ */
+int mmattn_bwd(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
+               const int32_t* blocks, int32_t n_blocks, int32_t block,
+               int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,
+               const void* o_loc, const float* lse, const void* do_loc,
+               void* dq_loc, void* dk, void* dv, void* ws, size_t ws_bytes, void* stream);
+
+/* Library version string (static storage). */
+const char* mmattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMATTN_H */

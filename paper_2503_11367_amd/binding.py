@@ -1,0 +1,191 @@
+"""Thin ctypes binding over libmmattn.so (include/mmattn.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  PyTorch supplies device memory and the current stream.  There is no
+fallback: if the library has not been built, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmmattn.so")
+
+OK = 0
+ERR_NAMES = {0: "OK", -1: "ERR_NULL", -2: "ERR_SHAPE", -3: "ERR_UNSUPPORTED",
+             -4: "ERR_WORKSPACE", -5: "ERR_LAYOUT", -6: "ERR_HIP"}
+OP_ENCODE, OP_TILE_MAP, OP_BALANCE, OP_FWD, OP_BWD = range(5)
+TILE_EMPTY, TILE_FULL, TILE_PARTIAL = 0, 1, 2
+SPAN_NONCAUSAL = 1
+BF16 = 0
+
+
+class Span(ctypes.Structure):
+    _fields_ = [("start", ctypes.c_int64), ("len", ctypes.c_int64),
+                ("modality", ctypes.c_int32), ("flags", ctypes.c_int32)]
+
+
+class MMAttnError(RuntimeError):
+    def __init__(self, call: str, rc: int):
+        super().__init__(f"{call} failed: {ERR_NAMES.get(rc, rc)} ({rc})")
+        self.rc = rc
+
+
+_lib = None
+_vp, _i32, _i64, _sz, _f32 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t,
+                               ctypes.c_float)
+
+
+def lib() -> ctypes.CDLL:
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2503_11367_amd.build` (no CPU fallback exists)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.mmattn_version.restype = ctypes.c_char_p
+        L.mmattn_workspace_size.restype = _sz
+        L.mmattn_workspace_size.argtypes = [ctypes.c_int, _i64, _i32, _i32, _i32, _i32, _i32]
+        L.mmattn_mask_encode.restype = ctypes.c_int
+        L.mmattn_mask_encode.argtypes = [_vp, _i32, _vp, _i32, _i64, _vp, _vp, _sz, _vp]
+        L.mmattn_tile_map.restype = ctypes.c_int
+        L.mmattn_tile_map.argtypes = [_vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]
+        L.mmattn_balance.restype = ctypes.c_int
+        L.mmattn_balance.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
+        L.mmattn_fwd.restype = ctypes.c_int
+        L.mmattn_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
+                                 ctypes.c_int, _vp, _vp, _vp, _sz, _vp]
+        L.mmattn_bwd.restype = ctypes.c_int
+        L.mmattn_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
+                                 ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+        _lib = L
+    return _lib
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _check(call: str, rc: int):
+    if rc != OK:
+        raise MMAttnError(call, rc)
+
+
+def workspace_size(op: int, S: int, n_blocks: int, block: int, Hq: int = 0, Hkv: int = 0,
+                   D: int = 0) -> int:
+    return int(lib().mmattn_workspace_size(op, S, n_blocks, block, Hq, Hkv, D))
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def mask_encode(spans: Sequence[Tuple[int, int, int]], sample_off: Sequence[int], S: int,
+                device="cuda", flags: Optional[Sequence[int]] = None, stream=None,
+                bits: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """mmattn_mask_encode.  spans: (start, len, modality); returns int64[S]
+    holding the 64-bit words."""
+    n = len(spans)
+    arr = (Span * max(n, 1))()
+    for i, (st, ln, mod) in enumerate(spans):
+        arr[i] = Span(int(st), int(ln), int(mod), int(flags[i]) if flags else 0)
+    off = (ctypes.c_int64 * len(sample_off))(*[int(x) for x in sample_off])
+    if bits is None:
+        bits = torch.empty(S, dtype=torch.int64, device=device)
+    ws = _workspace(workspace_size(OP_ENCODE, S, n, len(sample_off) - 1), bits.device)
+    rc = lib().mmattn_mask_encode(ctypes.addressof(arr) if n else 0, n, ctypes.addressof(off),
+                                  len(sample_off) - 1, S, _ptr(bits), _ptr(ws), ws.numel(),
+                                  _stream(stream))
+    _check("mmattn_mask_encode", rc)
+    return bits
+
+
+def tile_map(bits: torch.Tensor, tq: int, tk: int, stream=None, want_cls=True, want_rowpairs=True):
+    """mmattn_tile_map -> (cls uint8 [nq,nk], cnt int32-view-of-uint32 [nq,nk],
+    rowpairs int64-view-of-uint64 [nq])."""
+    S = bits.numel()
+    nq, nk = max(S // max(tq, 1), 0), max(S // max(tk, 1), 0)
+    dev = bits.device
+    cls = torch.empty((nq, nk), dtype=torch.uint8, device=dev) if want_cls else None
+    cnt = torch.empty((nq, nk), dtype=torch.int32, device=dev)
+    rp = torch.empty(nq, dtype=torch.int64, device=dev) if want_rowpairs else None
+    rc = lib().mmattn_tile_map(_ptr(bits), S, tq, tk, _ptr(cls), _ptr(cnt), _ptr(rp),
+                               _stream(stream))
+    _check("mmattn_tile_map", rc)
+    return cls, cnt, rp
+
+
+def balance(W: torch.Tensor, P: int, stream=None):
+    """mmattn_balance -> (rank_of_block int32[nB], load int64[P], rank_off
+    int32[P+1], rank_blocks int32[nB])."""
+    nB = W.numel()
+    dev = W.device
+    rob = torch.empty(nB, dtype=torch.int32, device=dev)
+    load = torch.empty(max(P, 1), dtype=torch.int64, device=dev)
+    off = torch.empty(max(P, 1) + 1, dtype=torch.int32, device=dev)
+    blocks = torch.empty(nB, dtype=torch.int32, device=dev)
+    rc = lib().mmattn_balance(_ptr(W), nB, P, _ptr(rob), _ptr(load), _ptr(off), _ptr(blocks),
+                              _stream(stream))
+    _check("mmattn_balance", rc)
+    return rob, load, off, blocks
+
+
+def fwd(q_loc: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bits: torch.Tensor,
+        blocks: torch.Tensor, block: int, scale: Optional[float] = None, stream=None,
+        ws: Optional[torch.Tensor] = None, out=None):
+    """mmattn_fwd.  q_loc [n_loc,Hq,D], k/v [S,Hkv,D] bf16; blocks int32.
+    Returns (o_loc bf16 [n_loc,Hq,D], lse fp32 [Hq,n_loc])."""
+    n_loc, Hq, D = q_loc.shape
+    S, Hkv, _ = k.shape
+    n_blocks = blocks.numel()
+    scale = float(D) ** -0.5 if scale is None else float(scale)
+    if out is None:
+        o = torch.empty_like(q_loc)
+        lse = torch.empty((Hq, n_loc), dtype=torch.float32, device=q_loc.device)
+    else:
+        o, lse = out
+    if ws is None:
+        ws = _workspace(workspace_size(OP_FWD, S, n_blocks, block, Hq, Hkv, D), q_loc.device)
+    rc = lib().mmattn_fwd(_ptr(q_loc), _ptr(k), _ptr(v), _ptr(bits), _ptr(blocks), n_blocks, block,
+                          S, Hq, Hkv, D, scale, BF16, _ptr(o), _ptr(lse), _ptr(ws), ws.numel(),
+                          _stream(stream))
+    _check("mmattn_fwd", rc)
+    return o, lse
+
+
+def bwd(q_loc, k, v, bits, blocks, block: int, o_loc, lse, do_loc, scale: Optional[float] = None,
+        stream=None, ws: Optional[torch.Tensor] = None, out=None):
+    """mmattn_bwd -> (dq_loc [n_loc,Hq,D], dk [S,Hkv,D], dv [S,Hkv,D]) bf16."""
+    n_loc, Hq, D = q_loc.shape
+    S, Hkv, _ = k.shape
+    n_blocks = blocks.numel()
+    scale = float(D) ** -0.5 if scale is None else float(scale)
+    if out is None:
+        dq, dk, dv = torch.empty_like(q_loc), torch.empty_like(k), torch.empty_like(v)
+    else:
+        dq, dk, dv = out
+    if ws is None:
+        ws = _workspace(workspace_size(OP_BWD, S, n_blocks, block, Hq, Hkv, D), q_loc.device)
+    rc = lib().mmattn_bwd(_ptr(q_loc), _ptr(k), _ptr(v), _ptr(bits), _ptr(blocks), n_blocks, block,
+                          S, Hq, Hkv, D, scale, BF16, _ptr(o_loc), _ptr(lse), _ptr(do_loc),
+                          _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(), _stream(stream))
+    _check("mmattn_bwd", rc)
+    return dq, dk, dv
+
+
+def bf16_from_bits(bits_u16: np.ndarray, device="cuda") -> torch.Tensor:
+    """uint16 bf16 patterns (host) -> bf16 tensor on the device."""
+    t = torch.from_numpy(np.ascontiguousarray(bits_u16).view(np.int16))
+    return t.to(device).view(torch.bfloat16)

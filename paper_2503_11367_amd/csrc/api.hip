@@ -1,0 +1,128 @@
+// C ABI of libmmattn: argument validation (host only, before any HIP call)
+// and dispatch to the kernels.  See include/mmattn.h for the contract.
+#include "common.h"
+
+using namespace mm;
+
+namespace {
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+int check_attn(const void* q, const void* k, const void* v, const uint64_t* bits,
+               const int32_t* blocks, int32_t n_blocks, int32_t block, int64_t S, int32_t Hq,
+               int32_t Hkv, int32_t D, float scale, int dtype) {
+    if (!q || !k || !v || !bits || !blocks) return MMATTN_ERR_NULL;
+    if (dtype != MMATTN_BF16) return MMATTN_ERR_UNSUPPORTED;
+    if (S <= 0 || n_blocks <= 0 || block <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0)
+        return MMATTN_ERR_SHAPE;
+    if (Hq % Hkv != 0 || S % block != 0 || (int64_t)n_blocks > S / block) return MMATTN_ERR_SHAPE;
+    if (!(scale > 0.0f)) return MMATTN_ERR_SHAPE;
+    if (D != 64 && D != 128) return MMATTN_ERR_UNSUPPORTED;
+    if (S % 128 != 0 || block % 16 != 0) return MMATTN_ERR_UNSUPPORTED;
+    if (S > ((int64_t)1 << 30) || Hq > 4096) return MMATTN_ERR_UNSUPPORTED;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(bits, 8) ||
+        !aligned(blocks, 4))
+        return MMATTN_ERR_SHAPE;
+    return MMATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mmattn_version(void) { return "mmattn 0.1 (gfx950)"; }
+
+size_t mmattn_workspace_size(int op, int64_t S, int32_t n_blocks, int32_t block, int32_t Hq,
+                             int32_t Hkv, int32_t D) {
+    if (S <= 0 || n_blocks < 0 || block < 0) return 0;
+    switch (op) {
+        case MMATTN_OP_ENCODE:
+            return align_up((size_t)n_blocks * sizeof(mmattn_span), 256) +
+                   align_up(((size_t)block + 1) * sizeof(int64_t), 256);
+        case MMATTN_OP_FWD:
+            if (Hq <= 0 || Hkv <= 0 || D <= 0 || block <= 0 || n_blocks <= 0) return 0;
+            return fwd_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D);
+        case MMATTN_OP_BWD:
+            if (Hq <= 0 || Hkv <= 0 || D <= 0 || block <= 0 || n_blocks <= 0) return 0;
+            return bwd_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D);
+        default:
+            return 0;
+    }
+}
+
+int mmattn_mask_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* sample_off,
+                       int32_t n_samples, int64_t S, uint64_t* d_bits, void* ws, size_t ws_bytes,
+                       void* stream) {
+    if (!sample_off || !d_bits || (n_spans > 0 && !spans)) return MMATTN_ERR_NULL;
+    if (S <= 0 || n_spans < 0 || n_samples < 1) return MMATTN_ERR_SHAPE;
+    if (n_spans > MMATTN_MAX_SPANS || n_samples > MMATTN_MAX_SAMPLES) return MMATTN_ERR_UNSUPPORTED;
+    if (sample_off[0] != 0 || sample_off[n_samples] != S) return MMATTN_ERR_LAYOUT;
+    for (int i = 0; i < n_samples; ++i)
+        if (sample_off[i + 1] <= sample_off[i]) return MMATTN_ERR_LAYOUT;
+    int smp = 0;
+    int64_t prev_end = 0;
+    for (int j = 0; j < n_spans; ++j) {
+        const mmattn_span& sp = spans[j];
+        if (sp.len <= 0 || sp.start < prev_end || sp.start + sp.len > S) return MMATTN_ERR_LAYOUT;
+        if (sp.modality < 1 || sp.modality > 15) return MMATTN_ERR_LAYOUT;
+        while (sample_off[smp + 1] <= sp.start) ++smp;
+        if (sp.start + sp.len > sample_off[smp + 1]) return MMATTN_ERR_LAYOUT;   // crosses samples
+        prev_end = sp.start + sp.len;
+    }
+    const size_t need = mmattn_workspace_size(MMATTN_OP_ENCODE, S, n_spans, n_samples, 0, 0, 0);
+    if (!ws || !aligned(ws, 256) || ws_bytes < need) return MMATTN_ERR_WORKSPACE;
+    return launch_encode(spans, n_spans, sample_off, n_samples, S, d_bits, ws, (hipStream_t)stream);
+}
+
+int mmattn_tile_map(const uint64_t* d_bits, int64_t S, int32_t tq, int32_t tk, uint8_t* d_cls,
+                    uint32_t* d_cnt, uint64_t* d_rowpairs, void* stream) {
+    if (!d_bits || !d_cnt) return MMATTN_ERR_NULL;
+    if (S <= 0 || tq <= 0 || tk <= 0 || S % tq != 0 || S % tk != 0) return MMATTN_ERR_SHAPE;
+    if ((int64_t)tq * tk > ((int64_t)1 << 31)) return MMATTN_ERR_SHAPE;
+    if (S / tq > 65535 || S / tk > ((int64_t)1 << 24)) return MMATTN_ERR_UNSUPPORTED;
+    return launch_tile_map(d_bits, S, nullptr, 1, S, tq, tk, d_cls, d_cnt, d_rowpairs,
+                           (hipStream_t)stream);
+}
+
+int mmattn_balance(const uint64_t* d_W, int32_t nB, int32_t P, int32_t* d_rank_of_block,
+                   uint64_t* d_load, int32_t* d_rank_off, int32_t* d_rank_blocks, void* stream) {
+    if (!d_W || !d_rank_of_block || !d_load || !d_rank_off || !d_rank_blocks)
+        return MMATTN_ERR_NULL;
+    if (nB < 1 || P < 1) return MMATTN_ERR_SHAPE;
+    if (nB > MMATTN_MAX_BLOCKS || P > MMATTN_MAX_RANKS) return MMATTN_ERR_UNSUPPORTED;
+    return launch_balance(d_W, nB, P, d_rank_of_block, d_load, d_rank_off, d_rank_blocks,
+                          (hipStream_t)stream);
+}
+
+int mmattn_fwd(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
+               const int32_t* blocks, int32_t n_blocks, int32_t block, int64_t S, int32_t Hq,
+               int32_t Hkv, int32_t D, float scale, int dtype, void* o_loc, float* lse, void* ws,
+               size_t ws_bytes, void* stream) {
+    if (!o_loc || !lse) return MMATTN_ERR_NULL;
+    int rc = check_attn(q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale, dtype);
+    if (rc != MMATTN_OK) return rc;
+    if (!aligned(o_loc, 16) || !aligned(lse, 4)) return MMATTN_ERR_SHAPE;
+    const size_t need = fwd_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D);
+    if (!ws || !aligned(ws, 256) || ws_bytes < need) return MMATTN_ERR_WORKSPACE;
+    AttnArgs a{q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale};
+    return launch_fwd(a, o_loc, lse, ws, (hipStream_t)stream);
+}
+
+int mmattn_bwd(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
+               const int32_t* blocks, int32_t n_blocks, int32_t block, int64_t S, int32_t Hq,
+               int32_t Hkv, int32_t D, float scale, int dtype, const void* o_loc, const float* lse,
+               const void* do_loc, void* dq_loc, void* dk, void* dv, void* ws, size_t ws_bytes,
+               void* stream) {
+    if (!o_loc || !lse || !do_loc || !dq_loc || !dk || !dv) return MMATTN_ERR_NULL;
+    int rc = check_attn(q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale, dtype);
+    if (rc != MMATTN_OK) return rc;
+    if (!aligned(o_loc, 16) || !aligned(do_loc, 16) || !aligned(dq_loc, 16) || !aligned(dk, 16) ||
+        !aligned(dv, 16) || !aligned(lse, 4))
+        return MMATTN_ERR_SHAPE;
+    const size_t need = bwd_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D);
+    if (!ws || !aligned(ws, 256) || ws_bytes < need) return MMATTN_ERR_WORKSPACE;
+    AttnArgs a{q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale};
+    return launch_bwd(a, o_loc, lse, do_loc, dq_loc, dk, dv, ws, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,135 @@
+// mmattn_balance: Alg. 1 of the paper (section 3.2.1) in its LPT reading --
+// blocks visited by (W descending, index ascending), each given to the rank
+// with (load ascending, rank ascending).  Integer-only; one workgroup, because
+// the greedy loop is inherently serial and the inputs are at most a few
+// thousand blocks.
+//
+//   phase 1  every thread ranks its blocks by counting the blocks that precede
+//            them in the visiting order (a total order, so ranks are a
+//            permutation);
+//   phase 2  wavefront 0 runs the greedy loop: lane l keeps the loads of ranks
+//            l, l+64, ... in registers and its own local minimum; a
+//            wave-level lexicographic min picks the receiving rank;
+//   phase 3  per-rank CSR lists in ascending block index by counting, for each
+//            block, the earlier blocks of the same rank.
+#include "common.h"
+
+namespace mm {
+
+constexpr int kBalThreads = 1024;
+constexpr int kBalSlots = MMATTN_MAX_RANKS / kWave;   // ranks per lane
+
+struct MinKey { uint64_t load; uint32_t rank; };
+
+__device__ __forceinline__ bool key_less(const MinKey& a, const MinKey& b) {
+    return a.load < b.load || (a.load == b.load && a.rank < b.rank);
+}
+
+__device__ __forceinline__ MinKey wave_min(MinKey k) {
+    for (int off = 32; off > 0; off >>= 1) {
+        MinKey o;
+        uint32_t lo = __shfl_xor((uint32_t)k.load, off);
+        uint32_t hi = __shfl_xor((uint32_t)(k.load >> 32), off);
+        o.load = ((uint64_t)hi << 32) | lo;
+        o.rank = __shfl_xor(k.rank, off);
+        if (key_less(o, k)) k = o;
+    }
+    return k;
+}
+
+__global__ void __launch_bounds__(kBalThreads)
+balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
+               int32_t* __restrict__ rank_of_block, uint64_t* __restrict__ load,
+               int32_t* __restrict__ rank_off, int32_t* __restrict__ rank_blocks) {
+    __shared__ uint16_t rob[MMATTN_MAX_BLOCKS];
+    __shared__ int32_t count[MMATTN_MAX_RANKS + 1];
+    const int tid = threadIdx.x;
+
+    // phase 1: visiting order, kept in rank_blocks until phase 3 overwrites it
+    int32_t* order = rank_blocks;
+    for (int b = tid; b < nB; b += kBalThreads) {
+        const uint64_t wb = W[b];
+        int pos = 0;
+        for (int c = 0; c < nB; ++c) {
+            const uint64_t wc = W[c];
+            pos += (wc > wb || (wc == wb && c < b)) ? 1 : 0;
+        }
+        order[pos] = b;
+    }
+    for (int g = tid; g <= P; g += kBalThreads) count[g] = 0;
+    __syncthreads();
+
+    // phase 2: greedy assignment by wavefront 0
+    if (tid < kWave) {
+        const int lane = tid;
+        uint64_t mine[kBalSlots];
+#pragma unroll
+        for (int s = 0; s < kBalSlots; ++s) mine[s] = 0;
+        MinKey local;                       // this lane's least-loaded rank
+        local.load = lane < P ? 0 : ~0ull;
+        local.rank = lane < P ? (uint32_t)lane : 0xFFFFFFFFu;
+        for (int t0 = 0; t0 < nB; t0 += kWave) {
+            const int t = t0 + lane;
+            const int32_t my_b = t < nB ? order[t] : 0;
+            const uint64_t my_w = t < nB ? W[my_b] : 0;
+            const int n = min(kWave, nB - t0);
+            for (int u = 0; u < n; ++u) {
+                const int32_t b = __shfl(my_b, u);
+                const uint32_t wlo = __shfl((uint32_t)my_w, u);
+                const uint32_t whi = __shfl((uint32_t)(my_w >> 32), u);
+                const uint64_t w = ((uint64_t)whi << 32) | wlo;
+                const MinKey best = wave_min(local);
+                const uint32_t g = best.rank;
+                if ((int)(g & (kWave - 1)) == lane) {
+                    const int slot = g / kWave;
+#pragma unroll
+                    for (int s = 0; s < kBalSlots; ++s)
+                        if (s == slot) mine[s] += w;
+                    // recompute the lane's local minimum over its ranks
+                    local.load = ~0ull;
+                    local.rank = 0xFFFFFFFFu;
+#pragma unroll
+                    for (int s = 0; s < kBalSlots; ++s) {
+                        const uint32_t r = (uint32_t)(lane + s * kWave);
+                        if ((int)r < P) {
+                            MinKey cand{mine[s], r};
+                            if (key_less(cand, local)) local = cand;
+                        }
+                    }
+                    rank_of_block[b] = (int32_t)g;
+                    rob[b] = (uint16_t)g;
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < kBalSlots; ++s) {
+            const int r = lane + s * kWave;
+            if (r < P) load[r] = mine[s];
+        }
+    }
+    __syncthreads();
+
+    // phase 3: CSR lists, ascending block index inside each rank
+    for (int b = tid; b < nB; b += kBalThreads) atomicAdd(&count[rob[b] + 1], 1);
+    __syncthreads();
+    if (tid == 0)
+        for (int g = 0; g < P; ++g) count[g + 1] += count[g];
+    __syncthreads();
+    for (int g = tid; g <= P; g += kBalThreads) rank_off[g] = count[g];
+    for (int b = tid; b < nB; b += kBalThreads) {
+        const uint16_t g = rob[b];
+        int before = 0;
+        for (int c = 0; c < b; ++c) before += rob[c] == g ? 1 : 0;
+        rank_blocks[count[g] + before] = b;
+    }
+}
+
+int launch_balance(const uint64_t* d_W, int32_t nB, int32_t P, int32_t* d_rank_of_block,
+                   uint64_t* d_load, int32_t* d_rank_off, int32_t* d_rank_blocks, hipStream_t st) {
+    hipLaunchKernelGGL(balance_kernel, dim3(1), dim3(kBalThreads), 0, st, d_W, nB, P,
+                       d_rank_of_block, d_load, d_rank_off, d_rank_blocks);
+    MM_LAUNCH_CHECK();
+    return MMATTN_OK;
+}
+
+}  // namespace mm

@@ -1,0 +1,76 @@
+// Internal helpers shared by the HIP translation units of libmmattn.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "mmattn.h"
+
+#define MM_HIP_TRY(expr)                                        \
+    do {                                                        \
+        hipError_t e_ = (expr);                                 \
+        if (e_ != hipSuccess) return MMATTN_ERR_HIP;            \
+    } while (0)
+
+#define MM_LAUNCH_CHECK()                                       \
+    do {                                                        \
+        if (hipGetLastError() != hipSuccess) return MMATTN_ERR_HIP; \
+    } while (0)
+
+namespace mm {
+
+constexpr int kWave = 64;
+
+// Mask word fields (paper section 4.2 layout as fixed in mmattn.h).
+constexpr int kSpanShift = 12;
+constexpr int kSampleShift = 28;
+constexpr int kCausalBit = 63;
+
+// Compact 33-bit view used by the kernels: low 16 bits span id, next 16 bits
+// sample id, plus the causal flag.  Equal `ss` words mean same sample AND
+// same span.
+__host__ __device__ inline uint32_t word_ss(uint64_t w) { return (uint32_t)(w >> kSpanShift); }
+__host__ __device__ inline uint32_t word_causal(uint64_t w) { return (uint32_t)(w >> kCausalBit); }
+
+// vis(q,k) = same_sample && ((causal(q) && k<=q) || (span(q)!=0 && span(q)==span(k)))
+__device__ __forceinline__ bool visible(uint32_t ss_q, uint32_t causal_q, int64_t q,
+                                        uint32_t ss_k, int64_t k) {
+    bool same_sample = (ss_q >> 16) == (ss_k >> 16);
+    bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_k;
+    return same_span || (same_sample && causal_q && k <= q);
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Global token position of local row r of a rank share (blocks == nullptr:
+// identity, the whole sequence).
+__device__ __forceinline__ int64_t row_pos(const int32_t* blocks, int32_t block, int64_t r) {
+    if (!blocks) return r;
+    int64_t b = r / block;
+    return (int64_t)blocks[b] * block + (r - b * block);
+}
+
+// ---- entry points implemented per translation unit (host side) -------------
+int launch_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* sample_off,
+                  int32_t n_samples, int64_t S, uint64_t* d_bits, void* ws, hipStream_t st);
+int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
+                    int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls, uint32_t* d_cnt,
+                    uint64_t* d_rowpairs, hipStream_t st);
+int launch_balance(const uint64_t* d_W, int32_t nB, int32_t P, int32_t* d_rank_of_block,
+                   uint64_t* d_load, int32_t* d_rank_off, int32_t* d_rank_blocks, hipStream_t st);
+
+struct AttnArgs {
+    const void *q, *k, *v;
+    const uint64_t* bits;
+    const int32_t* blocks;
+    int32_t n_blocks, block;
+    int64_t S;
+    int32_t Hq, Hkv, D;
+    float scale;
+};
+size_t fwd_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t D);
+size_t bwd_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t D);
+int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st);
+int launch_bwd(const AttnArgs& a, const void* o, const float* lse, const void* d_o,
+               void* dq, void* dk, void* dv, void* ws, hipStream_t st);
+
+}  // namespace mm

@@ -1,0 +1,57 @@
+// mmattn_mask_encode: per-token 64-bit mask words from a span list and packed
+// sample offsets (paper section 4.2, bitfield attention mask; App. C packing).
+// One thread per token; binary search over the (sorted) sample offsets and
+// span starts that were staged into the workspace.
+#include "common.h"
+
+namespace mm {
+
+struct DevSpan { int64_t start, len; int32_t modality, flags; };
+static_assert(sizeof(DevSpan) == sizeof(mmattn_span), "span layout");
+
+__global__ void __launch_bounds__(256)
+encode_kernel(const DevSpan* __restrict__ spans, int32_t n_spans,
+              const int64_t* __restrict__ sample_off, int32_t n_samples,
+              int64_t S, uint64_t* __restrict__ bits) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= S) return;
+    // sample = last i with sample_off[i] <= t
+    int lo = 0, hi = n_samples;              // invariant: off[lo] <= t < off[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (sample_off[mid] <= t) lo = mid; else hi = mid;
+    }
+    uint64_t w = 0xFFull | ((uint64_t)lo << kSampleShift);
+    uint64_t causal = 1;
+    // span = last j with start <= t, if t also lies before its end
+    int a = -1, b = n_spans;                 // start[a] <= t < start[b]
+    while (b - a > 1) {
+        int mid = (a + b) >> 1;
+        if (spans[mid].start <= t) a = mid; else b = mid;
+    }
+    if (a >= 0 && t < spans[a].start + spans[a].len) {
+        w |= (uint64_t)(a + 1) << kSpanShift;
+        w |= (uint64_t)(spans[a].modality & 0xF) << 8;
+        if (spans[a].flags & MMATTN_SPAN_NONCAUSAL) causal = 0;
+    }
+    bits[t] = w | (causal << kCausalBit);
+}
+
+int launch_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* sample_off,
+                  int32_t n_samples, int64_t S, uint64_t* d_bits, void* ws, hipStream_t st) {
+    char* base = (char*)ws;
+    DevSpan* d_spans = (DevSpan*)base;
+    int64_t* d_off = (int64_t*)(base + align_up((size_t)n_spans * sizeof(DevSpan), 256));
+    if (n_spans > 0)
+        MM_HIP_TRY(hipMemcpyAsync(d_spans, spans, (size_t)n_spans * sizeof(DevSpan),
+                                  hipMemcpyHostToDevice, st));
+    MM_HIP_TRY(hipMemcpyAsync(d_off, sample_off, (size_t)(n_samples + 1) * sizeof(int64_t),
+                              hipMemcpyHostToDevice, st));
+    unsigned grid = (unsigned)((S + 255) / 256);
+    hipLaunchKernelGGL(encode_kernel, dim3(grid), dim3(256), 0, st, d_spans, n_spans, d_off,
+                       n_samples, S, d_bits);
+    MM_LAUNCH_CHECK();
+    return MMATTN_OK;
+}
+
+}  // namespace mm

@@ -1,0 +1,105 @@
+"""GPU parity, integer stages: mask encode, tile map, balancer -- bit-exact
+against the oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import balance as ob
+from oracle import tilemap as ot
+from paper_2503_11367_amd import binding as mb
+from paper_2503_11367_amd import workloads as wl
+
+from gpu_util import DEV, fields, gpu_bits, oracle_bits, to_np_u64
+
+pytestmark = pytest.mark.gpu
+
+
+def layouts_small():
+    out = [wl.layout_tiny(), wl.Layout(256, [], [0, 256]), wl.Layout(256, [(0, 256, 1)], [0, 256])]
+    for seed in range(6):
+        out.append(wl.layout_random(seed, S=1024, n_samples=1 + seed % 4, noncausal_prob=0.3))
+    out.append(wl.layout_packed(seed=3, S=4096, n_samples=6, span_lo=30, span_hi=400))
+    return out
+
+
+@pytest.mark.parametrize("idx", range(10))
+def test_encode_small(idx):
+    lay = layouts_small()[idx]
+    assert np.array_equal(to_np_u64(gpu_bits(lay)), oracle_bits(lay))
+
+
+@pytest.mark.parametrize("c", [1, 2, 3, 4, 5])
+def test_encode_workloads(c):
+    lay = wl.workload(c).layout
+    assert np.array_equal(to_np_u64(gpu_bits(lay)), oracle_bits(lay))
+
+
+def check_tile_map(lay, tq, tk, use_c):
+    f = fields(lay)
+    bits = torch.from_numpy(oracle_bits(lay).view(np.int64)).to(DEV)      # oracle-encoded input
+    cls, cnt, rp = mb.tile_map(bits, tq, tk)
+    ref = (ot.tile_map_c if use_c else ot.tile_map)(f[0], f[1], f[2], tq, tk)
+    assert np.array_equal(cls.cpu().numpy(), ref[0])
+    assert np.array_equal(cnt.cpu().numpy().view(np.uint32), ref[1])
+    assert np.array_equal(rp.cpu().numpy().view(np.uint64), ref[2])
+
+
+@pytest.mark.parametrize("idx", range(10))
+@pytest.mark.parametrize("tile", [(64, 64), (128, 64), (16, 256), (256, 32)])
+def test_tile_map_small(idx, tile):
+    lay = layouts_small()[idx]
+    if lay.S % tile[0] or lay.S % tile[1]:
+        pytest.skip("tile does not divide S")
+    check_tile_map(lay, tile[0], tile[1], use_c=False)
+
+
+@pytest.mark.parametrize("c", [1, 2, 3, 4, 5])
+def test_tile_map_workloads(c):
+    w = wl.workload(c)
+    check_tile_map(w.layout, w.N_B, w.N_B, use_c=True)
+    if c in (2, 3):
+        check_tile_map(w.layout, 128, 64, use_c=True)
+
+
+def check_balance(W, P):
+    Wt = torch.from_numpy(np.asarray(W, dtype=np.uint64).view(np.int64)).to(DEV)
+    rob, load, off, blocks = mb.balance(Wt, P)
+    ref = ob.lpt(W, P)
+    assert np.array_equal(rob.cpu().numpy(), ref[0])
+    assert np.array_equal(load.cpu().numpy().view(np.uint64), ref[1])
+    assert np.array_equal(off.cpu().numpy(), ref[2])
+    assert np.array_equal(blocks.cpu().numpy(), ref[3])
+
+
+def test_balance_paper_example_and_edges():
+    check_balance([1, 2, 2, 4, 5, 2, 2, 8], 4)
+    check_balance([7], 1)
+    check_balance([7], 5)                     # more ranks than blocks
+    check_balance([0, 0, 0, 0], 2)            # all-zero workloads
+    check_balance([5] * 12, 4)                # all ties
+    check_balance([2 ** 63, 2 ** 62, 2 ** 62, 1], 2)     # needs full 64-bit loads
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_balance_random(seed):
+    rng = np.random.default_rng(seed)
+    nB = int(rng.integers(1, 2500))
+    P = int(rng.choice([1, 2, 3, 8, 63, 64, 65, 200, 1024]))
+    hi = int(rng.choice([4, 1000, 2 ** 40]))
+    check_balance(rng.integers(0, hi, size=nB).tolist(), P)
+
+
+@pytest.mark.parametrize("c", [1, 2, 3, 4, 5])
+def test_balance_workloads_end_to_end(c):
+    """encode -> tile map -> balance, all on the GPU, against the oracle chain."""
+    w = wl.workload(c)
+    f = fields(w.layout)
+    bits = gpu_bits(w.layout)
+    _, _, rp = mb.tile_map(bits, w.N_B, w.N_B)
+    rob, load, off, blocks = mb.balance(rp, w.P)
+    _, _, Wref = ot.tile_map_c(f[0], f[1], f[2], w.N_B, w.N_B)
+    ref = ob.lpt(Wref, w.P)
+    assert np.array_equal(rob.cpu().numpy(), ref[0])
+    assert np.array_equal(load.cpu().numpy().view(np.uint64), ref[1])
+    assert np.array_equal(blocks.cpu().numpy(), ref[3])
+    assert int(load.sum().item()) == int(Wref.sum())
