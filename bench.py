@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+One "step" = mask encode -> tile map -> balance -> (P-element readback to pick
+the rank) -> attention forward -> attention backward for that rank's query
+blocks, on synthetic inputs already resident in HBM.  The default workload is
+the vision-LLM configuration (S=8192, four 1024-token image spans among causal
+text, 32 Q / 8 KV heads, head_dim 128, bf16, all 64 blocks on one rank).
+
+Prints ONE JSON line: effective TFLOP/s on unmasked (query,key) pairs
+(fwd 4*D*Hq*pairs + bwd 10*D*Hq*pairs flops per step), a roofline object for the
+dominant kernel (timed live with HIP events recorded around that kernel on its
+stream) and the float64 CPU oracle timed on a bounded sample of the same
+workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published figure
+
+
+def build_inputs(w, device):
+    import torch
+    from paper_2503_11367_amd import binding as mb
+    from paper_2503_11367_amd import workloads as wl
+    lay = w.layout
+    S = lay.S
+    host = {"k": wl.normal_bf16(w.tensor_seed * 10 + 1, (S, w.Hkv, w.D)),
+            "v": wl.normal_bf16(w.tensor_seed * 10 + 2, (S, w.Hkv, w.D))}
+    dev = {k: mb.bf16_from_bits(v, device) for k, v in host.items()}
+    return host, dev
+
+
+def plan_on_gpu(w, device):
+    """encode -> tile map -> balance; returns device tensors + host copies of
+    the per-rank loads/offsets (the one readback on the path)."""
+    from paper_2503_11367_amd import binding as mb
+    lay = w.layout
+    bits = mb.mask_encode(lay.spans, lay.sample_off, lay.S, device=device, flags=lay.noncausal)
+    _, _, W = mb.tile_map(bits, w.N_B, w.N_B, want_cls=False)
+    rob, load, off, rblocks = mb.balance(W, w.P)
+    load_h = load.cpu().numpy().view(np.uint64)
+    off_h = off.cpu().numpy()
+    return bits, W, rblocks, load_h, off_h
+
+
+def imbalance_report(device):
+    """max/mean load over virtual ranks for the balanced workloads: LPT (GPU)
+    next to the zigzag and contiguous splits of the same block workloads."""
+    from paper_2503_11367_amd import workloads as wl
+    out = {}
+    for c in (1, 3, 4, 5):
+        w = wl.workload(c)
+        _, W, _, load_h, _ = plan_on_gpu(w, device)
+        Wh = W.cpu().numpy().view(np.uint64).astype(np.float64)
+        nB, P = Wh.size, w.P
+        entry = {"P": P, "lpt": float(load_h.max() * P / load_h.sum())}
+        if nB % (2 * P) == 0:
+            ch = Wh.reshape(2 * P, -1).sum(axis=1)
+            zz = ch[:P] + ch[::-1][:P]
+            entry["zigzag"] = float(zz.max() * P / zz.sum())
+        if nB % P == 0:
+            ct = Wh.reshape(P, -1).sum(axis=1)
+            entry["contiguous"] = float(ct.max() * P / ct.sum())
+        out[w.name] = entry
+    return out
+
+
+def cpu_baseline(w, blocks, host_q, host_k, host_v, host_do, n_heads, pairs):
+    """Time the float64 oracle (forward + backward) on the Q heads of one KV
+    group, all rows of the share."""
+    from oracle import attention as oa
+    from oracle import mask as om
+    from paper_2503_11367_amd import workloads as wl
+    lay = w.layout
+    f = om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal)
+    rows = oa.rows_of_blocks(blocks, w.N_B)
+    cvt = lambda b: wl.bf16_bits_to_f32(b).astype(np.float64)
+    Q, dO = cvt(host_q[:, :n_heads]), cvt(host_do[:, :n_heads])
+    K, V = cvt(host_k[:, :1]), cvt(host_v[:, :1])
+    t0 = time.perf_counter()
+    oa.forward(Q, K, V, rows, f[0], f[1], f[2])
+    oa.backward(Q, K, V, dO, rows, f[0], f[1], f[2])
+    dt = time.perf_counter() - t0
+    flops = 14.0 * w.D * n_heads * pairs
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": len(os.sched_getaffinity(0)),
+            "kind": "oracle", "seconds": dt,
+            "sample": f"float64 oracle fwd+bwd, all {len(rows)} rows of the share, "
+                      f"{n_heads} of {w.Hq} Q heads (one KV group)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2, the metric's config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path "
+              "(run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2503_11367_amd import binding as mb
+    from paper_2503_11367_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    device = torch.device("cuda:0")
+    torch.cuda.set_device(device)
+    mb.lib()
+
+    w = wl.workload(args.workload)
+    lay = w.layout
+    S = lay.S
+    host, dev = build_inputs(w, device)
+
+    # plan once up front to size the share-dependent inputs (Q_loc, dO_loc)
+    bits, W, rblocks, load_h, off_h = plan_on_gpu(w, device)
+    g = int(np.argmax(load_h))                 # heaviest rank (lowest id on ties)
+    nb = int(off_h[g + 1] - off_h[g])
+    n_loc = nb * w.N_B
+    pairs = int(load_h[g])
+    host["q"] = wl.normal_bf16(w.tensor_seed * 10 + 0, (n_loc, w.Hq, w.D))
+    host["do"] = wl.normal_bf16(w.tensor_seed * 10 + 3, (n_loc, w.Hq, w.D))
+    dev["q"] = mb.bf16_from_bits(host["q"], device)
+    dev["do"] = mb.bf16_from_bits(host["do"], device)
+
+    o = torch.empty_like(dev["q"])
+    lse = torch.empty((w.Hq, n_loc), dtype=torch.float32, device=device)
+    dq = torch.empty_like(dev["q"])
+    dk = torch.empty_like(dev["k"])
+    dv = torch.empty_like(dev["v"])
+    ws_f = torch.empty(mb.workspace_size(mb.OP_FWD, S, nb, w.N_B, w.Hq, w.Hkv, w.D),
+                       dtype=torch.uint8, device=device)
+    ws_b = torch.empty(mb.workspace_size(mb.OP_BWD, S, nb, w.N_B, w.Hq, w.Hkv, w.D),
+                       dtype=torch.uint8, device=device)
+
+    def step():
+        bits_, _, rblocks_, load_, off_ = plan_on_gpu(w, device)
+        g_ = int(np.argmax(load_))
+        bl = rblocks_[int(off_[g_]):int(off_[g_ + 1])]
+        mb.fwd(dev["q"], dev["k"], dev["v"], bits_, bl, w.N_B, ws=ws_f, out=(o, lse))
+        mb.bwd(dev["q"], dev["k"], dev["v"], bits_, bl, w.N_B, o, lse, dev["do"], ws=ws_b,
+               out=(dq, dk, dv))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # HIP events recorded by the library around each main kernel, one pair per step
+    stages = {"fwd": mb.STAGE_FWD, "dkv": mb.STAGE_DKV, "dq": mb.STAGE_DQ}
+    evs = {n: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.steps)] for n in stages}
+    for n in stages:
+        for a, b in evs[n]:
+            a.record(); b.record()             # materialise the handles
+    torch.cuda.synchronize()
+
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        for n, sid in stages.items():
+            mb.stage_events(sid, evs[n][i][0].cuda_event, evs[n][i][1].cuda_event)
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for sid in stages.values():
+        mb.stage_events(sid, 0, 0)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = {n: float(np.mean([a.elapsed_time(b) for a, b in evs[n]])) for n in stages}
+    flops_fwd = 4.0 * w.D * w.Hq * pairs
+    flops_bwd = 10.0 * w.D * w.Hq * pairs
+    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel and its algorithmic flops: dkv runs S, dP, dV, dK (8*D*Hq*pairs),
+    # dq's own product is dQ (2*D*Hq*pairs), fwd runs S and PV (4*D*Hq*pairs)
+    alg = {"fwd": flops_fwd, "dkv": 8.0 * w.D * w.Hq * pairs, "dq": 2.0 * w.D * w.Hq * pairs}
+    kname = {"fwd": "fwd_kernel", "dkv": "dkv_kernel", "dq": "dq_kernel"}
+    dom = max(kern_ms, key=kern_ms.get)
+    achieved = alg[dom] / (kern_ms[dom] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": kname[dom], "achieved": achieved,
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                "traffic": None, "avg_ms": kern_ms[dom]}
+
+    out = {
+        "metric": "masked-attention effective TFLOP/s (unmasked pairs) fwd+bwd",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "S": S, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "N_B": w.N_B,
+                   "P": w.P, "rank": g, "n_loc": n_loc, "pairs": pairs},
+        "roofline": roofline,
+        "kernels_ms": kern_ms,
+        "tflops": {"fwd": flops_fwd / (kern_ms["fwd"] * 1e-3) / 1e12,
+                   "bwd": flops_bwd / ((kern_ms["dkv"] + kern_ms["dq"]) * 1e-3) / 1e12},
+        "frac_of_peak": {"fwd": flops_fwd / (kern_ms["fwd"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                         "bwd": flops_bwd / ((kern_ms["dkv"] + kern_ms["dq"]) * 1e-3) / 1e12
+                         / PEAK_BF16_TFLOPS},
+    }
+
+    # planning time (encode + tile map + balance + readback), outside the timed region
+    torch.cuda.synchronize()
+    tp0 = time.perf_counter()
+    for _ in range(10):
+        plan_on_gpu(w, device)
+    torch.cuda.synchronize()
+    out["planning_us"] = (time.perf_counter() - tp0) / 10 * 1e6
+    out["imbalance"] = imbalance_report(device)
+
+    if not args.no_cpu_baseline:
+        blocks = rblocks[int(off_h[g]):int(off_h[g + 1])].cpu().numpy()
+        rep = w.Hq // w.Hkv
+        out["cpu_baseline"] = cpu_baseline(w, blocks, host["q"], host["k"], host["v"], host["do"],
+                                           rep, pairs)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.mmattn_bwd.restype = ctypes.c_int
         L.mmattn_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
                                  ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+        L.mmattn_stage_events.restype = ctypes.c_int
+        L.mmattn_stage_events.argtypes = [ctypes.c_int, _vp, _vp]
         _lib = L
     return _lib
 
@@ -183,6 +185,14 @@ def bwd(q_loc, k, v, bits, blocks, block: int, o_loc, lse, do_loc, scale: Option
                           _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(), _stream(stream))
     _check("mmattn_bwd", rc)
     return dq, dk, dv
+
+
+STAGE_FWD, STAGE_DKV, STAGE_DQ = 0, 1, 2
+
+
+def stage_events(stage: int, ev_start: int, ev_stop: int):
+    """mmattn_stage_events: raw hipEvent_t handles (0, 0 clears)."""
+    _check("mmattn_stage_events", lib().mmattn_stage_events(stage, ev_start, ev_stop))
 
 
 def bf16_from_bits(bits_u16: np.ndarray, device="cuda") -> torch.Tensor:

@@ -28,7 +28,16 @@ int check_attn(const void* q, const void* k, const void* v, const uint64_t* bits
 
 }  // namespace
 
+namespace mm { StageEvents g_stage_events[MMATTN_STAGE_COUNT] = {}; }
+
 extern "C" {
+
+int mmattn_stage_events(int stage, void* ev_start, void* ev_stop) {
+    if (stage < 0 || stage >= MMATTN_STAGE_COUNT) return MMATTN_ERR_SHAPE;
+    g_stage_events[stage].start = (hipEvent_t)ev_start;
+    g_stage_events[stage].stop = (hipEvent_t)ev_stop;
+    return MMATTN_OK;
+}
 
 const char* mmattn_version(void) { return "mmattn 0.1 (gfx950)"; }
 

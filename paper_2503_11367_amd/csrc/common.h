@@ -58,6 +58,16 @@ int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, 
 int launch_balance(const uint64_t* d_W, int32_t nB, int32_t P, int32_t* d_rank_of_block,
                    uint64_t* d_load, int32_t* d_rank_off, int32_t* d_rank_blocks, hipStream_t st);
 
+// optional per-stage event pairs (measurement aid, see mmattn_stage_events)
+struct StageEvents { hipEvent_t start, stop; };
+extern StageEvents g_stage_events[MMATTN_STAGE_COUNT];
+inline void stage_begin(int stage, hipStream_t st) {
+    if (g_stage_events[stage].start) (void)hipEventRecord(g_stage_events[stage].start, st);
+}
+inline void stage_end(int stage, hipStream_t st) {
+    if (g_stage_events[stage].stop) (void)hipEventRecord(g_stage_events[stage].stop, st);
+}
+
 struct AttnArgs {
     const void *q, *k, *v;
     const uint64_t* bits;

@@ -83,10 +83,10 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         const ushort_t* qp = Q + (row * Hq + h) * (int64_t)D + hh * 8;
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds)
-            qf[ds] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + ds * 16));
+            qf[ds] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qp + ds * 16));
     } else {
 #pragma unroll
-        for (int ds = 0; ds < NDS; ++ds) qf[ds] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+        for (int ds = 0; ds < NDS; ++ds) qf[ds] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
     }
 
     floatx16 o[NDB];
@@ -99,7 +99,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // ---- global -> register staging of one K/V tile -----------------------------
     constexpr int CH = D / 8;                          // 16-byte chunks per row
     constexpr int NLD = kFwdBN * CH / kFwdThreads;     // chunks per thread per tensor
-    uint4 kreg[NLD], vreg[NLD];
+    u32x4 kreg[NLD], vreg[NLD];
     uint32_t kssreg = 0;
     auto load_tile = [&](int it) {
         const int64_t k0 = (int64_t)(klist[it] & ~kPartialFlag) * kFwdBN;
@@ -107,8 +107,8 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         for (int i = 0; i < NLD; ++i) {
             const int c = tid + i * kFwdThreads, r = c / CH, cc = c % CH;
             const int64_t off = ((k0 + r) * Hkv + g) * (int64_t)D + cc * 8;
-            kreg[i] = *(const uint4*)(K + off);
-            vreg[i] = *(const uint4*)(V + off);
+            kreg[i] = *(const u32x4*)(K + off);
+            vreg[i] = *(const u32x4*)(V + off);
         }
         if (tid < kFwdBN) kssreg = word_ss(bits[k0 + tid]);
     };
@@ -116,8 +116,8 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int c = tid + i * kFwdThreads, r = c / CH, cc = c % CH;
-            *(uint4*)(sm.k + r * KP + cc * 8) = kreg[i];
-            *(uint4*)(sm.v + r * VP + cc * 8) = vreg[i];
+            *(u32x4*)(sm.k + r * KP + cc * 8) = kreg[i];
+            *(u32x4*)(sm.v + r * VP + cc * 8) = vreg[i];
         }
         if (tid < kFwdBN) sm.kss[tid] = kssreg;
     };
@@ -148,7 +148,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
             for (int ds = 0; ds < NDS; ++ds) {
                 const bf16x8 a = __builtin_bit_cast(
-                    bf16x8, *(const uint4*)(sm.k + kb * 32 * KP + k_off + ds * 16));
+                    bf16x8, *(const u32x4*)(sm.k + kb * 32 * KP + k_off + ds * 16));
                 s[kb] = mfma32(a, qf[ds], s[kb]);
             }
         }
@@ -217,7 +217,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
                 bf16x4 out;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) out[u] = (__bf16)(o[db][c * 4 + u] * inv);
-                *(uint2*)(op + db * 32 + c * 8) = __builtin_bit_cast(uint2, out);
+                *(u32x2*)(op + db * 32 + c * 8) = __builtin_bit_cast(u32x2, out);
             }
         if (hh == 0)
             LSE[(int64_t)h * n_loc + row] =
@@ -275,6 +275,7 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
 
     const float scale_log2 = a.scale * kLog2e;
     const unsigned grid = (unsigned)((int64_t)L.nq * a.Hq);
+    stage_begin(MMATTN_STAGE_FWD, st);
     if (a.D == 128)
         hipLaunchKernelGGL(fwd_kernel<128>, dim3(grid), dim3(kFwdThreads), 0, st,
                            (const ushort_t*)a.q, (const ushort_t*)a.k, (const ushort_t*)a.v, a.bits,
@@ -285,6 +286,7 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
                            (const ushort_t*)a.q, (const ushort_t*)a.k, (const ushort_t*)a.v, a.bits,
                            clean, a.block, n_loc, a.S, a.Hq, a.Hkv, scale_log2, plan, err,
                            (ushort_t*)o, lse);
+    stage_end(MMATTN_STAGE_FWD, st);
     MM_LAUNCH_CHECK();
     return MMATTN_OK;
 }

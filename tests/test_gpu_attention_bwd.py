@@ -1,0 +1,170 @@
+"""GPU parity, attention backward (through the C ABI) against the float64
+oracle: relative L2 error below 1e-2 on dQ, dK, dV (bf16 in/out, fp32
+accumulation).  The GPU backward consumes the GPU forward's O and LSE, as in
+training; the oracle recomputes its own forward in float64."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from oracle import balance as ob
+from oracle import tilemap as ot
+from paper_2503_11367_amd import binding as mb
+from paper_2503_11367_amd import workloads as wl
+
+from gpu_util import (DEV, bf16_to_f64, f64, fields, gpu_bits, make_tensors, max_abs, rel_l2)
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2
+
+
+def gpu_fwd_bwd(lay, blocks, block, t):
+    bits = gpu_bits(lay)
+    bl = torch.tensor(blocks, dtype=torch.int32, device=DEV)
+    o, lse = mb.fwd(t["q"], t["k"], t["v"], bits, bl, block)
+    dq, dk, dv = mb.bwd(t["q"], t["k"], t["v"], bits, bl, block, o, lse, t["do"])
+    torch.cuda.synchronize()
+    return o, lse, dq, dk, dv
+
+
+def run_case(lay, blocks, block, Hq, Hkv, D, seed):
+    f = fields(lay)
+    n_loc = len(blocks) * block
+    t = make_tensors(seed, n_loc, lay.S, Hq, Hkv, D)
+    o, lse, dq, dk, dv = gpu_fwd_bwd(lay, blocks, block, t)
+    rows = oa.rows_of_blocks(blocks, block)
+    Q, K, V, dO = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"]), f64(t["do_bits"])
+    dq_ref, dk_ref, dv_ref = oa.backward(Q, K, V, dO, rows, f[0], f[1], f[2])
+    for name, got, ref in (("dq", dq, dq_ref), ("dk", dk, dk_ref), ("dv", dv, dv_ref)):
+        g = bf16_to_f64(got)
+        assert np.isfinite(g).all(), name
+        assert rel_l2(g, ref) < TOL, (name, rel_l2(g, ref))
+    # keys that no row of the share sees get exactly zero
+    from oracle import mask as om
+    seen = om.visible(rows, np.arange(lay.S), f[0], f[1], f[2]).any(axis=0)
+    assert (bf16_to_f64(dk)[~seen] == 0).all() and (bf16_to_f64(dv)[~seen] == 0).all()
+
+
+def test_tiny_every_rank_share():
+    w = wl.workload(1)
+    f = fields(w.layout)
+    _, _, W = ot.tile_map(f[0], f[1], f[2], w.N_B, w.N_B)
+    _, _, off, rb = ob.lpt(W, w.P)
+    for g in range(w.P):
+        run_case(w.layout, rb[off[g]:off[g + 1]].tolist(), w.N_B, w.Hq, w.Hkv, w.D, seed=11 + g)
+    run_case(w.layout, list(range(8)), w.N_B, w.Hq, w.Hkv, w.D, seed=10)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("seed", range(4))
+def test_random_layouts(seed, D):
+    lay = wl.layout_random(40 + seed, S=1024, n_samples=1 + seed % 3, noncausal_prob=0.25 * (seed % 2))
+    block = [16, 32, 64, 128][seed % 4]
+    rng = np.random.default_rng(seed)
+    nb = lay.S // block
+    take = int(rng.integers(1, nb + 1))
+    blocks = np.sort(rng.choice(nb, size=take, replace=False)).tolist()
+    run_case(lay, blocks, block, Hq=4, Hkv=2, D=D, seed=20 + seed)
+
+
+def test_special_masks():
+    run_case(wl.Layout(512, [], [0, 512]), list(range(4)), 128, 2, 1, 128, seed=41)
+    run_case(wl.Layout(512, [(0, 512, 1)], [0, 512]), list(range(4)), 128, 2, 1, 128, seed=42)
+    run_case(wl.Layout(768, [(300, 100, 2)], [0, 200, 768]), [4, 1, 5], 128, 2, 2, 64, seed=43)
+
+
+def test_rank_partials_sum_to_full():
+    """Summing the ranks' partial dK/dV reproduces the single-rank result."""
+    w = wl.workload(1)
+    lay = w.layout
+    f = fields(lay)
+    t = make_tensors(77, lay.S, lay.S, 2, 1, 64)
+    _, _, dq_full, dk_full, dv_full = gpu_fwd_bwd(lay, list(range(8)), 64, t)
+    _, _, W = ot.tile_map(f[0], f[1], f[2], 64, 64)
+    _, _, off, rb = ob.lpt(W, 4)
+    dk_sum = np.zeros((lay.S, 1, 64))
+    dv_sum = np.zeros((lay.S, 1, 64))
+    for g in range(4):
+        blocks = rb[off[g]:off[g + 1]].tolist()
+        rows = oa.rows_of_blocks(blocks, 64)
+        tt = dict(t)
+        tt["q"] = t["q"][torch.from_numpy(rows).to(DEV)].contiguous()
+        tt["do"] = t["do"][torch.from_numpy(rows).to(DEV)].contiguous()
+        _, _, dq, dk, dv = gpu_fwd_bwd(lay, blocks, 64, tt)
+        assert rel_l2(bf16_to_f64(dq), bf16_to_f64(dq_full)[rows]) < 2e-3
+        dk_sum += bf16_to_f64(dk)
+        dv_sum += bf16_to_f64(dv)
+    assert rel_l2(dk_sum, bf16_to_f64(dk_full)) < 1e-2
+    assert rel_l2(dv_sum, bf16_to_f64(dv_full)) < 1e-2
+
+
+def group_check(w, blocks, t, outs, g, sel_rows=None):
+    """Oracle backward for the Q heads of KV group g on the whole share."""
+    f = fields(w.layout)
+    rep = w.Hq // w.Hkv
+    hs = slice(g * rep, (g + 1) * rep)
+    rows = oa.rows_of_blocks(blocks, w.N_B)
+    Q, K, V, dO = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"]), f64(t["do_bits"])
+    dq_ref, dk_ref, dv_ref = oa.backward(Q[:, hs], K[:, g:g + 1], V[:, g:g + 1], dO[:, hs], rows,
+                                         f[0], f[1], f[2])
+    _, _, dq, dk, dv = outs
+    assert rel_l2(bf16_to_f64(dq[:, hs]), dq_ref) < TOL
+    assert rel_l2(bf16_to_f64(dk[:, g:g + 1]), dk_ref) < TOL
+    assert rel_l2(bf16_to_f64(dv[:, g:g + 1]), dv_ref) < TOL
+
+
+def sampled_dq_and_dv_sums(w, blocks, t, outs, n_rows=24, heads=(0, 5)):
+    """Size-independent checks: dQ of sampled rows (each row needs only its own
+    softmax), and sum_k dV[k,g] = sum over the group's heads and rows of dO."""
+    f = fields(w.layout)
+    rep = w.Hq // w.Hkv
+    n_loc = len(blocks) * w.N_B
+    rows = oa.rows_of_blocks(blocks, w.N_B)
+    _, _, dq, dk, dv = outs
+    Q, K, V, dO = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"]), f64(t["do_bits"])
+    sel = np.sort(np.random.default_rng(1).choice(n_loc, size=n_rows, replace=False))
+    for h in heads:
+        g = h // rep
+        dq_ref, _, _ = oa.backward(Q[sel][:, h:h + 1], K[:, g:g + 1], V[:, g:g + 1],
+                                   dO[sel][:, h:h + 1], rows[sel], f[0], f[1], f[2])
+        assert rel_l2(bf16_to_f64(dq[torch.from_numpy(sel).to(DEV)][:, h:h + 1]), dq_ref) < TOL
+    dv_sum = dv.float().sum(dim=0).cpu().numpy().astype(np.float64)
+    ref = dO.reshape(n_loc, w.Hkv, rep, w.D).sum(axis=(0, 2))
+    assert np.abs(dv_sum - ref).max() < 2e-2 * np.abs(ref).max() + 0.5
+
+
+def test_workload2_full_sequence():
+    w = wl.workload(2)
+    blocks = list(range(w.layout.S // w.N_B))
+    t = make_tensors(w.tensor_seed, w.layout.S, w.layout.S, w.Hq, w.Hkv, w.D)
+    outs = gpu_fwd_bwd(w.layout, blocks, w.N_B, t)
+    group_check(w, blocks, t, outs, g=5)
+    sampled_dq_and_dv_sums(w, blocks, t, outs, heads=(0, 13, 31))
+
+
+@pytest.mark.parametrize("c", [3, 5])
+def test_workload_heaviest_rank_one_group(c):
+    w = wl.workload(c)
+    f = fields(w.layout)
+    _, _, W = ot.tile_map_c(f[0], f[1], f[2], w.N_B, w.N_B)
+    _, load, off, rb = ob.lpt(W, w.P)
+    g = int(np.argmax(load))
+    blocks = rb[off[g]:off[g + 1]].tolist()
+    t = make_tensors(w.tensor_seed, len(blocks) * w.N_B, w.layout.S, w.Hq, w.Hkv, w.D)
+    outs = gpu_fwd_bwd(w.layout, blocks, w.N_B, t)
+    sampled_dq_and_dv_sums(w, blocks, t, outs, heads=(1, w.Hq - 2))
+    if c == 3:
+        group_check(w, blocks, t, outs, g=2)
+
+
+def test_workload4_sampled():
+    w = wl.workload(4)
+    f = fields(w.layout)
+    _, _, W = ot.tile_map_c(f[0], f[1], f[2], w.N_B, w.N_B)
+    _, load, off, rb = ob.lpt(W, w.P)
+    g = int(np.argmax(load))
+    blocks = rb[off[g]:off[g + 1]].tolist()
+    t = make_tensors(w.tensor_seed, len(blocks) * w.N_B, w.layout.S, w.Hq, w.Hkv, w.D)
+    outs = gpu_fwd_bwd(w.layout, blocks, w.N_B, t)
+    sampled_dq_and_dv_sums(w, blocks, t, outs, n_rows=12, heads=(3, 30))
