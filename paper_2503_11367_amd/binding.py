@@ -14,7 +14,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmmattn.so")
+LIB_PATH = os.environ.get("MMATTN_LIB", os.path.join(_HERE, "libmmattn.so"))
 
 OK = 0
 ERR_NAMES = {0: "OK", -1: "ERR_NULL", -2: "ERR_SHAPE", -3: "ERR_UNSUPPORTED",

@@ -29,11 +29,13 @@ def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def build_lib(verbose: bool = True, extra=()) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build_lib(verbose: bool = True, extra=(), out: str = LIB, objdir: str = OBJ) -> str:
+    """Compile csrc/*.hip (extra: additional hipcc flags, e.g. -D tile knobs)
+    and link them into `out`."""
+    os.makedirs(objdir, exist_ok=True)
 
     def cc(src):
-        obj = os.path.join(OBJ, src[:-4] + ".o")
+        obj = os.path.join(objdir, src[:-4] + ".o")
         cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         return src, obj, r
@@ -48,13 +50,13 @@ def build_lib(verbose: bool = True, extra=()) -> str:
             if verbose and msgs.strip():
                 print(msgs)
             objs.append(obj)
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", out)
+    return out
 
 
 if __name__ == "__main__":
