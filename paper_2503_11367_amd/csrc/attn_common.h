@@ -43,24 +43,86 @@ __device__ __forceinline__ int c_row(int r, int hh) { return 8 * (r >> 2) + 4 * 
 // global_load_lds_dwordx4 writes lane l's 16 bytes at (wave-uniform base) + 16*l,
 // so a tile cannot be padded; instead every 256-byte "super-row" R (one row for
 // D=128, two rows for D=64) is rotated: its 16-byte chunk c' sits at position
-// (c' + ROT*R) & 15.  The bank of every element is then the same as in a padded
-// layout of pitch 256+16*ROT bytes: ROT=1 makes 16-byte row-fragment reads
-// conflict free, ROT=4 the transpose reads (LDS: 64 banks of 4 B for these widths).
-template <int D, int ROT>
+// (c' + rot(R)) & 15.  Measured on gfx950 (LDS conflict counters): 16-byte
+// row-fragment reads are conflict free when 16 consecutive rows get 16 distinct
+// rotations; transpose reads (4 rows x 64 B per pass) when 4 consecutive rows
+// are a quarter of the banks apart.
+//   MODE 1: rot = R        row fragments only            (like a 272-byte pitch)
+//   MODE 4: rot = 4R       transpose reads only          (like a 320-byte pitch)
+//   MODE 0: rot = ((R&3)<<2) | ((R>>2)&3)   both access patterns
+template <int D, int MODE>
 struct SwzTile {
     static constexpr int RB = D * 2;          // bytes per row
     static constexpr int CPR = RB / 16;       // 16-byte chunks per row
     static constexpr int RPS = 256 / RB;      // rows per super-row
+    __device__ static __forceinline__ int rot(int R) {
+        return MODE == 1 ? R : (MODE == 4 ? 4 * R : (((R & 3) << 2) | ((R >> 2) & 3)));
+    }
     // byte offset of chunk c of row r
     __device__ static __forceinline__ int byte_of(int r, int c) {
         const int R = r / RPS, cp = (r % RPS) * CPR + c;
-        return R * 256 + (((cp + ROT * R) & 15) << 4);
+        return R * 256 + (((cp + rot(R)) & 15) << 4);
     }
     // (row, chunk) stored at position p of super-row R
     __device__ static __forceinline__ void src_of(int R, int p, int& r, int& c) {
-        const int cp = (p - ROT * R) & 15;
+        const int cp = (p - rot(R)) & 15;
         r = R * RPS + cp / CPR;
         c = cp % CPR;
+    }
+};
+
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef shortx4 __attribute__((address_space(3))) * lds_s4;
+
+// Per-lane LDS byte offsets of MFMA operand fragments inside a SwzTile, computed
+// once.  The rotation repeats every 16 super-rows, so row offsets that are
+// multiples of PER = 16*RPS rows are plain address increments (immediates).
+//
+// Row fragments: operand row `li` (+ a multiple of 32 rows), elements
+// 16*ds + 8*hh .. +7.
+template <class Tile, int D>
+struct RowFragAddr {
+    static constexpr int NDS = D / 16;
+    int off[NDS];
+    __device__ __forceinline__ void init(int lane) {
+        const int li = lane & 31, hh = lane >> 5;
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) off[ds] = Tile::byte_of(li, 2 * ds + hh);
+    }
+    // rows32: which block of 32 rows (compile-time constant after unrolling)
+    __device__ __forceinline__ bf16x8 read(const unsigned char* tile, int rows32, int ds) const {
+        return __builtin_bit_cast(bf16x8, *(const u32x4*)(tile + rows32 * 32 * Tile::RB + off[ds]));
+    }
+};
+
+// Fragments of the TRANSPOSE of a row-major tile (A operand whose contraction
+// index runs over the tile's rows): 32 columns db*32.. x 16 rows ks*16.., rows in
+// the permutation that matches a C tile fed back as B operand.  Two transpose
+// reads (rows +0 and +8).
+template <class Tile, int D>
+struct TrFragAddr {
+    static constexpr int NDB = D / 32;
+    static constexpr int PER = 16 * Tile::RPS;      // rows after which the rotation repeats
+    static constexpr int NV = PER / 8;              // distinct 8-row offsets inside a period
+    int off[NDB][NV];
+    __device__ __forceinline__ void init(int lane) {
+        const int hh = lane >> 5, s16 = lane & 15, grp = (lane >> 4) & 1;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int row = v * 8 + 4 * hh + (s16 >> 2);
+                const int col = db * 32 + 16 * grp + 4 * (s16 & 3);
+                off[db][v] = Tile::byte_of(row, col >> 3) + (col & 7) * 2;
+            }
+    }
+    __device__ __forceinline__ bf16x8 read(const unsigned char* tile, int ks, int db) const {
+        const int r_lo = ks * 16, r_hi = ks * 16 + 8;            // compile-time after unrolling
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s4)(tile + (r_lo / PER) * PER * Tile::RB + off[db][(r_lo % PER) / 8]));
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s4)(tile + (r_hi / PER) * PER * Tile::RB + off[db][(r_hi % PER) / 8]));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
 };
 
