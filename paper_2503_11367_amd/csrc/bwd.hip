@@ -6,17 +6,18 @@
 //                                      Hq/Hkv query heads of the KV head)
 //   dQ = scale dS K
 // Launches:
-//   delta_kernel   Delta and LSE in base-2 units, padded to whole q-tiles;
-//   dkv_kernel     key-outer: a workgroup owns 128 keys of one KV head (32 per
-//                  wavefront), keeps dK^T/dV^T accumulators and its K fragments
-//                  in registers, its V tile in LDS, and streams the active
-//                  32-row query tiles of every head of the group through an LDS
-//                  ring.  When there are too few (k-tile, KV head) units to fill
+//   bwd_prep_kernel  Delta and LSE in base-2 units, padded to whole q-tiles, and
+//                  head-major copies of Q and dO for the key-outer pass;
+//   dkv_kernel     key-outer: a workgroup owns 128 keys of one KV head and streams
+//                  the active 32-row query tiles of every head of the group
+//                  through an LDS ring; per 32-key block one wavefront forms P
+//                  and accumulates dV^T, its partner takes P one step later and
+//                  accumulates dK^T.  When there are too few (k-tile, KV head) units to fill
 //                  the chip, a unit's step list is cut into chunks that run as
 //                  separate workgroups (the intra-GPU balancing idea of paper
-//                  section 3.2.2 applied to the key-outer pass); chunks of one
-//                  unit add their fp32 partial sums atomically and a small
-//                  kernel converts them to bf16;
+//                  section 3.2.2 applied to the key-outer pass: split the work
+//                  of a block, write partial results, aggregate in one more
+//                  launch); the partials are fp32 and summed in a fixed order;
 //   dq_kernel      query-outer, same shape as the forward kernel.
 // All contractions are 32x32x16 bf16 MFMAs.  Tiles go global -> LDS directly
 // (no registers) into rotation-swizzled layouts; a tile that is needed both as
@@ -27,15 +28,21 @@
 
 namespace mm {
 
-// ---------------------------------------------------------------- delta ------
+// ---------------------------------------------------------------- prep -------
 // One thread per 8 elements; D/8 consecutive lanes reduce one (row, head).
-// Output ld[Hq][n_pad][2] = (LSE in base-2 units, Delta); rows n_loc .. n_pad-1 are
-// padding: LSE = +inf (probability 0), Delta = 0.
+//   ld[Hq][n_pad][2] = (LSE in base-2 units, Delta = rowsum(dO o O)); rows
+//                      n_loc .. n_pad-1 are padding: LSE = +inf (probability 0), Delta = 0
+//   qh, doh [Hq][n_pad][D]  head-major copies of Q and dO (padding rows zero) for the
+//                      key-outer pass: there a tile is 64 consecutive rows of ONE head,
+//                      which in the token-major layout are Hq*D*2 bytes apart -- a
+//                      power-of-two stride that lands a whole tile stream on a few L2
+//                      sets (measured: half of all tile requests missed).
 template <int D>
 __global__ void __launch_bounds__(256)
-delta_kernel(const ushort_t* __restrict__ O, const ushort_t* __restrict__ dO,
-             const float* __restrict__ lse, int64_t n_loc, int64_t n_pad, int32_t Hq,
-             float* __restrict__ ld) {
+bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
+                const ushort_t* __restrict__ dO, const float* __restrict__ lse, int64_t n_loc,
+                int64_t n_pad, int32_t Hq, float* __restrict__ ld, ushort_t* __restrict__ qh,
+                ushort_t* __restrict__ doh) {
     constexpr int TPR = D / 8;
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t rh = gid / TPR;                       // row*Hq + h over padded rows
@@ -45,19 +52,27 @@ delta_kernel(const ushort_t* __restrict__ O, const ushort_t* __restrict__ dO,
     float acc = 0.f;
     const bool in_pad = row < n_pad;
     const bool ok = row < n_loc;
+    u32x4 qv = {0u, 0u, 0u, 0u}, dv = {0u, 0u, 0u, 0u};
     if (ok) {
         const int64_t e = (row * Hq + h) * (int64_t)D + c * 8;
+        qv = *(const u32x4*)(Q + e);
+        dv = *(const u32x4*)(dO + e);
         const bf16x8 x = __builtin_bit_cast(bf16x8, *(const u32x4*)(O + e));
-        const bf16x8 y = __builtin_bit_cast(bf16x8, *(const u32x4*)(dO + e));
+        const bf16x8 y = __builtin_bit_cast(bf16x8, dv);
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += (float)x[u] * (float)y[u];
     }
 #pragma unroll
     for (int off = TPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-    if (in_pad && c == 0) {           // ld[h][row] = (base-2 LSE, Delta)
-        float* out = ld + ((int64_t)h * n_pad + row) * 2;
-        out[0] = ok ? lse[(int64_t)h * n_loc + row] * kLog2e : INFINITY;
-        out[1] = ok ? acc : 0.f;
+    if (in_pad) {
+        const int64_t e = ((int64_t)h * n_pad + row) * D + c * 8;
+        *(u32x4*)(qh + e) = qv;
+        *(u32x4*)(doh + e) = dv;
+        if (c == 0) {
+            float* out = ld + ((int64_t)h * n_pad + row) * 2;
+            out[0] = ok ? lse[(int64_t)h * n_loc + row] * kLog2e : INFINITY;
+            out[1] = ok ? acc : 0.f;
+        }
     }
 }
 
@@ -75,34 +90,47 @@ __device__ __forceinline__ void dma4(const void* base_uniform, uint32_t off, uin
 }
 
 // ---------------------------------------------------------------- dK / dV ----
+// Key-outer pass with role-specialised wavefronts.  A workgroup owns 128 keys of
+// one KV head; for each 32-key block there is a "V wave" and a "K wave" (8
+// wavefronts, the two of a block share a SIMD).  A step is 64 query rows of one
+// head (two 32-row sub-blocks, independent instruction streams inside a wave):
+//   V wave, step i:    S = Q K^T -> P = exp2(S - LSE) (masked) -> bf16;
+//                      dV^T += dO^T P;   P goes to LDS for its partner;
+//   K wave, step i-1:  dP = dO V^T;  dS = P o (dP - Delta);  dK^T += Q^T dS.
+// The K wave runs one step behind, so one workgroup barrier per step orders the
+// P hand-over, and neither role needs both accumulators: registers stay below
+// the 256 a two-waves-per-SIMD kernel may use, with K and V fragments resident.
 constexpr int kKvBN = 128;      // keys per workgroup
-constexpr int kKvBM = 32;       // query rows per step
-constexpr int kKvThreads = 256;
-constexpr int kKvNST = 2;       // LDS ring stages for the Q/dO tiles
-#ifndef MM_KV_OCC
-#define MM_KV_OCC 2
+constexpr int kKvBM = 64;       // query rows per step
+constexpr int kKvSub = kKvBM / 32;
+constexpr int kKvThreads = 512;
+#ifndef MM_KV_NST
+#define MM_KV_NST 3             // LDS ring stages for the Q/dO tiles (prefetch distance NST-2)
 #endif
+constexpr int kKvNST = MM_KV_NST;
 
 template <int D>
 struct KvSmem {
-    alignas(1024) unsigned char v[kKvBN * D * 2];               // this workgroup's V rows (MODE 1)
     alignas(1024) unsigned char q[kKvNST][kKvBM * D * 2];       // MODE 0: rows and transpose
     alignas(1024) unsigned char d[kKvNST][kKvBM * D * 2];
-    alignas(256) float ld[kKvNST][4][64];                       // per wave: (lse2, delta) of 32 rows
+    alignas(1024) unsigned char p[2][4][64 * 32 * kKvSub];      // P hand-over: [parity][key block][sub][lane] 2 x 16 B
+    alignas(256) float ld[kKvNST][8][2 * kKvBM];                // per wave: (lse2, delta) of the step's rows
     uint32_t q_ss[kKvBM];                                       // mask fields of a PARTIAL step's rows
     uint32_t q_causal[kKvBM];
     int32_t q_pos[kKvBM];
 };
 
+// A (k-tile, KV head) unit is processed by `cmax` workgroups, each taking `hpc`
+// of the group's query heads (cmax * hpc = Hq/Hkv).
 struct KvChunking {
-    int32_t cmax;        // chunks per (k-tile, KV head) unit at most
-    int32_t len;         // steps per chunk
+    int32_t cmax;
+    int32_t hpc;
 };
 
 template <int D>
-__global__ void __launch_bounds__(kKvThreads, MM_KV_OCC)
-dkv_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
-           const ushort_t* __restrict__ V, const ushort_t* __restrict__ dO,
+__global__ void __launch_bounds__(kKvThreads, 2)
+dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
+           const ushort_t* __restrict__ V, const ushort_t* __restrict__ dOh,
            const uint64_t* __restrict__ bits, const int32_t* __restrict__ blocks, int32_t block,
            int64_t n_loc, int64_t n_pad, int64_t S, int32_t Hq, int32_t Hkv, float scale,
            float scale_log2, const float* __restrict__ ld_g,
@@ -111,11 +139,13 @@ dkv_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
            float* __restrict__ accV) {
     constexpr int NDS = D / 16, NDB = D / 32;
     constexpr int RB = D * 2;
+    constexpr int NST = kKvNST;
     using QT = SwzTile<D, 0>;
-    using VT = SwzTile<D, 1>;
-    constexpr int NI = kKvBM * RB / 1024 / 4;          // 1 KiB transfers per wave per tensor per step
-    constexpr int NIV = kKvBN * RB / 1024 / 4;         // same for the V tile
+    constexpr int NI = kKvBM * RB / 1024 / 8;          // 1 KiB transfers per wave per tensor per step
     constexpr int kStage = kKvBM * RB;
+    static_assert(NI >= 1, "head_dim");
+    constexpr int kPerStep = 2 * NI + kKvSub;          // + the (lse2, delta) rows, 32 per transfer
+    static_assert(NST >= 3 && NST <= 8 && (NST - 3) * kPerStep < 64, "ring depth");
     __shared__ KvSmem<D> sm;
     if (*err) return;
 
@@ -139,110 +169,133 @@ dkv_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     }
     const int kt = plan.korder[tile_rank];
     const int n_q = plan.qcount[kt];
-    const int n_steps_all = n_q * rep;
-    const int step0 = chunk * ch.len;
-    if (step0 >= n_steps_all && chunk > 0) return;             // nothing for this chunk
-    const int n_steps = max(0, min(ch.len, n_steps_all - step0));   // 0: chunk 0 writes zeros
-    const bool shared_unit = n_steps_all > ch.len;             // several chunks: accumulate atomically
+    const bool shared_unit = ch.cmax > 1;              // several workgroups per unit: fp32 partials, summed later
+    const int n_steps = n_q * ch.hpc;                  // 0 (no query sees these keys): writes zeros
+    const int head0 = g * rep + chunk * ch.hpc;        // first query head of this workgroup
     const uint32_t* qlist = plan.qlist + (int64_t)kt * plan.nq;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool k_role = wave >= 4;                     // waves 0-3: V role, 4-7: K role
+    const int kblk = wave & 3;                         // 32-key block of this wave
     const int li = lane & 31, hh = lane >> 5;
 
-    // this lane's key: position, mask fields, K fragments (B operand of S = Q K^T)
-    const int64_t key = (int64_t)kt * kKvBN + wave * 32 + li;
+    // this lane's key; the role's resident operand (B operand, 8 head-dim values per step):
+    // V role keeps K (for S = Q K^T), K role keeps V (for dP = dO V^T)
+    const int64_t key = (int64_t)kt * kKvBN + kblk * 32 + li;
     const uint32_t k_ss = word_ss(bits[key]);
-    bf16x8 kf[NDS];
+    bf16x8 res[NDS];
     {
+        const ushort_t* src = k_role ? V : K;
         const int64_t off = (key * Hkv + g) * (int64_t)D + hh * 8;
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds)
-            kf[ds] = __builtin_bit_cast(bf16x8, *(const u32x4*)(K + off + ds * 16));
+            res[ds] = __builtin_bit_cast(bf16x8, *(const u32x4*)(src + off + ds * 16));
     }
-    floatx16 dk[NDB], dv[NDB];
+    floatx16 acc[NDB];                                 // dV^T (V role) or dK^T (K role)
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
     // ---- transfers -------------------------------------------------------------------
-    // V tile of the workgroup's 128 keys (once)
-    {
-        const ushort_t* vt = V + ((int64_t)kt * kKvBN * Hkv) * D;
-#pragma unroll
-        for (int i = 0; i < NIV; ++i) {
-            const int R = 4 * (wave * NIV + i) + (lane >> 4), p = lane & 15;
-            int r, c;
-            VT::src_of(R, p, r, c);
-            dma16(vt, (uint32_t)(((r * Hkv + g) * D + c * 8) * 2),
-                  lds_addr_of(sm.v) + (wave * NIV + i) * 1024);
-        }
-    }
-    // Q/dO tile of one step: (row, chunk) this lane fetches for each of its transfers
-    int tr_row[NI], tr_chunk[NI];
+    uint32_t tr_off[NI];                               // byte offset inside a (head-major) tile this lane fetches
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-        const int R = 4 * (wave * NI + i) + (lane >> 4), p = lane & 15;
-        QT::src_of(R, p, tr_row[i], tr_chunk[i]);
+        int r, c;
+        QT::src_of(4 * (wave * NI + i) + (lane >> 4), lane & 15, r, c);
+        tr_off[i] = (uint32_t)((r * D + c * 8) * 2);
     }
     const uint32_t lds_q = lds_addr_of(sm.q[0]) + (wave * NI) * 1024;
     const uint32_t lds_d = lds_addr_of(sm.d[0]) + (wave * NI) * 1024;
-    const uint32_t lds_ld = lds_addr_of(sm.ld[0][0]) + wave * 256;
-    const int64_t row_stride = (int64_t)Hq * D;        // elements between consecutive local rows
+    const uint32_t lds_ld = lds_addr_of(sm.ld[0][0]) + wave * (8 * kKvBM);
     auto issue_step = [&](uint32_t entry, int hq, int stage) {
         const int64_t r0 = (int64_t)(entry & ~kPartialFlag) * kKvBM;
-        const int64_t last = n_loc - 1 - r0;           // rows past the end re-read the last row
-        const ushort_t* qb = Q + (r0 * Hq + hq) * (int64_t)D;
-        const ushort_t* db_ = dO + (r0 * Hq + hq) * (int64_t)D;
+        const int64_t tile = ((int64_t)hq * n_pad + r0) * D;   // 64 consecutive rows, padded with zeros
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const int64_t rr = min((int64_t)tr_row[i], last);
-            const uint32_t off = (uint32_t)((rr * row_stride + tr_chunk[i] * 8) * 2);
-            dma16(qb, off, lds_q + stage * kStage + i * 1024);
-            dma16(db_, off, lds_d + stage * kStage + i * 1024);
+            dma16(Qh + tile, tr_off[i], lds_q + stage * kStage + i * 1024);
+            dma16(dOh + tile, tr_off[i], lds_d + stage * kStage + i * 1024);
         }
-        // (lse2, delta) pairs of the 32 rows: 256 contiguous bytes of the padded array
-        dma4(ld_g + ((int64_t)hq * n_pad + r0) * 2, (uint32_t)(lane * 4), lds_ld + stage * (4 * 256));
+        // (lse2, delta) pairs of the step's rows: contiguous in the padded array, 32 rows per transfer
+        const float* lb = ld_g + ((int64_t)hq * n_pad + r0) * 2;
+#pragma unroll
+        for (int sb = 0; sb < kKvSub; ++sb)
+            dma4(lb + sb * 64, (uint32_t)(lane * 4), lds_ld + stage * (8 * 8 * kKvBM) + sb * 256);
     };
 
-    // the step list is fetched 64 entries at a time, one per lane, and read back with
-    // readlane; (head, list index) of the next step advance incrementally
+    // Step s is query tile qlist[n_q-1 - s%n_q] of head head0 + s/n_q: every k-tile
+    // of a head walks the query tiles from the last one down, so the workgroups
+    // that are resident together read the same Q/dO tiles at about the same time
+    // and share them in L2.  The list is fetched 64 entries at a time, one per lane,
+    // and read back with readlane; the head of the next step advances incrementally.
     auto fetch_chunk = [&](int first_step) -> uint32_t {
-        const int gs = step0 + first_step + lane;
-        return gs < n_steps_all ? qlist[gs % n_q] : 0u;
+        const int s_ = first_step + lane;
+        return s_ < n_steps ? qlist[n_q - 1 - s_ % n_q] : 0u;
     };
     uint32_t list_chunk = n_steps > 0 ? fetch_chunk(0) : 0u;
-    int hq_next = g * rep + (n_q > 0 ? step0 / n_q : 0);       // head of the step to issue next
-    int qi_next = n_q > 0 ? step0 % n_q : 0;                   // its index in the q list
-    uint32_t entry = 0u;
+    int hq_next = head0;                                       // head of the step to issue next
+    int qi_next = 0;                                           // its position in the walk
     RowFragAddr<QT, D> qrow;      // Q and dO tiles share layout and lane pattern
     TrFragAddr<QT, D> qtr;
-    RowFragAddr<VT, D> vrow;
     qrow.init(lane);
     qtr.init(lane);
-    vrow.init(lane);
-    const unsigned char* v_mine = sm.v + wave * 32 * RB;   // my 32 keys' rows (a multiple of the period)
-    if (n_steps > 0) {
-        entry = __builtin_amdgcn_readlane(list_chunk, 0);
-        issue_step(entry, hq_next, 0);
-        if (++qi_next == n_q) { qi_next = 0; ++hq_next; }
-    }
-    int st = 0;
-    for (int step = 0; step < n_steps; ++step) {
-        const bool partial = (entry & kPartialFlag) != 0;
-        wait_vmcnt<0>();                    // this step's tiles (and, first time, V) have landed
-        __syncthreads();
-        uint32_t entry_next = 0u;
-        if (step + 1 < n_steps) {
-            if (((step + 1) & 63) == 0) list_chunk = fetch_chunk(step + 1);
-            entry_next = __builtin_amdgcn_readlane(list_chunk, (step + 1) & 63);
-            issue_step(entry_next, hq_next, st ^ 1);
+
+    // Every ordinary vector load issued so far (resident fragments, mask word, list
+    // chunk) is awaited here, once: the compiler then has nothing pending when the
+    // loop starts and inserts no waits of its own inside it (such a wait would also
+    // drain the tile transfers, which it cannot see).
+    wait_vmcnt<0>();
+
+    // prologue: steps 0 .. NST-3 in flight; pend[] holds the list entries of the steps
+    // i-1 (K role's), i (V role's) and the ones in flight
+    uint32_t pend[NST - 1];
+#pragma unroll
+    for (int j = 0; j < NST - 1; ++j) pend[j] = 0u;
+#pragma unroll
+    for (int j = 0; j < NST - 2; ++j)
+        if (j < n_steps) {
+            pend[j + 1] = __builtin_amdgcn_readlane(list_chunk, j);
+            issue_step(pend[j + 1], hq_next, j);
             if (++qi_next == n_q) { qi_next = 0; ++hq_next; }
         }
-        if (partial) {
+
+    int st = 0;                                        // stage of step i
+    const int n_iter = n_steps > 0 ? n_steps + 1 : 0;
+    for (int i = 0; i < n_iter; ++i) {
+        // step i's tiles have landed once only the younger steps' transfers remain
+        {
+            const int younger = max(0, min(NST - 3, n_steps - 1 - i));
+            if (younger == 0) wait_vmcnt<0>();
+            else if (younger == 1) wait_vmcnt<(NST > 3 ? 1 : 0) * kPerStep>();
+            else if (younger == 2) wait_vmcnt<(NST > 4 ? 2 : 0) * kPerStep>();
+            else if (younger == 3) wait_vmcnt<(NST > 5 ? 3 : 0) * kPerStep>();
+            else if (younger == 4) wait_vmcnt<(NST > 6 ? 4 : 0) * kPerStep>();
+            else wait_vmcnt<(NST > 7 ? 5 : 0) * kPerStep>();
+        }
+        __syncthreads();                    // step i landed; step i-2's stage and P(i-2) are free
+        uint32_t fresh = 0u;
+        const int nxt = i + NST - 2;        // step to put in flight now
+        if (nxt < n_steps) {
+            if ((nxt & 63) == 0) {
+                list_chunk = fetch_chunk(nxt);
+                wait_vmcnt<0>();            // awaited here so that no wait is needed after the branch
+            }
+            fresh = __builtin_amdgcn_readlane(list_chunk, nxt & 63);
+            int sn = st + NST - 2;
+            if (sn >= NST) sn -= NST;
+            issue_step(fresh, hq_next, sn);
+            if (++qi_next == n_q) { qi_next = 0; ++hq_next; }
+        }
+        const uint32_t e_cur = pend[1];     // step i
+#pragma unroll
+        for (int j = 0; j + 1 < NST - 1; ++j) pend[j] = pend[j + 1];
+        pend[NST - 2] = fresh;
+
+        const bool partial = i < n_steps && (e_cur & kPartialFlag) != 0;
+        if (partial) {                      // workgroup-uniform
             if (tid < kKvBM) {
-                const int64_t r = min((int64_t)(entry & ~kPartialFlag) * kKvBM + tid, n_loc - 1);
+                const int64_t r = min((int64_t)(e_cur & ~kPartialFlag) * kKvBM + tid, n_loc - 1);
                 const int64_t p = row_pos(blocks, block, r);
                 const uint64_t w = bits[p];
                 sm.q_ss[tid] = word_ss(w);
@@ -251,106 +304,122 @@ dkv_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             }
             __syncthreads();
         }
-        const unsigned char* qt = sm.q[st];
-        const unsigned char* dt = sm.d[st];
-        const float* ld = sm.ld[st][wave];
 
-        // S = Q K^T and dP = dO V^T : rows = the step's 32 queries, columns = my 32 keys
-        floatx16 s, dp;
+        // Both roles run the same two MFMA phases on different tiles; only the
+        // element-wise part in between differs (kept in one place each so that the
+        // accumulator is updated by a single instruction stream).
+        const bool active = k_role ? i >= 1 : i < n_steps;
+        if (active) {
+            int sa = st;                                // V role: step i;  K role: step i-1
+            if (k_role) { sa = st - 1; if (sa < 0) sa += NST; }
+            const unsigned char* t1 = k_role ? sm.d[sa] : sm.q[sa];   // rows:      dO | Q
+            const unsigned char* t2 = k_role ? sm.q[sa] : sm.d[sa];   // transpose: Q  | dO
+            // per-row constant: lse2 (V role) or Delta (K role) of the (lse2, delta) pairs
+            const float* ld = sm.ld[sa][wave] + (k_role ? 1 : 0);
+            floatx16 x[kKvSub];                         // S (V role) or dP (K role) per sub-block
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+            for (int sb = 0; sb < kKvSub; ++sb)
 #pragma unroll
-        for (int ds = 0; ds < NDS; ++ds)
-            s = mfma32(qrow.read(qt, 0, ds), kf[ds], s);
+                for (int r = 0; r < 16; ++r) x[sb][r] = 0.f;
 #pragma unroll
-        for (int ds = 0; ds < NDS; ++ds)
-            dp = mfma32(qrow.read(dt, 0, ds), vrow.read(v_mine, 0, ds), dp);
-        bf16x8 pf[2], dsf[2];
+            for (int ds = 0; ds < NDS; ++ds)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            // rows 8c+4hh .. +3: (lse2, delta) pairs
-            const floatx4 a4 = *(const floatx4*)(ld + 2 * (8 * c + 4 * hh));
-            const floatx4 b4 = *(const floatx4*)(ld + 2 * (8 * c + 4 * hh) + 4);
-            const float l_[4] = {a4[0], a4[2], b4[0], b4[2]};
-            const float d_[4] = {a4[1], a4[3], b4[1], b4[3]};
+                for (int sb = 0; sb < kKvSub; ++sb)
+                    x[sb] = mfma32(qrow.read(t1, sb, ds), res[ds], x[sb]);
+            bf16x8 bop[2 * kKvSub];                     // P (V role) or dS (K role), bf16
+            if (!k_role) {
+                if (partial) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int r = 4 * c + u;
-                const int qr = 8 * c + 4 * hh + u;
-                float p = __builtin_amdgcn_exp2f(s[r] * scale_log2 - l_[u]);
-                if (partial && !visible(sm.q_ss[qr], sm.q_causal[qr], sm.q_pos[qr], k_ss, key)) p = 0.f;
-                pf[r >> 3][r & 7] = (__bf16)p;
-                dsf[r >> 3][r & 7] = (__bf16)(p * (dp[r] - d_[u]));
+                    for (int sb = 0; sb < kKvSub; ++sb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int qr = sb * 32 + c_row(r, hh);
+                            if (!visible(sm.q_ss[qr], sm.q_causal[qr], sm.q_pos[qr], k_ss, key))
+                                x[sb][r] = -INFINITY;
+                        }
+                }
+                // masked entries are -inf: exp2 gives 0 (padding rows have LSE = +inf)
+#pragma unroll
+                for (int sb = 0; sb < kKvSub; ++sb) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        bop[sb * 2 + (r >> 3)][r & 7] = (__bf16)__builtin_amdgcn_exp2f(
+                            x[sb][r] * scale_log2 - ld[2 * (sb * 32 + c_row(r, hh))]);
+                    unsigned char* pb = sm.p[i & 1][kblk] + (sb * 64 + lane) * 32;
+                    *(u32x4*)pb = __builtin_bit_cast(u32x4, bop[sb * 2]);
+                    *(u32x4*)(pb + 16) = __builtin_bit_cast(u32x4, bop[sb * 2 + 1]);
+                }
+            } else {
+#pragma unroll
+                for (int sb = 0; sb < kKvSub; ++sb) {
+                    const unsigned char* pb = sm.p[(i - 1) & 1][kblk] + (sb * 64 + lane) * 32;
+                    const bf16x8 p0 = __builtin_bit_cast(bf16x8, *(const u32x4*)pb);
+                    const bf16x8 p1 = __builtin_bit_cast(bf16x8, *(const u32x4*)(pb + 16));
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float pv = (float)(r < 8 ? p0[r & 7] : p1[r & 7]);
+                        bop[sb * 2 + (r >> 3)][r & 7] =
+                            (__bf16)(pv * (x[sb][r] - ld[2 * (sb * 32 + c_row(r, hh))]));
+                    }
+                }
             }
+#pragma unroll
+            for (int ks = 0; ks < 2 * kKvSub; ++ks)
+#pragma unroll
+                for (int db = 0; db < NDB; ++db)
+                    acc[db] = mfma32(qtr.read(t2, ks, db), bop[ks], acc[db]);
         }
-        // dV^T += dO^T P ;  dK^T += Q^T dS
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int db = 0; db < NDB; ++db) {
-                dv[db] = mfma32(qtr.read(dt, ks, db), pf[ks], dv[db]);
-                dk[db] = mfma32(qtr.read(qt, ks, db), dsf[ks], dk[db]);
-            }
-        st ^= 1;
-        entry = entry_next;
+        if (++st == NST) st = 0;
     }
-    wait_vmcnt<0>();                        // (no steps: the V transfer must still finish)
 
     // ---- epilogue: lane holds key `key`, 4 consecutive d per register quad ------------
     const int64_t obase = (key * Hkv + g) * (int64_t)D + 4 * hh;
+    const float osc = k_role ? scale : 1.0f;
     if (shared_unit) {
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t e = obase + db * 32 + (r >> 2) * 8 + (r & 3);
-                unsafeAtomicAdd(accK + e, dk[db][r] * scale);
-                unsafeAtomicAdd(accV + e, dv[db][r]);
-            }
-    } else {
+        // this workgroup's partial sums, fp32, in its own slice [chunk][S][Hkv][D]
+        float* dst = (k_role ? accK : accV) + (int64_t)chunk * S * Hkv * D + obase;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                bf16x4 ok, ov;
+                floatx4 out;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    ok[u] = (__bf16)(dk[db][c * 4 + u] * scale);
-                    ov[u] = (__bf16)dv[db][c * 4 + u];
-                }
-                *(u32x2*)(dK + obase + db * 32 + c * 8) = __builtin_bit_cast(u32x2, ok);
-                *(u32x2*)(dV + obase + db * 32 + c * 8) = __builtin_bit_cast(u32x2, ov);
+                for (int u = 0; u < 4; ++u) out[u] = acc[db][c * 4 + u] * osc;
+                *(floatx4*)(dst + db * 32 + c * 8) = out;
+            }
+    } else {
+        ushort_t* dst = k_role ? dK : dV;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                bf16x4 out;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) out[u] = (__bf16)(acc[db][c * 4 + u] * osc);
+                *(u32x2*)(dst + obase + db * 32 + c * 8) = __builtin_bit_cast(u32x2, out);
             }
     }
 }
 
-// zero (before) / convert to bf16 (after) the fp32 accumulators of the units whose
-// step list was cut into several chunks; one workgroup per (k-tile, KV head)
-template <bool FINISH>
+// sum the per-workgroup fp32 partials of every (k-tile, KV head) unit in a fixed
+// order and write bf16; 4 elements per thread
 __global__ void __launch_bounds__(256)
-dkv_shared_units_kernel(TilePlanT plan, KvChunking ch, int32_t rep, int32_t Hkv, int32_t D,
-                        const int32_t* __restrict__ err, float* __restrict__ accK,
-                        float* __restrict__ accV, ushort_t* __restrict__ dK,
-                        ushort_t* __restrict__ dV) {
+dkv_reduce_kernel(int32_t cmax, int64_t n_elems, const int32_t* __restrict__ err,
+                  const float* __restrict__ accK, const float* __restrict__ accV,
+                  ushort_t* __restrict__ dK, ushort_t* __restrict__ dV) {
     if (*err) return;
-    const int kt = blockIdx.x, g = blockIdx.y;
-    if (plan.qcount[kt] * rep <= ch.len) return;
-    const int per_row = D / 4;                           // float4 per key row
-    for (int i = threadIdx.x; i < kKvBN * per_row; i += 256) {
-        const int r = i / per_row, c = i - r * per_row;
-        const int64_t e = (((int64_t)kt * kKvBN + r) * Hkv + g) * (int64_t)D + c * 4;
-        if (!FINISH) {
-            *(floatx4*)(accK + e) = floatx4{0.f, 0.f, 0.f, 0.f};
-            *(floatx4*)(accV + e) = floatx4{0.f, 0.f, 0.f, 0.f};
-        } else {
-            const floatx4 a = *(const floatx4*)(accK + e), b = *(const floatx4*)(accV + e);
-            bf16x4 oa, ob;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) { oa[u] = (__bf16)a[u]; ob[u] = (__bf16)b[u]; }
-            *(u32x2*)(dK + e) = __builtin_bit_cast(u32x2, oa);
-            *(u32x2*)(dV + e) = __builtin_bit_cast(u32x2, ob);
-        }
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e >= n_elems) return;
+    floatx4 a = *(const floatx4*)(accK + e), b = *(const floatx4*)(accV + e);
+    for (int c = 1; c < cmax; ++c) {
+        a += *(const floatx4*)(accK + c * n_elems + e);
+        b += *(const floatx4*)(accV + c * n_elems + e);
     }
+    bf16x4 oa, ob;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { oa[u] = (__bf16)a[u]; ob[u] = (__bf16)b[u]; }
+    *(u32x2*)(dK + e) = __builtin_bit_cast(u32x2, oa);
+    *(u32x2*)(dV + e) = __builtin_bit_cast(u32x2, ob);
 }
 
 // ---------------------------------------------------------------- dQ ---------
@@ -469,6 +538,9 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     auto entry_at = [&](int it) -> uint32_t {
         return __builtin_amdgcn_readlane(list_chunk, it & 63);
     };
+    // all ordinary vector loads so far are awaited once, before the transfers start
+    // (see the note in the forward kernel)
+    wait_vmcnt<0>();
     uint32_t pend[NST - 1];
 #pragma unroll
     for (int j = 0; j < NST - 1; ++j) {
@@ -494,6 +566,7 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             if (((it + NST - 1) & 63) == 0) {
                 const int j = it + NST - 1 + lane;
                 list_chunk = j < n_active ? klist[j] : 0u;
+                wait_vmcnt<0>();           // awaited here so that no wait is needed after the branch
             }
             fresh = entry_at(it + NST - 1);
             int sn = st + NST - 1;
@@ -522,11 +595,17 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
             for (int ds = 0; ds < NDS; ++ds)
                 dp = mfma32(krow.read(vb_base, kb, ds), dof[ds], dp);
+            if (partial) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kl = kb * 32 + c_row(r, hh);
+                    if (!visible(q_ss, q_causal, q_pos, sm.kss[kl], k0 + kl)) s[r] = -INFINITY;
+                }
+            }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int kl = kb * 32 + c_row(r, hh);
-                float p = __builtin_amdgcn_exp2f(s[r] * scale_log2 - my_lse2);
-                if (partial && !visible(q_ss, q_causal, q_pos, sm.kss[kl], k0 + kl)) p = 0.f;
+                // masked entries are -inf: exp2 gives 0 (padding rows have LSE = +inf)
+                const float p = __builtin_amdgcn_exp2f(s[r] * scale_log2 - my_lse2);
                 dsf[kb * 2 + (r >> 3)][r & 7] = (__bf16)(p * (dp[r] - my_delta));
             }
         };
@@ -557,26 +636,26 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 
 // ---------------------------------------------------------------- host -------
 struct BwdLayout {
-    size_t err, clean_blocks, ld, cls_a, kcount, klist, qorder, cls_b, qcount, qlist,
+    size_t err, clean_blocks, ld, qh, doh, cls_a, kcount, klist, qorder, cls_b, qcount, qlist,
         korder, acc_k, acc_v, total;
     int32_t nq_a, nk_a, nq_b, nk_b;
     int64_t n_pad;
     KvChunking ch;
 };
 
-// Cut the step lists only when the (k-tile, KV head) units alone cannot fill the
-// chip a few times over (512 resident workgroups).
-static KvChunking kv_chunking(int32_t nk_b, int32_t nq_b, int32_t Hq, int32_t Hkv) {
+// Split the query heads of a (k-tile, KV head) unit over several workgroups only
+// when the units alone cannot fill the chip a few times over (256 resident
+// workgroups).
+static KvChunking kv_chunking(int32_t nk_b, int32_t Hq, int32_t Hkv) {
     const int64_t units = (int64_t)nk_b * Hkv;
-    const int64_t max_steps = (int64_t)nq_b * (Hq / Hkv);
-    int64_t cmax = (2048 + units - 1) / units;
-    if (cmax > 8) cmax = 8;
-    if (cmax < 1) cmax = 1;
-    int64_t len = (max_steps + cmax - 1) / cmax;
-    if (len < 32) len = 32;
-    cmax = (max_steps + len - 1) / len;
-    if (cmax < 1) cmax = 1;
-    return KvChunking{(int32_t)cmax, (int32_t)len};
+    const int32_t rep = Hq / Hkv;
+    int32_t cmax = 1;                  // smallest divisor of rep that yields >= 2048 workgroups, else rep
+    for (int32_t c = 1; c <= rep; ++c) {
+        if (rep % c) continue;
+        cmax = c;
+        if (units * c >= 2048) break;
+    }
+    return KvChunking{cmax, rep / cmax};
 }
 
 static BwdLayout bwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t Hq, int32_t Hkv,
@@ -587,12 +666,14 @@ static BwdLayout bwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     L.nq_b = (int32_t)((n_loc + kKvBM - 1) / kKvBM);
     L.nk_b = (int32_t)(S / kKvBN);
     L.n_pad = (int64_t)L.nq_a * kDqBM;
-    L.ch = kv_chunking(L.nk_b, L.nq_b, Hq, Hkv);
+    L.ch = kv_chunking(L.nk_b, Hq, Hkv);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
     L.err = take(256);
     L.clean_blocks = take((size_t)n_blocks * 4);
     L.ld = take((size_t)Hq * L.n_pad * 8);
+    L.qh = take((size_t)Hq * L.n_pad * D * 2);
+    L.doh = take((size_t)Hq * L.n_pad * D * 2);
     L.cls_a = take((size_t)L.nq_a * L.nk_a);
     L.kcount = take((size_t)L.nq_a * 4);
     L.klist = take((size_t)L.nq_a * L.nk_a * 4);
@@ -601,7 +682,7 @@ static BwdLayout bwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     L.qcount = take((size_t)L.nk_b * 4);
     L.qlist = take((size_t)L.nq_b * L.nk_b * 4);
     L.korder = take((size_t)L.nk_b * 4);
-    const size_t acc = L.ch.cmax > 1 ? (size_t)S * Hkv * D * 4 : 0;
+    const size_t acc = L.ch.cmax > 1 ? (size_t)L.ch.cmax * S * Hkv * D * 4 : 0;
     L.acc_k = take(acc);
     L.acc_v = take(acc);
     L.total = off;
@@ -633,6 +714,8 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     int32_t* err = (int32_t*)(base + L.err);
     int32_t* clean = (int32_t*)(base + L.clean_blocks);
     float* ld = (float*)(base + L.ld);
+    ushort_t* qh = (ushort_t*)(base + L.qh);
+    ushort_t* doh = (ushort_t*)(base + L.doh);
     float* acc_k = (float*)(base + L.acc_k);
     float* acc_v = (float*)(base + L.acc_v);
     TilePlan pa;
@@ -662,23 +745,23 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     const float scale_log2 = a.scale * kLog2e;
     {
         const int64_t threads = L.n_pad * a.Hq * (D / 8);
-        hipLaunchKernelGGL(delta_kernel<D>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                           (const ushort_t*)o, (const ushort_t*)d_o, lse, n_loc, L.n_pad, a.Hq, ld);
+        hipLaunchKernelGGL(bwd_prep_kernel<D>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+                           st, (const ushort_t*)a.q, (const ushort_t*)o, (const ushort_t*)d_o, lse,
+                           n_loc, L.n_pad, a.Hq, ld, qh, doh);
     }
     const int rep = a.Hq / a.Hkv;
-    if (L.ch.cmax > 1)
-        hipLaunchKernelGGL(dkv_shared_units_kernel<false>, dim3(L.nk_b, a.Hkv), dim3(256), 0, st, pb,
-                           L.ch, rep, a.Hkv, D, err, acc_k, acc_v, (ushort_t*)dk, (ushort_t*)dv);
     stage_begin(MMATTN_STAGE_DKV, st);
     hipLaunchKernelGGL(dkv_kernel<D>, dim3((unsigned)((int64_t)L.nk_b * a.Hkv * L.ch.cmax)),
-                       dim3(kKvThreads), 0, st, (const ushort_t*)a.q, (const ushort_t*)a.k,
-                       (const ushort_t*)a.v, (const ushort_t*)d_o, a.bits, clean, a.block, n_loc,
+                       dim3(kKvThreads), 0, st, (const ushort_t*)qh, (const ushort_t*)a.k,
+                       (const ushort_t*)a.v, (const ushort_t*)doh, a.bits, clean, a.block, n_loc,
                        L.n_pad, a.S, a.Hq, a.Hkv, a.scale, scale_log2, ld, pb, L.ch, err,
                        (ushort_t*)dk, (ushort_t*)dv, acc_k, acc_v);
+    if (L.ch.cmax > 1) {
+        const int64_t n_elems = a.S * a.Hkv * D;
+        hipLaunchKernelGGL(dkv_reduce_kernel, dim3((unsigned)((n_elems / 4 + 255) / 256)), dim3(256), 0,
+                           st, L.ch.cmax, n_elems, err, acc_k, acc_v, (ushort_t*)dk, (ushort_t*)dv);
+    }
     stage_end(MMATTN_STAGE_DKV, st);
-    if (L.ch.cmax > 1)
-        hipLaunchKernelGGL(dkv_shared_units_kernel<true>, dim3(L.nk_b, a.Hkv), dim3(256), 0, st, pb,
-                           L.ch, rep, a.Hkv, D, err, acc_k, acc_v, (ushort_t*)dk, (ushort_t*)dv);
     const bool pair = rep % 2 == 0;
     stage_begin(MMATTN_STAGE_DQ, st);
     if (pair) launch_dq_kernel<D, 2, 3>(a, d_o, n_loc, L, scale_log2, clean, ld, pa, err, dq, st);

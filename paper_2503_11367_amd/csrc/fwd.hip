@@ -157,6 +157,12 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         return __builtin_amdgcn_readlane(list_chunk, it & 63);
     };
 
+    // Every ordinary vector load issued so far (Q fragments, mask word, list chunk)
+    // is awaited here, once: the compiler then has nothing pending when the loop
+    // starts and inserts no waits of its own inside it (such a wait would also
+    // drain the tile transfers, which it cannot see).
+    wait_vmcnt<0>();
+
     // prologue: tiles 0 .. NST-2 in flight; pend[] holds their list entries
     uint32_t pend[NST - 1];
 #pragma unroll
@@ -185,6 +191,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
                 // next 64 list entries (this vector load also drains the transfers in flight)
                 const int j = it + NST - 1 + lane;
                 list_chunk = j < n_active ? klist[j] : 0u;
+                wait_vmcnt<0>();           // awaited here so that no wait is needed after the branch
             }
             fresh = entry_at(it + NST - 1);
             int sn = st + NST - 1;
