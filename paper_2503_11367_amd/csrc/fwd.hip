@@ -16,8 +16,15 @@
 //   O^T += V^T P^T (A = V fragment read from the row-major V tile with the LDS
 //                  transpose read ds_read_b64_tr_b16).
 // K/V tiles go HBM/L2 -> LDS directly (global_load_lds_dwordx4, no registers)
-// through a ring of NST stages: the transfers of the next NST-1 tiles overlap the
+// through a ring of NST stages: the transfers of the next tiles overlap the
 // math of the current one and there is one workgroup barrier per tile.
+// The loop is a software pipeline over half tiles (32 keys): while the
+// probabilities of one half tile are exponentiated and multiplied into O, the
+// scores of the next one are already being formed.  Registers (about 230 per
+// lane) and LDS (the ring) allow one workgroup of 8 wavefronts per CU, two
+// wavefronts per SIMD, so latencies are covered inside the wave: operand
+// fragments are requested four MFMAs ahead and the instruction order is pinned
+// slot by slot (see `step`).
 // FULL tiles skip the predicate; PARTIAL tiles evaluate it per element from the
 // 64-bit words (query word in registers, key words from LDS).
 #include "attn_common.h"
@@ -26,17 +33,16 @@ namespace mm {
 
 constexpr int kFwdBM = 128;     // query rows per q-tile
 constexpr int kFwdBN = 64;      // keys per k-tile
-// the running row max is only raised when it would grow by more than this many
-// powers of two; until then probabilities are taken relative to the stale max
-// (they stay below 2^kRescaleThreshold, harmless in fp32/bf16) and the
-// accumulator rescale is skipped
-constexpr float kRescaleThreshold = 8.0f;
+// how far (in powers of two) the running row maximum may drift from the shift that
+// the probabilities are taken relative to before the shift follows it; inside
+// this band probabilities stay within 2^+-kShiftSlack, harmless in fp32/bf16
+constexpr float kShiftSlack = 64.0f;
 
 template <int D, int NST>
 struct FwdSmem {
     alignas(1024) unsigned char k[NST][kFwdBN * D * 2];   // rotated tiles, see SwzTile
     alignas(1024) unsigned char v[NST][kFwdBN * D * 2];
-    uint32_t kss[kFwdBN];                                 // sample/span fields of a PARTIAL tile's keys
+    uint32_t kss[2][kFwdBN];                              // sample/span fields of a PARTIAL tile's keys, by tile parity
 };
 
 // HPW query heads per workgroup (4 wavefronts each), NST LDS stages.
@@ -111,7 +117,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = 0.f, m_true = -INFINITY, l_run = 0.f;   // shift, running maximum (log2 units), row sum
 
     // ---- tile transfers: which global chunk lands at this lane's LDS slot --------
     uint32_t gk[NI], gv[NI];              // byte offsets inside a tile of K / V
@@ -138,16 +144,18 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     };
 
     // ---- LDS read offsets (bytes) ---------------------------------------------------
-    int koff[NDS];                         // K fragment of row li, contraction step ds
+    // (LDS byte addresses inside stage 0; stage, half tile and key-row offsets are
+    // compile-time constants that end up in the instructions' offset fields)
+    uint32_t kaddr[NDS];                   // K fragment of row li, contraction step ds
 #pragma unroll
-    for (int ds = 0; ds < NDS; ++ds) koff[ds] = KT::byte_of(li, 2 * ds + hh);
+    for (int ds = 0; ds < NDS; ++ds) kaddr[ds] = lds_addr_of(sm.k[0]) + KT::byte_of(li, 2 * ds + hh);
     // transpose read: inside a 16-lane group lane s fetches 4 elements of row
     // (s/4), columns 4*(s%4)..; the group ends up holding column (s) x 4 rows.
     const int s16 = lane & 15, grp = lane >> 4;
-    int voff[NDB];
+    uint32_t vaddr[NDB];
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
-        voff[db] = VT::byte_of(4 * hh + s16 / 4, 4 * db + 2 * (grp & 1) + ((s16 & 3) >> 1)) +
+        vaddr[db] = lds_addr_of(sm.v[0]) + VT::byte_of(4 * hh + s16 / 4, 4 * db + 2 * (grp & 1) + ((s16 & 3) >> 1)) +
                    8 * (s16 & 1);
 
     // the k-tile list is fetched 64 entries at a time, one per lane, and read back
@@ -163,8 +171,180 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // drain the tile transfers, which it cannot see).
     wait_vmcnt<0>();
 
-    // prologue: tiles 0 .. NST-2 in flight; pend[] holds their list entries
-    uint32_t pend[NST - 1];
+    // ---- software pipeline over half tiles (32 keys) ---------------------------------
+    // While the probabilities of one half tile are exponentiated and multiplied into
+    // O, the scores of the next half tile are already being formed, so the matrix
+    // and the vector pipes of a wave overlap.  Tiles j and j+1 are resident, up to
+    // NST-2 more are in flight.  With two wavefronts per SIMD the LDS latency has to
+    // be covered inside the wave: every operand fragment is requested NKF matrix
+    // instructions before its use, and the order below is pinned slot by slot
+    // (one MFMA, one fragment request, one slice of vector work per slot).
+    static_assert(NST >= 3, "the pipeline needs two resident tiles and one in flight");
+    constexpr int NKF = NDS / 2;           // fragments in flight; equals NDB
+    static_assert(NKF == NDB, "slot plan assumes head_dim/32 fragments in flight");
+    constexpr int EPS = 16 / NDS;          // probabilities formed per S slot
+#define MM_SLOT_END() __builtin_amdgcn_sched_barrier(0)
+    // `off`: byte offset of the half tile from stage 0 of its ring (compile-time once unrolled)
+    auto read_k = [&](int off, int ds) __attribute__((always_inline)) -> bf16x8 {
+        return __builtin_bit_cast(bf16x8, *(lds_u4)(uintptr_t)(kaddr[ds] + (uint32_t)off));
+    };
+    auto read_v = [&](int off, int ks, int db) __attribute__((always_inline)) -> bf16x8 {
+        const uint32_t p0 = vaddr[db] + (uint32_t)(off + ks * 16 * RB);
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)p0);
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)(p0 + 8 * RB));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // max over the two half-waves (lanes l and l^32 hold the same query)
+    auto pair_max = [&](float x) __attribute__((always_inline)) -> float {
+        // both copies go in equal; the swap leaves the lower half-wave's values in
+        // one register and the upper half-wave's in the other, in all 64 lanes
+        float a = x, b = x;
+        asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+        return fmaxf(a, b);
+    };
+    // raw scores of keys 32*kb .. +31 of the tile in `stage` (prologue only)
+    auto scores = [&](int off, floatx16& s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) s = mfma32(read_k(off, ds), qf[ds], s);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] *= scale_log2;
+    };
+    auto mask_scores = [&](uint32_t entry, int parity, int kb, floatx16& s) __attribute__((always_inline)) {
+        if (entry & kPartialFlag) {            // workgroup-uniform
+            const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kl = kb * 32 + c_row(r, hh);
+                if (!visible(q_ss, q_causal, q_pos, sm.kss[parity][kl], k0 + kl)) s[r] = -INFINITY;
+            }
+        }
+    };
+    // Softmax is invariant under a per-query shift of the scores, so the shift m_run only
+    // has to keep 2^(s - m_run) inside the fp32/bf16 exponent range.  It starts at 0 and
+    // follows the true running maximum m_true only when the two drift more than
+    // kShiftSlack apart: for ordinary score magnitudes it stays 0 and the probabilities
+    // are plain exp2 of the scaled scores, with no per-element subtraction.
+    // The scores of the half tile leave this function already shifted.
+    auto new_max = [&](float m_loc, floatx16& s) __attribute__((always_inline)) {
+        m_true = fmaxf(m_true, m_loc);
+        // an all-masked prefix (m_true = -inf) keeps the shift
+        const bool move = m_true != -INFINITY && fabsf(m_true - m_run) > kShiftSlack;
+        if (__any(move)) {
+            const float m_new = move ? m_true : m_run;
+            // lowering by more than the exponent range only happens while O and l are still 0
+            const float alpha = __builtin_amdgcn_exp2f(fminf(m_run - m_new, 126.f));
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+            m_run = m_new;
+        }
+        if (__any(m_run != 0.f)) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] -= m_run;
+        }
+    };
+    // key words of a PARTIAL tile into sm.kss[parity] (followed by a barrier)
+    auto stage_keys = [&](uint32_t entry, int parity) __attribute__((always_inline)) {
+        if (entry & kPartialFlag) {            // workgroup-uniform
+            const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
+            if (tid < kFwdBN) sm.kss[parity][tid] = word_ss(bits[k0 + tid]);
+            __syncthreads();
+        }
+    };
+    // One pipeline step.  kf[] holds the first NKF K fragments of the NEXT half tile
+    // (at kn) on entry and those of the half tile after it (at kp) on exit.  The
+    // step is a sequence of NDS + 2*NDB slots, each one MFMA, one fragment request
+    // and an even share of the vector work: a wave cannot issue for some cycles after
+    // an MFMA and the matrix pipe is busy for 32, so about four plain vector
+    // instructions per slot are free and more stretch the slot.
+    auto step = [&](int kn, floatx16& s_next, const floatx16& s_cur, int vb, int kp, bf16x8 (&kf)[NKF],
+                    uint32_t e_next, int parity_next, int kb_next, bool live_next) __attribute__((always_inline)) {
+        constexpr int PPS = EPS / 2;       // probability pairs exponentiated per S slot
+        constexpr int MPS = 16 / NDB;      // scores scaled per early / folded into the maximum per late PV slot
+        constexpr int DPS = 8 / NDB;       // row-sum updates per late PV slot
+        bf16x8 vf[NKF], pf0, pf1;
+        float ef[16];                      // exp2 of the current scores
+        uint32_t pw[8];                    // the same as bf16 pairs, in score-register order
+        float m_loc = -INFINITY;
+        // The empty asm statements tie each slice of vector work to its slot: without
+        // them the compiler gathers the slices where their results are consumed.
+        MM_SLOT_END();
+#pragma unroll
+        for (int t = 0; t < NDS + 2 * NDB; ++t) {
+            // ---- matrix instruction and the fragment request that refills its operand ----
+            if (t < NDS) {
+                if (t == 0) {
+                    floatx16 z;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                    s_next = mfma32(kf[0], qf[0], z);
+                } else {
+                    s_next = mfma32(kf[t % NKF], qf[t], s_next);
+                }
+                if (t < NKF) kf[t] = read_k(kn, NKF + t);
+                else vf[t - NKF] = read_v(vb, 0, t - NKF);
+            } else if (t < NDS + NDB) {        // keys 0..15 of the half tile
+                if (t == NDS) pf0 = __builtin_bit_cast(bf16x8, u32x4{pw[0], pw[1], pw[2], pw[3]});
+                o[t - NDS] = mfma32(vf[t - NDS], pf0, o[t - NDS]);
+                vf[t - NDS] = read_v(vb, 1, t - NDS);
+            } else {                           // keys 16..31; next step's K fragments
+                if (t == NDS + NDB) pf1 = __builtin_bit_cast(bf16x8, u32x4{pw[4], pw[5], pw[6], pw[7]});
+                o[t - NDS - NDB] = mfma32(vf[t - NDS - NDB], pf1, o[t - NDS - NDB]);
+                kf[t - NDS - NDB] = read_k(kp, t - NDS - NDB);
+            }
+            // ---- vector work ----
+            if (t >= 1 && t <= NDS) {          // round the previous slot's exponentials to bf16
+#pragma unroll
+                for (int u = 0; u < PPS; ++u) {
+                    const int pr = (t - 1) * PPS + u;
+                    const bf16x2 pb = {(__bf16)ef[2 * pr], (__bf16)ef[2 * pr + 1]};
+                    pw[pr] = __builtin_bit_cast(uint32_t, pb);
+                    asm volatile("" : "+v"(pw[pr]));
+                }
+            }
+            if (t < NDS) {
+#pragma unroll
+                for (int u = 0; u < EPS; ++u) {
+                    const int r = t * EPS + u;
+                    ef[r] = __builtin_amdgcn_exp2f(s_cur[r]);
+                    asm volatile("" : "+v"(ef[r]));
+                }
+            } else if (t < NDS + NDB) {
+                // the finished scores become exponents of 2
+#pragma unroll
+                for (int u = 0; u < MPS; ++u) {
+                    const int r = (t - NDS) * MPS + u;
+                    s_next[r] *= scale_log2;
+                    asm volatile("" : "+v"(s_next[r]));
+                }
+            } else {
+                // row sums of the bf16-rounded probabilities (what the PV product sees)
+#pragma unroll
+                for (int u = 0; u < DPS; ++u) {
+                    const int pr = (t - NDS - NDB) * DPS + u;
+                    l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[pr]),
+                                                            bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l_run, false);
+                }
+#pragma unroll
+                for (int u = 0; u < MPS; ++u) m_loc = fmaxf(m_loc, s_next[(t - NDS - NDB) * MPS + u]);
+                asm volatile("" : "+v"(l_run), "+v"(m_loc));
+            }
+            MM_SLOT_END();
+            if (t == NDS + NDB - 1) mask_scores(e_next, parity_next, kb_next, s_next);
+        }
+        if (live_next) new_max(pair_max(m_loc), s_next);   // past the last tile the scores are stale data
+    };
+    auto wait_landed = [&](int younger) __attribute__((always_inline)) {
+        if (younger >= 2) wait_vmcnt<4 * NI>();
+        else if (younger == 1) wait_vmcnt<2 * NI>();
+        else wait_vmcnt<0>();
+    };
+
+    uint32_t pend[NST - 1];                // list entries of tiles j .. j+NST-2
 #pragma unroll
     for (int j = 0; j < NST - 1; ++j) {
         pend[j] = 0u;
@@ -173,117 +353,60 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             issue_tile(pend[j], j);
         }
     }
-
-    int st = 0;                            // stage of tile `it`
-    for (int it = 0; it < n_active; ++it) {
-        const uint32_t entry = pend[0];
-        const bool partial = (entry & kPartialFlag) != 0;
-        const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
-        // tile `it` has landed once at most the transfers of the younger tiles remain
-        const int younger = min(NST - 2, n_active - 1 - it);
-        if (younger >= 2) wait_vmcnt<(NST > 3 ? 4 * NI : 0)>();
-        else if (younger == 1) wait_vmcnt<(NST > 2 ? 2 * NI : 0)>();
-        else wait_vmcnt<0>();
-        __syncthreads();                   // everyone's share landed; stage of tile it-1 is free
-        uint32_t fresh = 0u;
-        if (it + NST - 1 < n_active) {
-            if (((it + NST - 1) & 63) == 0) {
-                // next 64 list entries (this vector load also drains the transfers in flight)
-                const int j = it + NST - 1 + lane;
-                list_chunk = j < n_active ? klist[j] : 0u;
-                wait_vmcnt<0>();           // awaited here so that no wait is needed after the branch
-            }
-            fresh = entry_at(it + NST - 1);
-            int sn = st + NST - 1;
-            if (sn >= NST) sn -= NST;
-            issue_tile(fresh, sn);
-        }
-#pragma unroll
-        for (int j = 0; j + 1 < NST - 1; ++j) pend[j] = pend[j + 1];
-        pend[NST - 2] = fresh;
-        if (partial && tid < kFwdBN) sm.kss[tid] = word_ss(bits[k0 + tid]);
-        const unsigned char* kb_base = sm.k[st];
-        const unsigned char* vb_base = sm.v[st];
-
-        // ---- S^T = K Q^T --------------------------------------------------------
-        floatx16 s[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-            for (int ds = 0; ds < NDS; ++ds) {
-                const bf16x8 a = __builtin_bit_cast(
-                    bf16x8, *(const u32x4*)(kb_base + kb * 32 * RB + koff[ds]));
-                s[kb] = mfma32(a, qf[ds], s[kb]);
-            }
-        }
-        // ---- mask ----------------------------------------------------------------
-        if (partial) {
-            __syncthreads();               // key words of this tile are in LDS (workgroup-uniform branch)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kl = kb * 32 + c_row(r, hh);
-                    if (!visible(q_ss, q_causal, q_pos, sm.kss[kl], k0 + kl)) s[kb][r] = -INFINITY;
-                }
-        }
-        // ---- online softmax (base 2) ---------------------------------------------
+    floatx16 s_a, s_b;                     // scores of the current / next half tile, alternating
+    bf16x8 kf[NKF];                        // leading K fragments of the next half tile
+    if (n_active > 0) {
+        wait_landed(min(NST - 2, n_active - 1));
+        __syncthreads();
+        stage_keys(pend[0], 0);
+        scores(0, s_a);
+        mask_scores(pend[0], 0, 0, s_a);
         float m_loc = -INFINITY;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int r = 0; r < 16; ++r) m_loc = fmaxf(m_loc, s_a[r]);
+        new_max(pair_max(m_loc), s_a);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) m_loc = fmaxf(m_loc, s[kb][r]);
-        m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
-        const float m_cand = fmaxf(m_run, m_loc * scale_log2);
-        // (-inf) - (-inf) is NaN and compares false: an all-masked prefix keeps -inf
-        const float m_new = (m_cand - m_run > kRescaleThreshold) ? m_cand : m_run;
-        if (__any(m_new != m_run)) {
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-            m_run = m_new;
-        }
-        const float m_use = m_run == -INFINITY ? 0.f : m_run;
-        bf16x8 pf[4];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(s[kb][r] * scale_log2 - m_use);
-                pf[kb * 2 + (r >> 3)][r & 7] = (__bf16)p;
-            }
-        // row sums of the bf16-rounded probabilities (what the PV product sees)
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const bf16x2 pr = {pf[ks][2 * u], pf[ks][2 * u + 1]};
-                l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l_run, false);
-            }
-        // ---- O^T += V^T P^T --------------------------------------------------------
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-            for (int db = 0; db < NDB; ++db) {
-                typedef short shortx4 __attribute__((ext_vector_type(4)));
-                typedef shortx4 __attribute__((address_space(3))) * lds_s4;
-                const unsigned char* p0 = vb_base + ks * 16 * RB + voff[db];
-                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)p0);
-                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(p0 + 8 * RB));
-                const bf16x8 a = __builtin_bit_cast(
-                    bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                o[db] = mfma32(a, pf[ks], o[db]);
-            }
-        }
-        if (++st == NST) st = 0;
+        for (int i = 0; i < NKF; ++i) kf[i] = read_k(32 * RB, i);
     }
-
+    // The ring position of tile j is j mod NST; the loop is unrolled NST-fold so that
+    // every stage index below is a compile-time constant.
+    for (int j0 = 0; j0 < n_active; j0 += NST) {
+#pragma unroll
+        for (int st = 0; st < NST; ++st) {
+            const int j = j0 + st;
+            if (j >= n_active) break;
+            constexpr int kHalf = 32 * RB;
+            const int st1 = (st + 1) % NST, sn = (st + NST - 1) % NST;
+            const bool more = j + 1 < n_active;
+            // tile j+1 has landed once at most the transfers of the tiles after it remain
+            wait_landed(max(0, min(NST - 3, n_active - 2 - j)));
+            __syncthreads();               // everyone's share landed; stage of tile j-1 is free
+            uint32_t fresh = 0u;
+            if (j + NST - 1 < n_active) {
+                if (((j + NST - 1) & 63) == 0) {
+                    // next 64 list entries (this vector load also drains the transfers in flight)
+                    const int i = j + NST - 1 + lane;
+                    list_chunk = i < n_active ? klist[i] : 0u;
+                    wait_vmcnt<0>();       // awaited here so that no wait is needed after the branch
+                }
+                fresh = entry_at(j + NST - 1);
+                issue_tile(fresh, sn);
+            }
+            const uint32_t e_cur = pend[0], e_next = pend[1];
+#pragma unroll
+            for (int i = 0; i + 1 < NST - 1; ++i) pend[i] = pend[i + 1];
+            pend[NST - 2] = fresh;
+            // first half of tile j (scores in s_a) while the second half's scores form in s_b
+            step(st * kStageBytes + kHalf, s_b, s_a, st * kStageBytes, st1 * kStageBytes, kf, e_cur, j & 1,
+                 1, true);
+            // second half of tile j while the first half of tile j+1 forms in s_a (stale but
+            // harmless data past the last tile)
+            if (more) stage_keys(e_next, (j + 1) & 1);
+            step(st1 * kStageBytes, s_a, s_b, st * kStageBytes + kHalf, st1 * kStageBytes + kHalf, kf,
+                 more ? e_next : 0u, (j + 1) & 1, 0, more);
+        }
+    }
+#undef MM_SLOT_END
     // ---- epilogue -----------------------------------------------------------------
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
@@ -366,11 +489,11 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
     const bool pair = (a.Hq / a.Hkv) % 2 == 0;     // two heads of a KV group per workgroup
     stage_begin(MMATTN_STAGE_FWD, st);
     if (a.D == 128) {
-        if (pair) launch_fwd_kernel<128, 2, 3>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
-        else      launch_fwd_kernel<128, 1, 2>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
+        if (pair) launch_fwd_kernel<128, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
+        else      launch_fwd_kernel<128, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
     } else {
-        if (pair) launch_fwd_kernel<64, 2, 3>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
-        else      launch_fwd_kernel<64, 1, 2>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
+        if (pair) launch_fwd_kernel<64, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
+        else      launch_fwd_kernel<64, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
     }
     stage_end(MMATTN_STAGE_FWD, st);
     MM_LAUNCH_CHECK();

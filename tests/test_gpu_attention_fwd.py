@@ -1,6 +1,9 @@
 """GPU parity, attention forward (through the C ABI) against the float64
 oracle.  Tolerances (bf16 inputs, fp32 accumulation, bf16 output): max-abs
-2e-2 and relative L2 5e-3 on O; LSE within 2e-3 absolute."""
+2e-2 and relative L2 5e-3 on O.  The kernel sums the bf16-rounded probabilities
+(the ones its PV product uses, so that O is normalised consistently); a bf16
+rounding is off by at most 2^-8 relative, hence so is the row sum, and LSE
+(natural log) by at most 2^-8 = 3.9e-3 plus fp32 noise: 4.5e-3 absolute."""
 import numpy as np
 import pytest
 import torch
@@ -15,7 +18,7 @@ from gpu_util import (DEV, bf16_to_f64, f64, fields, gpu_bits, make_tensors, max
 
 pytestmark = pytest.mark.gpu
 
-TOL_MAX, TOL_L2, TOL_LSE = 2e-2, 5e-3, 2e-3
+TOL_MAX, TOL_L2, TOL_LSE = 2e-2, 5e-3, 4.5e-3
 
 
 def run_case(lay, blocks, block, Hq, Hkv, D, seed, heads=None, rows_sample=None):
