@@ -48,9 +48,7 @@ def plan_on_gpu(w, device):
     lay = w.layout
     bits = mb.mask_encode(lay.spans, lay.sample_off, lay.S, device=device, flags=lay.noncausal)
     _, _, W = mb.tile_map(bits, w.N_B, w.N_B, want_cls=False)
-    rob, load, off, rblocks = mb.balance(W, w.P)
-    load_h = load.cpu().numpy().view(np.uint64)
-    off_h = off.cpu().numpy()
+    _, _, _, rblocks, load_h, off_h = mb.balance(W, w.P, host=True)
     return bits, W, rblocks, load_h, off_h
 
 

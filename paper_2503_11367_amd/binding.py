@@ -129,19 +129,26 @@ def tile_map(bits: torch.Tensor, tq: int, tk: int, stream=None, want_cls=True, w
     return cls, cnt, rp
 
 
-def balance(W: torch.Tensor, P: int, stream=None):
+def balance(W: torch.Tensor, P: int, stream=None, host: bool = False):
     """mmattn_balance -> (rank_of_block int32[nB], load int64[P], rank_off
-    int32[P+1], rank_blocks int32[nB])."""
+    int32[P+1], rank_blocks int32[nB]).  load and rank_off share one
+    allocation; with host=True two more items follow, their host copies
+    (uint64 / int32 numpy arrays) fetched with a single device-to-host copy."""
     nB = W.numel()
     dev = W.device
+    Pn = max(P, 1)
     rob = torch.empty(nB, dtype=torch.int32, device=dev)
-    load = torch.empty(max(P, 1), dtype=torch.int64, device=dev)
-    off = torch.empty(max(P, 1) + 1, dtype=torch.int32, device=dev)
+    both = torch.empty(8 * Pn + 4 * (Pn + 1), dtype=torch.uint8, device=dev)
+    load = both[:8 * Pn].view(torch.int64)
+    off = both[8 * Pn:].view(torch.int32)
     blocks = torch.empty(nB, dtype=torch.int32, device=dev)
     rc = lib().mmattn_balance(_ptr(W), nB, P, _ptr(rob), _ptr(load), _ptr(off), _ptr(blocks),
                               _stream(stream))
     _check("mmattn_balance", rc)
-    return rob, load, off, blocks
+    if not host:
+        return rob, load, off, blocks
+    h = both.cpu().numpy()
+    return rob, load, off, blocks, h[:8 * Pn].view("<u8"), h[8 * Pn:].view("<i4")
 
 
 def fwd(q_loc: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bits: torch.Tensor,

@@ -173,6 +173,7 @@ struct TilePlan {
     int32_t* kcount;
     uint32_t* klist;
     int32_t* qorder;
+    int32_t* ticket;     // zeroed counter used by the list builder (one per plan)
 };
 
 // transposed plan for key-outer kernels: for each k-tile the active q-tiles
@@ -182,10 +183,12 @@ struct TilePlanT {
     int32_t* qcount;     // [nk]
     uint32_t* qlist;     // [nk][nq]
     int32_t* korder;     // [nk] by qcount descending
+    int32_t* ticket;
 };
 
-int launch_transpose_perm(const void* x, void* xt, int64_t n, int64_t n_pad, int32_t H, int32_t D,
-                          hipStream_t st);
+// int32 words cleared by launch_validate_blocks at `err`: the error flag, then one
+// ticket per tile plan of the call
+constexpr int kFlagInts = 4;
 int launch_compact_rows(const TilePlan& p, hipStream_t st);
 int launch_compact_cols(const TilePlanT& p, hipStream_t st);
 int launch_validate_blocks(const int32_t* blocks, int32_t n_blocks, int64_t n_seq_blocks,

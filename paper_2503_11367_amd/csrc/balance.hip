@@ -25,16 +25,35 @@ __device__ __forceinline__ bool key_less(const MinKey& a, const MinKey& b) {
     return a.load < b.load || (a.load == b.load && a.rank < b.rank);
 }
 
+// minimum of v over the 64 lanes, returned wave-uniform: prefix minima inside each
+// row of 16 lanes (row_shr 1,2,4,8), then lane 15 of a row into the next row
+// (row_bcast:15) and lane 31 into the upper half (row_bcast:31); lane 63 ends up
+// with the minimum.  Lanes without a source keep the identity.
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    constexpr int kId = -1;                 // 0xFFFFFFFF, identity of the unsigned minimum
+#define MM_MIN_DPP(ctrl, rows)                                                                  \
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp(kId, (int)v, ctrl, rows, 0xf, false))
+    MM_MIN_DPP(0x111, 0xf);                 // row_shr:1
+    MM_MIN_DPP(0x112, 0xf);                 // row_shr:2
+    MM_MIN_DPP(0x114, 0xf);                 // row_shr:4
+    MM_MIN_DPP(0x118, 0xf);                 // row_shr:8
+    MM_MIN_DPP(0x142, 0xa);                 // row_bcast:15 into rows 1 and 3
+    MM_MIN_DPP(0x143, 0xc);                 // row_bcast:31 into rows 2 and 3
+#undef MM_MIN_DPP
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// lexicographic minimum of (load, rank) over the wavefront: three 32-bit minima,
+// each restricted to the lanes that tie on the more significant parts
 __device__ __forceinline__ MinKey wave_min(MinKey k) {
-    for (int off = 32; off > 0; off >>= 1) {
-        MinKey o;
-        uint32_t lo = __shfl_xor((uint32_t)k.load, off);
-        uint32_t hi = __shfl_xor((uint32_t)(k.load >> 32), off);
-        o.load = ((uint64_t)hi << 32) | lo;
-        o.rank = __shfl_xor(k.rank, off);
-        if (key_less(o, k)) k = o;
-    }
-    return k;
+    const uint32_t hi = (uint32_t)(k.load >> 32), lo = (uint32_t)k.load;
+    const uint32_t hi_min = wave_min_u32(hi);
+    const uint32_t lo_min = wave_min_u32(hi == hi_min ? lo : 0xFFFFFFFFu);
+    const bool tie = hi == hi_min && lo == lo_min;
+    MinKey r;
+    r.load = ((uint64_t)hi_min << 32) | lo_min;
+    r.rank = wave_min_u32(tie ? k.rank : 0xFFFFFFFFu);
+    return r;
 }
 
 __global__ void __launch_bounds__(kBalThreads)
@@ -74,9 +93,9 @@ balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
             const uint64_t my_w = t < nB ? W[my_b] : 0;
             const int n = min(kWave, nB - t0);
             for (int u = 0; u < n; ++u) {
-                const int32_t b = __shfl(my_b, u);
-                const uint32_t wlo = __shfl((uint32_t)my_w, u);
-                const uint32_t whi = __shfl((uint32_t)(my_w >> 32), u);
+                const int32_t b = __builtin_amdgcn_readlane(my_b, u);
+                const uint32_t wlo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)my_w, u);
+                const uint32_t whi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(my_w >> 32), u);
                 const uint64_t w = ((uint64_t)whi << 32) | wlo;
                 const MinKey best = wave_min(local);
                 const uint32_t g = best.rank;

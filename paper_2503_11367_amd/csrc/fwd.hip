@@ -476,6 +476,7 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
     plan.kcount = (int32_t*)(base + L.kcount);
     plan.klist = (uint32_t*)(base + L.klist);
     plan.qorder = (int32_t*)(base + L.qorder);
+    plan.ticket = err + 1;
 
     int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
     if (rc) return rc;
