@@ -30,7 +30,7 @@ namespace mm {
 
 // ---------------------------------------------------------------- prep -------
 // One thread per 8 elements; D/8 consecutive lanes reduce one (row, head).
-//   ld[Hq][n_pad][2] = (LSE in base-2 units, Delta = rowsum(dO o O)); rows
+//   ld[Hq][2][n_pad] = LSE in base-2 units, then Delta = rowsum(dO o O), per head; rows
 //                      n_loc .. n_pad-1 are padding: LSE = +inf (probability 0), Delta = 0
 //   qh, doh [Hq][n_pad][D]  head-major copies of Q and dO (padding rows zero) for the
 //                      key-outer pass: there a tile is 64 consecutive rows of ONE head,
@@ -69,9 +69,9 @@ bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
         *(u32x4*)(qh + e) = qv;
         *(u32x4*)(doh + e) = dv;
         if (c == 0) {
-            float* out = ld + ((int64_t)h * n_pad + row) * 2;
+            float* out = ld + (int64_t)h * 2 * n_pad + row;
             out[0] = ok ? lse[(int64_t)h * n_loc + row] * kLog2e : INFINITY;
-            out[1] = ok ? acc : 0.f;
+            out[n_pad] = ok ? acc : 0.f;
         }
     }
 }
@@ -93,28 +93,32 @@ __device__ __forceinline__ void dma4(const void* base_uniform, uint32_t off, uin
 // Key-outer pass with role-specialised wavefronts.  A workgroup owns 128 keys of
 // one KV head; for each 32-key block there is a "V wave" and a "K wave" (8
 // wavefronts, the two of a block share a SIMD).  A step is 64 query rows of one
-// head (two 32-row sub-blocks, independent instruction streams inside a wave):
-//   V wave, step i:    S = Q K^T -> P = exp2(S - LSE) (masked) -> bf16;
+// head, handled as two units of 32 rows:
+//   V wave, unit u:    S = Q K^T -> P = exp2(S - LSE) (masked) -> bf16;
 //                      dV^T += dO^T P;   P goes to LDS for its partner;
-//   K wave, step i-1:  dP = dO V^T;  dS = P o (dP - Delta);  dK^T += Q^T dS.
+//   K wave, one step later:  dP = dO V^T;  dS = P o (dP - Delta);  dK^T += Q^T dS.
 // The K wave runs one step behind, so one workgroup barrier per step orders the
-// P hand-over, and neither role needs both accumulators: registers stay below
-// the 256 a two-waves-per-SIMD kernel may use, with K and V fragments resident.
+// P hand-over, and neither role needs both accumulators.  Inside a wave the units
+// form a software pipeline like the forward kernel's: while the element-wise work
+// of unit u runs, the first product of unit u+1 (S or dP) is already being formed,
+// then the second product of unit u follows; operand fragments are requested a
+// few MFMAs ahead and the instruction order is pinned slot by slot.
+// Rings: Q tiles of steps i-1 (K wave), i, i+1 (V wave) are resident while
+// i+2 lands: 4 stages, unrolled so that their LDS offsets are immediates; dO
+// tiles of steps i-1, i are resident while i+1 lands: 3 stages, addressed
+// through per-iteration base registers.
 constexpr int kKvBN = 128;      // keys per workgroup
 constexpr int kKvBM = 64;       // query rows per step
-constexpr int kKvSub = kKvBM / 32;
 constexpr int kKvThreads = 512;
-#ifndef MM_KV_NST
-#define MM_KV_NST 3             // LDS ring stages for the Q/dO tiles (prefetch distance NST-2)
-#endif
-constexpr int kKvNST = MM_KV_NST;
+constexpr int kKvQst = 4;       // Q ring stages
+constexpr int kKvDst = 3;       // dO ring stages
 
 template <int D>
 struct KvSmem {
-    alignas(1024) unsigned char q[kKvNST][kKvBM * D * 2];       // MODE 0: rows and transpose
-    alignas(1024) unsigned char d[kKvNST][kKvBM * D * 2];
-    alignas(1024) unsigned char p[2][4][64 * 32 * kKvSub];      // P hand-over: [parity][key block][sub][lane] 2 x 16 B
-    alignas(256) float ld[kKvNST][8][2 * kKvBM];                // per wave: (lse2, delta) of the step's rows
+    alignas(1024) unsigned char q[kKvQst][kKvBM * D * 2];       // MODE 0: rows and transpose
+    alignas(1024) unsigned char d[kKvDst][kKvBM * D * 2];
+    alignas(1024) unsigned char p[2][4][2 * 64 * 32];           // P hand-over: [step parity][key block][unit][lane] 2 x 16 B
+    alignas(256) float ld[kKvQst][2][kKvBM];                    // lse2 and delta of a step's rows
     uint32_t q_ss[kKvBM];                                       // mask fields of a PARTIAL step's rows
     uint32_t q_causal[kKvBM];
     int32_t q_pos[kKvBM];
@@ -139,13 +143,16 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
            float* __restrict__ accV) {
     constexpr int NDS = D / 16, NDB = D / 32;
     constexpr int RB = D * 2;
-    constexpr int NST = kKvNST;
     using QT = SwzTile<D, 0>;
     constexpr int NI = kKvBM * RB / 1024 / 8;          // 1 KiB transfers per wave per tensor per step
     constexpr int kStage = kKvBM * RB;
+    constexpr int kUnit = 32 * RB;                     // bytes of a unit's 32 rows
     static_assert(NI >= 1, "head_dim");
-    constexpr int kPerStep = 2 * NI + kKvSub;          // + the (lse2, delta) rows, 32 per transfer
-    static_assert(NST >= 3 && NST <= 8 && (NST - 3) * kPerStep < 64, "ring depth");
+    constexpr int NKF = NDS / 2;                       // fragments in flight; equals NDB
+    static_assert(NKF == NDB, "slot plan assumes head_dim/32 fragments in flight");
+    constexpr int NS = NDS + 2 * NDB;                  // slots (MFMAs) per unit
+    constexpr int SLV = NDS + NDB - 1;                 // slots that carry element-wise work
+    constexpr int PER = 16 * QT::RPS, NV = PER / 8;    // transpose-read address period
     __shared__ KvSmem<D> sm;
     if (*err) return;
 
@@ -198,7 +205,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
-    // ---- transfers -------------------------------------------------------------------
+    // ---- transfers (all 8 wavefronts share every tile) ------------------------------
     uint32_t tr_off[NI];                               // byte offset inside a (head-major) tile this lane fetches
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
@@ -208,38 +215,71 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     }
     const uint32_t lds_q = lds_addr_of(sm.q[0]) + (wave * NI) * 1024;
     const uint32_t lds_d = lds_addr_of(sm.d[0]) + (wave * NI) * 1024;
-    const uint32_t lds_ld = lds_addr_of(sm.ld[0][0]) + wave * (8 * kKvBM);
-    auto issue_step = [&](uint32_t entry, int hq, int stage) {
+    const uint32_t lds_ld = lds_addr_of(sm.ld[0][0]);
+    auto issue_q = [&](uint32_t entry, int hq, int stage) {     // Q tile and the rows' (lse2, delta)
         const int64_t r0 = (int64_t)(entry & ~kPartialFlag) * kKvBM;
-        const int64_t tile = ((int64_t)hq * n_pad + r0) * D;   // 64 consecutive rows, padded with zeros
+        const int64_t tile = ((int64_t)hq * n_pad + r0) * D;    // 64 consecutive rows, padded with zeros
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            dma16(Qh + tile, tr_off[i], lds_q + stage * kStage + i * 1024);
-            dma16(dOh + tile, tr_off[i], lds_d + stage * kStage + i * 1024);
-        }
-        // (lse2, delta) pairs of the step's rows: contiguous in the padded array, 32 rows per transfer
-        const float* lb = ld_g + ((int64_t)hq * n_pad + r0) * 2;
+        for (int i = 0; i < NI; ++i) dma16(Qh + tile, tr_off[i], lds_q + stage * kStage + i * 1024);
+        if (wave < 2)                                           // wave 0: lse2 rows, wave 1: delta rows
+            dma4(ld_g + ((int64_t)hq * 2 + wave) * n_pad + r0, (uint32_t)(lane * 4),
+                 lds_ld + stage * (8 * kKvBM) + wave * (4 * kKvBM));
+    };
+    auto issue_d = [&](uint32_t entry, int hq, int stage) {
+        const int64_t r0 = (int64_t)(entry & ~kPartialFlag) * kKvBM;
+        const int64_t tile = ((int64_t)hq * n_pad + r0) * D;
 #pragma unroll
-        for (int sb = 0; sb < kKvSub; ++sb)
-            dma4(lb + sb * 64, (uint32_t)(lane * 4), lds_ld + stage * (8 * 8 * kKvBM) + sb * 256);
+        for (int i = 0; i < NI; ++i) dma16(dOh + tile, tr_off[i], lds_d + stage * kStage + i * 1024);
     };
 
     // Step s is query tile qlist[n_q-1 - s%n_q] of head head0 + s/n_q: every k-tile
     // of a head walks the query tiles from the last one down, so the workgroups
     // that are resident together read the same Q/dO tiles at about the same time
     // and share them in L2.  The list is fetched 64 entries at a time, one per lane,
-    // and read back with readlane; the head of the next step advances incrementally.
+    // and read back with readlane.
     auto fetch_chunk = [&](int first_step) -> uint32_t {
         const int s_ = first_step + lane;
         return s_ < n_steps ? qlist[n_q - 1 - s_ % n_q] : 0u;
     };
     uint32_t list_chunk = n_steps > 0 ? fetch_chunk(0) : 0u;
-    int hq_next = head0;                                       // head of the step to issue next
-    int qi_next = 0;                                           // its position in the walk
-    RowFragAddr<QT, D> qrow;      // Q and dO tiles share layout and lane pattern
-    TrFragAddr<QT, D> qtr;
-    qrow.init(lane);
-    qtr.init(lane);
+    int hq_next = head0;                               // head of the step whose Q tile is issued next
+    int qi_next = 0;                                   // its position in the walk
+
+    // ---- fragment addresses (LDS byte addresses at ring stage 0) ---------------------
+    // row fragments feed the first product (V role: Q ring, K role: dO ring), transpose
+    // fragments the second (V role: dO ring, K role: Q ring)
+    uint32_t row_addr[NDS], tr_addr[NDB][NV];
+    {
+        RowFragAddr<QT, D> fr;
+        TrFragAddr<QT, D> ft;
+        fr.init(lane);
+        ft.init(lane);
+        const uint32_t rbase = lds_addr_of(k_role ? sm.d[0] : sm.q[0]);
+        const uint32_t tbase = lds_addr_of(k_role ? sm.q[0] : sm.d[0]);
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) row_addr[ds] = rbase + (uint32_t)fr.off[ds];
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int v = 0; v < NV; ++v) tr_addr[db][v] = tbase + (uint32_t)ft.off[db][v];
+    }
+    // P hand-over slot of this lane, and the row constants (4 consecutive rows per 16-byte
+    // read: lse2 for the V role, delta for the K role)
+    const uint32_t p_addr = lds_addr_of(sm.p[0][kblk]) + lane * 32;
+    const uint32_t rc_addr = lds_ld + (k_role ? 4 * kKvBM : 0) + hh * 16;
+
+    auto read_row = [&](uint32_t a, int imm) __attribute__((always_inline)) -> bf16x8 {
+        return __builtin_bit_cast(bf16x8, *(lds_u4)(uintptr_t)(a + (uint32_t)imm));
+    };
+    // transpose fragment of rows ks*16.. (ks counted inside the 64-row tile), columns db*32..
+    auto read_tr = [&](const uint32_t (&a)[NDB][NV], int imm, int ks, int db) __attribute__((always_inline)) -> bf16x8 {
+        const int r_lo = ks * 16, r_hi = ks * 16 + 8;
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)(
+            a[db][(r_lo % PER) / 8] + (uint32_t)(imm + (r_lo / PER) * PER * RB)));
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)(
+            a[db][(r_hi % PER) / 8] + (uint32_t)(imm + (r_hi / PER) * PER * RB)));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
 
     // Every ordinary vector load issued so far (resident fragments, mask word, list
     // chunk) is awaited here, once: the compiler then has nothing pending when the
@@ -247,53 +287,166 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     // drain the tile transfers, which it cannot see).
     wait_vmcnt<0>();
 
-    // prologue: steps 0 .. NST-3 in flight; pend[] holds the list entries of the steps
-    // i-1 (K role's), i (V role's) and the ones in flight
-    uint32_t pend[NST - 1];
-#pragma unroll
-    for (int j = 0; j < NST - 1; ++j) pend[j] = 0u;
-#pragma unroll
-    for (int j = 0; j < NST - 2; ++j)
-        if (j < n_steps) {
-            pend[j + 1] = __builtin_amdgcn_readlane(list_chunk, j);
-            issue_step(pend[j + 1], hq_next, j);
+    // prologue: Q tiles of steps 0 and 1 and the dO tile of step 0; ent[] holds the
+    // list entries of steps i, i+1, i+2 and hq_d the head of the next dO tile
+    uint32_t ent[3] = {0u, 0u, 0u};
+    int hq_d = head0, hq_d1 = head0;                   // heads of steps i+1 and i+2 (dO is issued one step after Q)
+    if (n_steps > 0) {
+        ent[0] = __builtin_amdgcn_readlane(list_chunk, 0);
+        issue_q(ent[0], hq_next, 0);
+        issue_d(ent[0], hq_next, 0);
+        if (++qi_next == n_q) { qi_next = 0; ++hq_next; }
+        hq_d = hq_next;
+        if (n_steps > 1) {
+            ent[1] = __builtin_amdgcn_readlane(list_chunk, 1);
+            issue_q(ent[1], hq_next, 1);
             if (++qi_next == n_q) { qi_next = 0; ++hq_next; }
         }
+        hq_d1 = hq_next;
+    }
 
-    int st = 0;                                        // stage of step i
-    const int n_iter = n_steps > 0 ? n_steps + 1 : 0;
-    for (int i = 0; i < n_iter; ++i) {
-        // step i's tiles have landed once only the younger steps' transfers remain
-        {
-            const int younger = max(0, min(NST - 3, n_steps - 1 - i));
-            if (younger == 0) wait_vmcnt<0>();
-            else if (younger == 1) wait_vmcnt<(NST > 3 ? 1 : 0) * kPerStep>();
-            else if (younger == 2) wait_vmcnt<(NST > 4 ? 2 : 0) * kPerStep>();
-            else if (younger == 3) wait_vmcnt<(NST > 5 ? 3 : 0) * kPerStep>();
-            else if (younger == 4) wait_vmcnt<(NST > 6 ? 4 : 0) * kPerStep>();
-            else wait_vmcnt<(NST > 7 ? 5 : 0) * kPerStep>();
+#define MM_SLOT_END() __builtin_amdgcn_sched_barrier(0)
+    floatx16 xa, xb;                       // S (V role) / dP (K role) of the current and the next unit, alternating
+    bf16x8 rf[NKF];                        // leading row fragments of the next first product
+    floatx4 rc[4];                         // row constants of the current unit
+    u32x4 pin[2];                          // K role: P of the current unit
+
+    // first product without overlap (start-up only)
+    auto first_plain = [&](floatx16& x, const uint32_t (&a)[NDS], int imm) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) x[r] = 0.f;
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) x = mfma32(read_row(a[ds], imm), res[ds], x);
+    };
+    auto mask_unit = [&](floatx16& x, int sb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int qr = sb * 32 + c_row(r, hh);
+            if (!visible(sm.q_ss[qr], sm.q_causal[qr], sm.q_pos[qr], k_ss, key)) x[r] = -INFINITY;
         }
-        __syncthreads();                    // step i landed; step i-2's stage and P(i-2) are free
-        uint32_t fresh = 0u;
-        const int nxt = i + NST - 2;        // step to put in flight now
-        if (nxt < n_steps) {
-            if ((nxt & 63) == 0) {
-                list_chunk = fetch_chunk(nxt);
-                wait_vmcnt<0>();            // awaited here so that no wait is needed after the branch
+    };
+    // One unit: NS slots, each one MFMA, one fragment request and a share of the
+    // element-wise work (see the forward kernel).  KR: std::true_type for the K role.
+    //   x_next <- first product of the NEXT unit: fragments 0..NKF-1 are in rf[],
+    //             the others are read at a1_hi[..] + off1 (run-time, uniform) + imm1
+    //   x_cur  -> P or dS of this unit (bf16), second product from the transpose
+    //             fragments at a2 + imm2, row groups ks0 and ks0+1
+    //   rf[]   <- fragments 0..NKF-1 of the first product after that: a1n_lo[..] + imm1n
+    //   rc[]   holds the row constants of this unit's first 8 element rows on entry; the
+    //             others are read early in the unit (rcb + rc_imm), the next unit's first
+    //             ones at its end (rcb_n + rc_imm_n)
+    //   V role: this unit's P is stored at pb + p_imm;  K role: it is read from there (the
+    //             first half is in pin[0] on entry) and pin[0] <- the next unit's, at
+    //             pb + p_imm_n (-1 when that P is not published yet)
+    auto unit = [&](auto KR_, floatx16& x_next, const floatx16& x_cur, const uint32_t* a1_hi, int off1,
+                    int imm1, const uint32_t* a1n_lo, int imm1n, const uint32_t (&a2)[NDB][NV], int imm2,
+                    int ks0, uint32_t rcb, int rc_imm, uint32_t rcb_n, int rc_imm_n, uint32_t pb,
+                    int p_imm, int p_imm_n) __attribute__((always_inline)) {
+        constexpr bool KR = decltype(KR_)::value;
+        bf16x8 tf[NKF], pf0, pf1;
+        float ev[16];
+        uint32_t pw[8];
+        auto slot_of = [](int e) { return e * SLV / 16; };
+        auto read_rc = [&](uint32_t base, int imm, int q4) __attribute__((always_inline)) -> floatx4 {
+            return *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(base + (uint32_t)(imm + q4 * 32));
+        };
+        auto read_p = [&](int imm) __attribute__((always_inline)) -> u32x4 {
+            return *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(pb + (uint32_t)imm);
+        };
+        MM_SLOT_END();
+#pragma unroll
+        for (int t = 0; t < NS; ++t) {
+            // ---- matrix instruction and the request that refills its operand ----
+            if (t < NDS) {
+                if (t == 0) {
+                    floatx16 z;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                    x_next = mfma32(rf[0], res[0], z);
+                } else {
+                    x_next = mfma32(rf[t % NKF], res[t], x_next);
+                }
+                if (t < NKF) rf[t] = read_row(a1_hi[t] + (uint32_t)off1, imm1);
+                else tf[t - NKF] = read_tr(a2, imm2, ks0, t - NKF);
+            } else if (t < NDS + NDB) {
+                if (t == NDS) pf0 = __builtin_bit_cast(bf16x8, u32x4{pw[0], pw[1], pw[2], pw[3]});
+                acc[t - NDS] = mfma32(tf[t - NDS], pf0, acc[t - NDS]);
+                tf[t - NDS] = read_tr(a2, imm2, ks0 + 1, t - NDS);
+            } else {
+                if (t == NDS + NDB) pf1 = __builtin_bit_cast(bf16x8, u32x4{pw[4], pw[5], pw[6], pw[7]});
+                acc[t - NDS - NDB] = mfma32(tf[t - NDS - NDB], pf1, acc[t - NDS - NDB]);
+                rf[t - NDS - NDB] = read_row(a1n_lo[t - NDS - NDB], imm1n);
             }
-            fresh = __builtin_amdgcn_readlane(list_chunk, nxt & 63);
-            int sn = st + NST - 2;
-            if (sn >= NST) sn -= NST;
-            issue_step(fresh, hq_next, sn);
+            // ---- element-wise work ----
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (slot_of(2 * k + 1) + 1 == t) {              // round a finished pair to bf16
+                    const bf16x2 pb2 = {(__bf16)ev[2 * k], (__bf16)ev[2 * k + 1]};
+                    pw[k] = __builtin_bit_cast(uint32_t, pb2);
+                    asm volatile("" : "+v"(pw[k]));
+                    if (!KR && (k & 3) == 3) {                  // eight probabilities done: publish them
+                        const u32x4 o4 = {pw[k - 3], pw[k - 2], pw[k - 1], pw[k]};
+                        *(u32x4 __attribute__((address_space(3)))*)(uintptr_t)(
+                            pb + (uint32_t)(p_imm + (k >> 2) * 16)) = o4;
+                    }
+                }
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (slot_of(e) == t) {
+                    const float c = rc[e >> 2][e & 3];
+                    if (!KR) {
+                        // masked entries are -inf: exp2 gives 0 (padding rows have LSE = +inf)
+                        ev[e] = __builtin_amdgcn_exp2f(x_cur[e] * scale_log2 - c);
+                    } else {
+                        const uint32_t w = pin[e >> 3][(e & 7) >> 1];
+                        const float pv = __builtin_bit_cast(float, (e & 1) ? (w & 0xffff0000u) : (w << 16));
+                        ev[e] = pv * (x_cur[e] - c);
+                    }
+                    asm volatile("" : "+v"(ev[e]));
+                }
+            // row constants: four rows per read, requested a few slots before their use
+            if (t == (slot_of(8) > 4 ? slot_of(8) - 4 : 0)) rc[2] = read_rc(rcb, rc_imm, 2);
+            if (t == (slot_of(12) > 5 ? slot_of(12) - 4 : 1)) rc[3] = read_rc(rcb, rc_imm, 3);
+            if (t == SLV + 1) {
+                rc[0] = read_rc(rcb_n, rc_imm_n, 0);
+                rc[1] = read_rc(rcb_n, rc_imm_n, 1);
+            }
+            // K role: P of this unit's last 8 element rows, then of the next unit's first 8
+            if (KR && t == (slot_of(8) > 4 ? slot_of(8) - 4 : 0)) pin[1] = read_p(p_imm + 16);
+            if (KR && t == SLV + 2 && p_imm_n >= 0) pin[0] = read_p(p_imm_n);
+            MM_SLOT_END();
+        }
+    };
+
+    // top of iteration i, common to both roles: everything issued one iteration ago has
+    // landed (Q and row constants of step i+1, dO of step i); after the barrier step i-1's
+    // P is published and the stages of step i-2 are free, so the next transfers start.
+    // Returns whether step i is PARTIAL (its rows' mask fields are then staged in LDS).
+    int dst = 0;                           // dO ring stage of step i
+    auto top = [&](int i) __attribute__((always_inline)) -> bool {
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (i + 2 < n_steps) {
+            if (((i + 2) & 63) == 0) {
+                list_chunk = fetch_chunk(i + 2);
+                wait_vmcnt<0>();           // nothing else is in flight here
+            }
+            ent[2] = __builtin_amdgcn_readlane(list_chunk, (i + 2) & 63);
+            issue_q(ent[2], hq_next, (i + 2) & (kKvQst - 1));
             if (++qi_next == n_q) { qi_next = 0; ++hq_next; }
         }
-        const uint32_t e_cur = pend[1];     // step i
-#pragma unroll
-        for (int j = 0; j + 1 < NST - 1; ++j) pend[j] = pend[j + 1];
-        pend[NST - 2] = fresh;
-
+        if (i + 1 < n_steps) {
+            int dn = dst + 1;
+            if (dn == kKvDst) dn = 0;
+            issue_d(ent[1], hq_d, dn);
+        }
+        hq_d = hq_d1;
+        hq_d1 = hq_next;
+        const uint32_t e_cur = ent[0];
+        ent[0] = ent[1];
+        ent[1] = ent[2];
         const bool partial = i < n_steps && (e_cur & kPartialFlag) != 0;
-        if (partial) {                      // workgroup-uniform
+        if (partial) {                     // workgroup-uniform
             if (tid < kKvBM) {
                 const int64_t r = min((int64_t)(e_cur & ~kPartialFlag) * kKvBM + tid, n_loc - 1);
                 const int64_t p = row_pos(blocks, block, r);
@@ -304,73 +457,101 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             }
             __syncthreads();
         }
+        return partial;
+    };
+    constexpr int kLdStage = 8 * kKvBM;    // bytes of a stage of row constants
+    // byte step from dO stage `dst` to the next one
+    auto d_step = [&]() -> int { return dst + 1 == kKvDst ? -(kKvDst - 1) * kStage : kStage; };
 
-        // Both roles run the same two MFMA phases on different tiles; only the
-        // element-wise part in between differs (kept in one place each so that the
-        // accumulator is updated by a single instruction stream).
-        const bool active = k_role ? i >= 1 : i < n_steps;
-        if (active) {
-            int sa = st;                                // V role: step i;  K role: step i-1
-            if (k_role) { sa = st - 1; if (sa < 0) sa += NST; }
-            const unsigned char* t1 = k_role ? sm.d[sa] : sm.q[sa];   // rows:      dO | Q
-            const unsigned char* t2 = k_role ? sm.q[sa] : sm.d[sa];   // transpose: Q  | dO
-            // per-row constant: lse2 (V role) or Delta (K role) of the (lse2, delta) pairs
-            const float* ld = sm.ld[sa][wave] + (k_role ? 1 : 0);
-            floatx16 x[kKvSub];                         // S (V role) or dP (K role) per sub-block
+    if (!k_role) {
+        // ---- V role: step i (units 2i, 2i+1).  Unrolled over the Q ring so that the
+        // stage offsets are immediates; the dO tile of step i is addressed through dtr[].
+        uint32_t dtr[NDB][NV];
 #pragma unroll
-            for (int sb = 0; sb < kKvSub; ++sb)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) x[sb][r] = 0.f;
+            for (int v = 0; v < NV; ++v) dtr[db][v] = tr_addr[db][v];
+        for (int i0 = 0; i0 <= n_steps; i0 += kKvQst) {
 #pragma unroll
-            for (int ds = 0; ds < NDS; ++ds)
+            for (int u = 0; u < kKvQst; ++u) {
+                const int i = i0 + u;
+                if (i > n_steps) break;
+                const int qs0 = u, qs1 = (u + 1) % kKvQst;
+                const bool partial = top(i);
+                if (i == 0 && n_steps > 0) {
+                    first_plain(xa, row_addr, 0);
 #pragma unroll
-                for (int sb = 0; sb < kKvSub; ++sb)
-                    x[sb] = mfma32(qrow.read(t1, sb, ds), res[ds], x[sb]);
-            bf16x8 bop[2 * kKvSub];                     // P (V role) or dS (K role), bf16
-            if (!k_role) {
-                if (partial) {
-#pragma unroll
-                    for (int sb = 0; sb < kKvSub; ++sb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int qr = sb * 32 + c_row(r, hh);
-                            if (!visible(sm.q_ss[qr], sm.q_causal[qr], sm.q_pos[qr], k_ss, key))
-                                x[sb][r] = -INFINITY;
-                        }
+                    for (int j = 0; j < NKF; ++j) rf[j] = read_row(row_addr[j], kUnit);
+                    rc[0] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(rc_addr);
+                    rc[1] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(rc_addr + 32);
                 }
-                // masked entries are -inf: exp2 gives 0 (padding rows have LSE = +inf)
-#pragma unroll
-                for (int sb = 0; sb < kKvSub; ++sb) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        bop[sb * 2 + (r >> 3)][r & 7] = (__bf16)__builtin_amdgcn_exp2f(
-                            x[sb][r] * scale_log2 - ld[2 * (sb * 32 + c_row(r, hh))]);
-                    unsigned char* pb = sm.p[i & 1][kblk] + (sb * 64 + lane) * 32;
-                    *(u32x4*)pb = __builtin_bit_cast(u32x4, bop[sb * 2]);
-                    *(u32x4*)(pb + 16) = __builtin_bit_cast(u32x4, bop[sb * 2 + 1]);
+                if (i < n_steps) {
+                    if (partial) mask_unit(xa, 0);
+                    unit(std::false_type{}, xb, xa, &row_addr[NKF], 0, qs0 * kStage + kUnit, &row_addr[0],
+                         qs1 * kStage, dtr, 0, 0, rc_addr, qs0 * kLdStage, rc_addr, qs0 * kLdStage + 128,
+                         p_addr, (u & 1) * 16384, -1);
+                    if (partial) mask_unit(xb, 1);
+                    unit(std::false_type{}, xa, xb, &row_addr[NKF], 0, qs1 * kStage, &row_addr[0],
+                         qs1 * kStage + kUnit, dtr, 0, 2, rc_addr, qs0 * kLdStage + 128, rc_addr,
+                         qs1 * kLdStage, p_addr, (u & 1) * 16384 + 2048, -1);
                 }
-            } else {
-#pragma unroll
-                for (int sb = 0; sb < kKvSub; ++sb) {
-                    const unsigned char* pb = sm.p[(i - 1) & 1][kblk] + (sb * 64 + lane) * 32;
-                    const bf16x8 p0 = __builtin_bit_cast(bf16x8, *(const u32x4*)pb);
-                    const bf16x8 p1 = __builtin_bit_cast(bf16x8, *(const u32x4*)(pb + 16));
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float pv = (float)(r < 8 ? p0[r & 7] : p1[r & 7]);
-                        bop[sb * 2 + (r >> 3)][r & 7] =
-                            (__bf16)(pv * (x[sb][r] - ld[2 * (sb * 32 + c_row(r, hh))]));
-                    }
-                }
-            }
-#pragma unroll
-            for (int ks = 0; ks < 2 * kKvSub; ++ks)
+                const int delta = d_step();
+                if (++dst == kKvDst) dst = 0;
 #pragma unroll
                 for (int db = 0; db < NDB; ++db)
-                    acc[db] = mfma32(qtr.read(t2, ks, db), bop[ks], acc[db]);
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) dtr[db][v] += (uint32_t)delta;
+            }
         }
-        if (++st == NST) st = 0;
+    } else {
+        // ---- K role: step i-1 (units 2i-2, 2i-1) and the first product of step i.  All
+        // ring positions are run-time here: drow[] is the dO tile of step i (the one of
+        // step i-1 lies dprev bytes from it), qtr[] the Q tile of step i-1, rcp / rcc
+        // the row constants of steps i-1 / i, pp the P buffer of step i-1.
+        uint32_t drow[NDS], qtr[NDB][NV];
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) drow[ds] = row_addr[ds];
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int v = 0; v < NV; ++v) qtr[db][v] = tr_addr[db][v] + (uint32_t)((kKvQst - 1) * kStage);
+        int dprev = 0, qpos = kKvQst - 1;
+        uint32_t rcp = rc_addr + (uint32_t)((kKvQst - 1) * kLdStage), rcc = rc_addr;
+        uint32_t pp = p_addr + 16384u;
+        for (int i = 0; i <= n_steps; ++i) {
+            top(i);
+            if (i == 0 && n_steps > 0) {
+                first_plain(xa, drow, 0);
+#pragma unroll
+                for (int j = 0; j < NKF; ++j) rf[j] = read_row(drow[j], kUnit);
+                rc[0] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(rc_addr);
+                rc[1] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(rc_addr + 32);
+            }
+            if (i >= 1) {
+                pin[0] = *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(pp);
+                unit(std::true_type{}, xb, xa, &drow[NKF], dprev, kUnit, &drow[0], 0, qtr, 0, 0, rcp, 0,
+                     rcp, 128, pp, 0, 2048);
+                unit(std::true_type{}, xa, xb, &drow[NKF], 0, 0, &drow[0], kUnit, qtr, 0, 2, rcp, 128,
+                     rcc, 0, pp, 2048, -1);
+            }
+            // advance: dO ring, Q ring position of step i, row constants, P parity
+            const int delta = d_step();
+            if (++dst == kKvDst) dst = 0;
+            dprev = -delta;
+#pragma unroll
+            for (int ds = 0; ds < NDS; ++ds) drow[ds] += (uint32_t)delta;
+            const int qdelta = qpos + 1 == kKvQst ? -(kKvQst - 1) : 1;
+            qpos += qdelta;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int v = 0; v < NV; ++v) qtr[db][v] += (uint32_t)(qdelta * kStage);
+            rcp = rcc;
+            rcc = rc_addr + (uint32_t)(((i + 1) & (kKvQst - 1)) * kLdStage);
+            pp = p_addr + (uint32_t)((i & 1) * 16384);
+        }
     }
+#undef MM_SLOT_END
 
     // ---- epilogue: lane holds key `key`, 4 consecutive d per register quad ------------
     const int64_t obase = (key * Hkv + g) * (int64_t)D + 4 * hh;
@@ -480,8 +661,8 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     const bool row_ok = row < n_loc;
     int64_t q_pos = 0;
     uint32_t q_ss = 0, q_causal = 0;
-    const float my_lse2 = ld_g[((int64_t)h * n_pad + row) * 2];         // +inf on padding rows
-    const float my_delta = ld_g[((int64_t)h * n_pad + row) * 2 + 1];
+    const float my_lse2 = ld_g[(int64_t)h * 2 * n_pad + row];           // +inf on padding rows
+    const float my_delta = ld_g[((int64_t)h * 2 + 1) * n_pad + row];
     bf16x8 qf[NDS], dof[NDS];
 #pragma unroll
     for (int ds = 0; ds < NDS; ++ds) {
