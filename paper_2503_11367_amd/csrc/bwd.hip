@@ -31,7 +31,9 @@ namespace mm {
 // ---------------------------------------------------------------- prep -------
 // One thread per 8 elements; D/8 consecutive lanes reduce one (row, head).
 //   ld[Hq][2][n_pad] = LSE in base-2 units, then Delta = rowsum(dO o O), per head; rows
-//                      n_loc .. n_pad-1 are padding: LSE = +inf (probability 0), Delta = 0
+//                      n_loc .. n_pad-1 are padding: LSE = +inf (probability 0), Delta = 0;
+//                      followed by [3][n_pad] uint32: every local row's sample/span field,
+//                      causal flag and sequence position (the mask inputs of the key-outer pass)
 //   qh, doh [Hq][n_pad][D]  head-major copies of Q and dO (padding rows zero) for the
 //                      key-outer pass: there a tile is 64 consecutive rows of ONE head,
 //                      which in the token-major layout are Hq*D*2 bytes apart -- a
@@ -40,9 +42,10 @@ namespace mm {
 template <int D>
 __global__ void __launch_bounds__(256)
 bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
-                const ushort_t* __restrict__ dO, const float* __restrict__ lse, int64_t n_loc,
-                int64_t n_pad, int32_t Hq, float* __restrict__ ld, ushort_t* __restrict__ qh,
-                ushort_t* __restrict__ doh) {
+                const ushort_t* __restrict__ dO, const float* __restrict__ lse,
+                const uint64_t* __restrict__ bits, const int32_t* __restrict__ blocks, int32_t block,
+                int64_t n_loc, int64_t n_pad, int32_t Hq, float* __restrict__ ld,
+                ushort_t* __restrict__ qh, ushort_t* __restrict__ doh) {
     constexpr int TPR = D / 8;
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t rh = gid / TPR;                       // row*Hq + h over padded rows
@@ -72,6 +75,20 @@ bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
             float* out = ld + (int64_t)h * 2 * n_pad + row;
             out[0] = ok ? lse[(int64_t)h * n_loc + row] * kLog2e : INFINITY;
             out[n_pad] = ok ? acc : 0.f;
+            if (h == 0) {
+                uint32_t* info = (uint32_t*)(ld + (int64_t)Hq * 2 * n_pad) + row;
+                uint32_t ss = 0u, ca = 0u;
+                int64_t pos = 0;
+                if (ok) {
+                    pos = row_pos(blocks, block, row);
+                    const uint64_t w = bits[pos];
+                    ss = word_ss(w);
+                    ca = word_causal(w);
+                }
+                info[0] = ss;
+                info[n_pad] = ca;
+                info[2 * n_pad] = (uint32_t)pos;
+            }
         }
     }
 }
@@ -117,11 +134,9 @@ template <int D>
 struct KvSmem {
     alignas(1024) unsigned char q[kKvQst][kKvBM * D * 2];       // MODE 0: rows and transpose
     alignas(1024) unsigned char d[kKvDst][kKvBM * D * 2];
-    alignas(1024) unsigned char p[2][4][2 * 64 * 32];           // P hand-over: [step parity][key block][unit][lane] 2 x 16 B
+    alignas(1024) unsigned char p[2][4][2 * 2 * 64 * 16];       // P hand-over: [step parity][key block][unit][half][lane] 16 B
     alignas(256) float ld[kKvQst][2][kKvBM];                    // lse2 and delta of a step's rows
-    uint32_t q_ss[kKvBM];                                       // mask fields of a PARTIAL step's rows
-    uint32_t q_causal[kKvBM];
-    int32_t q_pos[kKvBM];
+    alignas(256) uint32_t info[kKvQst][3][kKvBM];               // sample/span field, causal flag, position of a step's rows
 };
 
 // A (k-tile, KV head) unit is processed by `cmax` workgroups, each taking `hpc`
@@ -216,6 +231,8 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     const uint32_t lds_q = lds_addr_of(sm.q[0]) + (wave * NI) * 1024;
     const uint32_t lds_d = lds_addr_of(sm.d[0]) + (wave * NI) * 1024;
     const uint32_t lds_ld = lds_addr_of(sm.ld[0][0]);
+    const uint32_t lds_info = lds_addr_of(sm.info[0][0]);
+    const uint32_t* info_g = (const uint32_t*)(ld_g + (int64_t)Hq * 2 * n_pad);
     auto issue_q = [&](uint32_t entry, int hq, int stage) {     // Q tile and the rows' (lse2, delta)
         const int64_t r0 = (int64_t)(entry & ~kPartialFlag) * kKvBM;
         const int64_t tile = ((int64_t)hq * n_pad + r0) * D;    // 64 consecutive rows, padded with zeros
@@ -224,6 +241,9 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
         if (wave < 2)                                           // wave 0: lse2 rows, wave 1: delta rows
             dma4(ld_g + ((int64_t)hq * 2 + wave) * n_pad + r0, (uint32_t)(lane * 4),
                  lds_ld + stage * (8 * kKvBM) + wave * (4 * kKvBM));
+        else if (wave < 5)                                      // waves 2-4: the rows' mask inputs
+            dma4(info_g + (int64_t)(wave - 2) * n_pad + r0, (uint32_t)(lane * 4),
+                 lds_info + stage * (12 * kKvBM) + (wave - 2) * (4 * kKvBM));
     };
     auto issue_d = [&](uint32_t entry, int hq, int stage) {
         const int64_t r0 = (int64_t)(entry & ~kPartialFlag) * kKvBM;
@@ -265,7 +285,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     }
     // P hand-over slot of this lane, and the row constants (4 consecutive rows per 16-byte
     // read: lse2 for the V role, delta for the K role)
-    const uint32_t p_addr = lds_addr_of(sm.p[0][kblk]) + lane * 32;
+    const uint32_t p_addr = lds_addr_of(sm.p[0][kblk]) + lane * 16;
     const uint32_t rc_addr = lds_ld + (k_role ? 4 * kKvBM : 0) + hh * 16;
 
     auto read_row = [&](uint32_t a, int imm) __attribute__((always_inline)) -> bf16x8 {
@@ -318,11 +338,17 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds) x = mfma32(read_row(a[ds], imm), res[ds], x);
     };
-    auto mask_unit = [&](floatx16& x, int sb) __attribute__((always_inline)) {
+    // PARTIAL steps: rows 8*q4 + 4*hh + 0..3 (+32 per unit) of the step's mask inputs, 16 bytes per read
+    const uint32_t info_addr = lds_info + hh * 16;
+    auto mask_unit = [&](floatx16& x, int imm) __attribute__((always_inline)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int qr = sb * 32 + c_row(r, hh);
-            if (!visible(sm.q_ss[qr], sm.q_causal[qr], sm.q_pos[qr], k_ss, key)) x[r] = -INFINITY;
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const u32x4 ss = *(lds_u4)(uintptr_t)(info_addr + (uint32_t)(imm + q4 * 32));
+            const u32x4 ca = *(lds_u4)(uintptr_t)(info_addr + (uint32_t)(imm + q4 * 32 + 4 * kKvBM));
+            const u32x4 ps = *(lds_u4)(uintptr_t)(info_addr + (uint32_t)(imm + q4 * 32 + 8 * kKvBM));
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (!visible(ss[j], ca[j], (int64_t)ps[j], k_ss, key)) x[q4 * 4 + j] = -INFINITY;
         }
     };
     // One unit: NS slots, each one MFMA, one fragment request and a share of the
@@ -387,7 +413,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
                     if (!KR && (k & 3) == 3) {                  // eight probabilities done: publish them
                         const u32x4 o4 = {pw[k - 3], pw[k - 2], pw[k - 1], pw[k]};
                         *(u32x4 __attribute__((address_space(3)))*)(uintptr_t)(
-                            pb + (uint32_t)(p_imm + (k >> 2) * 16)) = o4;
+                            pb + (uint32_t)(p_imm + (k >> 2) * 1024)) = o4;
                     }
                 }
 #pragma unroll
@@ -412,7 +438,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
                 rc[1] = read_rc(rcb_n, rc_imm_n, 1);
             }
             // K role: P of this unit's last 8 element rows, then of the next unit's first 8
-            if (KR && t == (slot_of(8) > 4 ? slot_of(8) - 4 : 0)) pin[1] = read_p(p_imm + 16);
+            if (KR && t == (slot_of(8) > 4 ? slot_of(8) - 4 : 0)) pin[1] = read_p(p_imm + 1024);
             if (KR && t == SLV + 2 && p_imm_n >= 0) pin[0] = read_p(p_imm_n);
             MM_SLOT_END();
         }
@@ -421,11 +447,12 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     // top of iteration i, common to both roles: everything issued one iteration ago has
     // landed (Q and row constants of step i+1, dO of step i); after the barrier step i-1's
     // P is published and the stages of step i-2 are free, so the next transfers start.
-    // Returns whether step i is PARTIAL (its rows' mask fields are then staged in LDS).
+    // Returns whether step i is PARTIAL.
     int dst = 0;                           // dO ring stage of step i
-    auto top = [&](int i) __attribute__((always_inline)) -> bool {
+    auto top = [&](int i, auto&& after_barrier) __attribute__((always_inline)) -> bool {
         wait_vmcnt<0>();
         __syncthreads();
+        after_barrier();                   // LDS reads that should start before the transfer bookkeeping
         if (i + 2 < n_steps) {
             if (((i + 2) & 63) == 0) {
                 list_chunk = fetch_chunk(i + 2);
@@ -445,19 +472,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
         const uint32_t e_cur = ent[0];
         ent[0] = ent[1];
         ent[1] = ent[2];
-        const bool partial = i < n_steps && (e_cur & kPartialFlag) != 0;
-        if (partial) {                     // workgroup-uniform
-            if (tid < kKvBM) {
-                const int64_t r = min((int64_t)(e_cur & ~kPartialFlag) * kKvBM + tid, n_loc - 1);
-                const int64_t p = row_pos(blocks, block, r);
-                const uint64_t w = bits[p];
-                sm.q_ss[tid] = word_ss(w);
-                sm.q_causal[tid] = word_causal(w);
-                sm.q_pos[tid] = (int32_t)p;
-            }
-            __syncthreads();
-        }
-        return partial;
+        return i < n_steps && (e_cur & kPartialFlag) != 0;
     };
     constexpr int kLdStage = 8 * kKvBM;    // bytes of a stage of row constants
     // byte step from dO stage `dst` to the next one
@@ -477,7 +492,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
                 const int i = i0 + u;
                 if (i > n_steps) break;
                 const int qs0 = u, qs1 = (u + 1) % kKvQst;
-                const bool partial = top(i);
+                const bool partial = top(i, [] {});
                 if (i == 0 && n_steps > 0) {
                     first_plain(xa, row_addr, 0);
 #pragma unroll
@@ -486,11 +501,11 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
                     rc[1] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(rc_addr + 32);
                 }
                 if (i < n_steps) {
-                    if (partial) mask_unit(xa, 0);
+                    if (partial) mask_unit(xa, qs0 * (12 * kKvBM));
                     unit(std::false_type{}, xb, xa, &row_addr[NKF], 0, qs0 * kStage + kUnit, &row_addr[0],
                          qs1 * kStage, dtr, 0, 0, rc_addr, qs0 * kLdStage, rc_addr, qs0 * kLdStage + 128,
                          p_addr, (u & 1) * 16384, -1);
-                    if (partial) mask_unit(xb, 1);
+                    if (partial) mask_unit(xb, qs0 * (12 * kKvBM) + 128);
                     unit(std::false_type{}, xa, xb, &row_addr[NKF], 0, qs1 * kStage, &row_addr[0],
                          qs1 * kStage + kUnit, dtr, 0, 2, rc_addr, qs0 * kLdStage + 128, rc_addr,
                          qs1 * kLdStage, p_addr, (u & 1) * 16384 + 2048, -1);
@@ -519,7 +534,9 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
         uint32_t rcp = rc_addr + (uint32_t)((kKvQst - 1) * kLdStage), rcc = rc_addr;
         uint32_t pp = p_addr + 16384u;
         for (int i = 0; i <= n_steps; ++i) {
-            top(i);
+            top(i, [&] {
+                if (i >= 1) pin[0] = *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(pp);
+            });
             if (i == 0 && n_steps > 0) {
                 first_plain(xa, drow, 0);
 #pragma unroll
@@ -528,7 +545,6 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
                 rc[1] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(rc_addr + 32);
             }
             if (i >= 1) {
-                pin[0] = *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(pp);
                 unit(std::true_type{}, xb, xa, &drow[NKF], dprev, kUnit, &drow[0], 0, qtr, 0, 0, rcp, 0,
                      rcp, 128, pp, 0, 2048);
                 unit(std::true_type{}, xa, xb, &drow[NKF], 0, 0, &drow[0], kUnit, qtr, 0, 2, rcp, 128,
@@ -852,7 +868,7 @@ static BwdLayout bwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
     L.err = take(256);
     L.clean_blocks = take((size_t)n_blocks * 4);
-    L.ld = take((size_t)Hq * L.n_pad * 8);
+    L.ld = take(((size_t)Hq * 2 + 3) * L.n_pad * 4);
     L.qh = take((size_t)Hq * L.n_pad * D * 2);
     L.doh = take((size_t)Hq * L.n_pad * D * 2);
     L.cls_a = take((size_t)L.nq_a * L.nk_a);
@@ -930,7 +946,7 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
         const int64_t threads = L.n_pad * a.Hq * (D / 8);
         hipLaunchKernelGGL(bwd_prep_kernel<D>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
                            st, (const ushort_t*)a.q, (const ushort_t*)o, (const ushort_t*)d_o, lse,
-                           n_loc, L.n_pad, a.Hq, ld, qh, doh);
+                           a.bits, clean, a.block, n_loc, L.n_pad, a.Hq, ld, qh, doh);
     }
     const int rep = a.Hq / a.Hkv;
     stage_begin(MMATTN_STAGE_DKV, st);
