@@ -361,13 +361,14 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     //   rc[]   holds the row constants of this unit's first 8 element rows on entry; the
     //             others are read early in the unit (rcb + rc_imm), the next unit's first
     //             ones at its end (rcb_n + rc_imm_n)
+    //   hook() runs after the second slot (scalar work hidden behind the matrix pipe)
     //   V role: this unit's P is stored at pb + p_imm;  K role: it is read from there (the
     //             first half is in pin[0] on entry) and pin[0] <- the next unit's, at
     //             pb + p_imm_n (-1 when that P is not published yet)
     auto unit = [&](auto KR_, floatx16& x_next, const floatx16& x_cur, const uint32_t* a1_hi, int off1,
                     int imm1, const uint32_t* a1n_lo, int imm1n, const uint32_t (&a2)[NDB][NV], int imm2,
                     int ks0, uint32_t rcb, int rc_imm, uint32_t rcb_n, int rc_imm_n, uint32_t pb,
-                    int p_imm, int p_imm_n) __attribute__((always_inline)) {
+                    int p_imm, int p_imm_n, auto&& hook) __attribute__((always_inline)) {
         constexpr bool KR = decltype(KR_)::value;
         bf16x8 tf[NKF], pf0, pf1;
         float ev[16];
@@ -441,6 +442,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             if (KR && t == (slot_of(8) > 4 ? slot_of(8) - 4 : 0)) pin[1] = read_p(p_imm + 1024);
             if (KR && t == SLV + 2 && p_imm_n >= 0) pin[0] = read_p(p_imm_n);
             MM_SLOT_END();
+            if (t == 1) hook();
         }
     };
 
@@ -452,7 +454,13 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     auto top = [&](int i, auto&& after_barrier) __attribute__((always_inline)) -> bool {
         wait_vmcnt<0>();
         __syncthreads();
-        after_barrier();                   // LDS reads that should start before the transfer bookkeeping
+        after_barrier();                   // LDS reads that should start right away
+        return i < n_steps && (ent[0] & kPartialFlag) != 0;
+    };
+    // the transfers of iteration i: Q tile (+ row data) of step i+2, dO tile of step i+1.
+    // Called from inside the iteration's first unit so that the scalar bookkeeping runs
+    // in the shadow of its matrix instructions.
+    auto issue = [&](int i) __attribute__((always_inline)) {
         if (i + 2 < n_steps) {
             if (((i + 2) & 63) == 0) {
                 list_chunk = fetch_chunk(i + 2);
@@ -469,10 +477,8 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
         }
         hq_d = hq_d1;
         hq_d1 = hq_next;
-        const uint32_t e_cur = ent[0];
         ent[0] = ent[1];
         ent[1] = ent[2];
-        return i < n_steps && (e_cur & kPartialFlag) != 0;
     };
     constexpr int kLdStage = 8 * kKvBM;    // bytes of a stage of row constants
     // byte step from dO stage `dst` to the next one
@@ -504,11 +510,13 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
                     if (partial) mask_unit(xa, qs0 * (12 * kKvBM));
                     unit(std::false_type{}, xb, xa, &row_addr[NKF], 0, qs0 * kStage + kUnit, &row_addr[0],
                          qs1 * kStage, dtr, 0, 0, rc_addr, qs0 * kLdStage, rc_addr, qs0 * kLdStage + 128,
-                         p_addr, (u & 1) * 16384, -1);
+                         p_addr, (u & 1) * 16384, -1, [&] { issue(i); });
                     if (partial) mask_unit(xb, qs0 * (12 * kKvBM) + 128);
                     unit(std::false_type{}, xa, xb, &row_addr[NKF], 0, qs1 * kStage, &row_addr[0],
                          qs1 * kStage + kUnit, dtr, 0, 2, rc_addr, qs0 * kLdStage + 128, rc_addr,
-                         qs1 * kLdStage, p_addr, (u & 1) * 16384 + 2048, -1);
+                         qs1 * kLdStage, p_addr, (u & 1) * 16384 + 2048, -1, [] {});
+                } else {
+                    issue(i);
                 }
                 const int delta = d_step();
                 if (++dst == kKvDst) dst = 0;
@@ -546,9 +554,11 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             }
             if (i >= 1) {
                 unit(std::true_type{}, xb, xa, &drow[NKF], dprev, kUnit, &drow[0], 0, qtr, 0, 0, rcp, 0,
-                     rcp, 128, pp, 0, 2048);
+                     rcp, 128, pp, 0, 2048, [&] { issue(i); });
                 unit(std::true_type{}, xa, xb, &drow[NKF], 0, 0, &drow[0], kUnit, qtr, 0, 2, rcp, 128,
-                     rcc, 0, pp, 2048, -1);
+                     rcc, 0, pp, 2048, -1, [] {});
+            } else {
+                issue(i);
             }
             // advance: dO ring, Q ring position of step i, row constants, P parity
             const int delta = d_step();
