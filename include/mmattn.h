@@ -29,10 +29,13 @@
  * The attend-set and modality fields are carried but not consulted.
  *
  * Ownership: the caller owns every buffer and the stream.  The library
- * allocates no device memory, keeps no state between calls and never
- * synchronises the stream; scratch comes in through `ws` (size from
- * mmattn_workspace_size, 256-byte aligned).  Host pointers are read before
- * the call returns.
+ * allocates no device memory, never synchronises the stream and keeps no
+ * state between calls (the one exception, the optional timing events of
+ * mmattn_stage_events, is stated there); scratch comes in through `ws` (size
+ * from mmattn_workspace_size, 256-byte aligned) and may be reused by the next
+ * call on the same stream.  Host pointers are read before the call returns.
+ * Results are deterministic: no atomics on floating-point data, every sum is
+ * taken in a fixed order.
  *
  * Errors: every call returns MMATTN_OK (0) or a negative mmattn_status.  All
  * argument checks run on the host before any GPU work is enqueued; nothing is
@@ -145,7 +148,10 @@ int mmattn_fwd(const void* q_loc, const void* k, const void* v, const uint64_t* 
  *   dk, dv       [S,Hkv,D] overwritten with THIS rank's partial sums over its
  *                rows and over the Hq/Hkv query heads of each KV head (rows
  *                of keys no query of the rank sees become 0)
- */
+ * With P = exp(S - LSE), Delta = rowsum(dO o O), dS = P o (dP - Delta):
+ * dV = P^T dO, dK = scale dS^T Q, dQ = scale dS K.  When there are few key
+ * tiles the query heads of a KV head are summed in two stages (fp32 partials
+ * in `ws`, fixed order).  Same shape requirements as mmattn_fwd. */
 int mmattn_bwd(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
                const int32_t* blocks, int32_t n_blocks, int32_t block,
                int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,
