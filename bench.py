@@ -27,6 +27,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published figure
+# HBM bytes per launch (fetched + written) of the dominant kernel, from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/attention_kernels_vlm_8k.md
+# (scaled by the copy-kernel calibration given there); None for workloads not profiled.
+MEASURED_TRAFFIC_BYTES = {("vlm_8k", "dkv_kernel"): None}
 
 
 def build_inputs(w, device):
@@ -52,17 +56,42 @@ def plan_on_gpu(w, device):
     return bits, W, rblocks, load_h, off_h
 
 
+def in_order_greedy_loads(Wf, P):
+    """Harness-side list scheduling in index order (Alg. 1 as printed, no sort):
+    each block to the least-loaded rank, lowest rank on ties."""
+    load = np.zeros(P, dtype=np.float64)
+    for wb in Wf:
+        load[int(np.argmin(load))] += wb
+    return load
+
+
 def imbalance_report(device):
-    """max/mean load over virtual ranks for the balanced workloads: LPT (GPU)
-    next to the zigzag and contiguous splits of the same block workloads."""
+    """max/mean load (in unmasked pairs) over virtual ranks for the balanced
+    workloads: LPT on pair workloads (GPU), LPT on tile-count workloads (GPU
+    balancer fed the number of non-empty tiles per block), next to index-order
+    greedy, the zigzag split and the contiguous split; plus the tile-class
+    histogram of the N_B x N_B tile map."""
+    import torch
+    from paper_2503_11367_amd import binding as mb
     from paper_2503_11367_amd import workloads as wl
     out = {}
     for c in (1, 3, 4, 5):
         w = wl.workload(c)
-        _, W, _, load_h, _ = plan_on_gpu(w, device)
+        bits, W, _, load_h, _ = plan_on_gpu(w, device)
+        cls, cnt, _ = mb.tile_map(bits, w.N_B, w.N_B)
+        cls_h = cls.cpu().numpy()
         Wh = W.cpu().numpy().view(np.uint64).astype(np.float64)
         nB, P = Wh.size, w.P
-        entry = {"P": P, "lpt": float(load_h.max() * P / load_h.sum())}
+        entry = {"P": P, "lpt": float(load_h.max() * P / load_h.sum()),
+                 "tiles": {"empty": int((cls_h == 0).sum()), "full": int((cls_h == 1).sum()),
+                           "partial": int((cls_h == 2).sum())}}
+        # Alg. 1's literal workload: non-empty tiles per block; loads still measured in pairs
+        Wt = (cnt.view(nB, -1) > 0).sum(dim=1).to(torch.int64).contiguous()
+        rob_t = mb.balance(Wt, P)[0].cpu().numpy()
+        lt = np.bincount(rob_t, weights=Wh, minlength=P)
+        entry["lpt_tile_count"] = float(lt.max() * P / lt.sum())
+        lg = in_order_greedy_loads(Wh, P)
+        entry["in_order"] = float(lg.max() * P / lg.sum())
         if nB % (2 * P) == 0:
             ch = Wh.reshape(2 * P, -1).sum(axis=1)
             zz = ch[:P] + ch[::-1][:P]
@@ -72,6 +101,25 @@ def imbalance_report(device):
             entry["contiguous"] = float(ct.max() * P / ct.sum())
         out[w.name] = entry
     return out
+
+
+def mfma_ceiling(device):
+    """Measured matrix-pipe ceiling (TFLOP/s): the library's MFMA-only kernel with
+    constant and with pseudo-random operands, HIP events on the current stream."""
+    import torch
+    from paper_2503_11367_amd import binding as mb
+    sink = torch.zeros(4096, dtype=torch.uint8, device=device)
+    res = {}
+    for name, rnd in (("constant_operands", False), ("random_operands", True)):
+        mb.mfma_ceiling(2000, rnd, sink)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fl = mb.mfma_ceiling(40000, rnd, sink)
+        b.record()
+        torch.cuda.synchronize()
+        res[name] = fl / (a.elapsed_time(b) * 1e-3) / 1e12
+    return res
 
 
 def cpu_baseline(w, blocks, host_q, host_k, host_v, host_do, n_heads, pairs):
@@ -201,7 +249,7 @@ def main():
     achieved = alg[dom] / (kern_ms[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": kname[dom], "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": None, "avg_ms": kern_ms[dom]}
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, kname[dom])), "avg_ms": kern_ms[dom]}
 
     out = {
         "metric": "masked-attention effective TFLOP/s (unmasked pairs) fwd+bwd",
@@ -227,6 +275,7 @@ def main():
     torch.cuda.synchronize()
     out["planning_us"] = (time.perf_counter() - tp0) / 10 * 1e6
     out["imbalance"] = imbalance_report(device)
+    out["mfma_ceiling_tflops"] = mfma_ceiling(device)
 
     if not args.no_cpu_baseline:
         blocks = rblocks[int(off_h[g]):int(off_h[g + 1])].cpu().numpy()

@@ -167,6 +167,19 @@ int mmattn_bwd(const void* q_loc, const void* k, const void* v, const uint64_t* 
 enum { MMATTN_STAGE_FWD = 0, MMATTN_STAGE_DKV = 1, MMATTN_STAGE_DQ = 2, MMATTN_STAGE_COUNT = 3 };
 int mmattn_stage_events(int stage, void* ev_start, void* ev_stop);
 
+/* Measurement aid (not part of the method): enqueue a kernel that only issues
+ * the bf16 32x32x16 matrix instruction from registers (256 workgroups of 8
+ * wavefronts, `iters` x 16 instructions per wavefront), so a harness can time
+ * a matrix-pipe ceiling for this GPU beside the published peak.
+ *   random_operands  0: constant operands; 1: pseudo-random bf16 operands
+ *                    (realistic switching activity, lower sustained clock)
+ *   d_sink           device, >= 2048 bytes, normally left untouched
+ *   flops            host, optional: receives the floating-point operations
+ *                    the launch performs
+ * 1 <= iters <= 2^24. */
+int mmattn_mfma_ceiling(int32_t iters, int32_t random_operands, void* d_sink, size_t sink_bytes,
+                        double* flops, void* stream);
+
 /* Library version string (static storage). */
 const char* mmattn_version(void);
 

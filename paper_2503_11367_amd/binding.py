@@ -64,6 +64,9 @@ def lib() -> ctypes.CDLL:
         L.mmattn_bwd.restype = ctypes.c_int
         L.mmattn_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
                                  ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+        L.mmattn_mfma_ceiling.restype = ctypes.c_int
+        L.mmattn_mfma_ceiling.argtypes = [ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_size_t,
+                                          ctypes.POINTER(ctypes.c_double), _vp]
         L.mmattn_stage_events.restype = ctypes.c_int
         L.mmattn_stage_events.argtypes = [ctypes.c_int, _vp, _vp]
         _lib = L
@@ -195,6 +198,15 @@ def bwd(q_loc, k, v, bits, blocks, block: int, o_loc, lse, do_loc, scale: Option
 
 
 STAGE_FWD, STAGE_DKV, STAGE_DQ = 0, 1, 2
+
+
+def mfma_ceiling(iters: int, random_operands: bool, sink: torch.Tensor, stream=None) -> float:
+    """mmattn_mfma_ceiling: enqueues the matrix-pipe-only kernel; returns its flop count."""
+    fl = ctypes.c_double(0.0)
+    rc = lib().mmattn_mfma_ceiling(int(iters), int(bool(random_operands)), _ptr(sink),
+                                   sink.numel() * sink.element_size(), ctypes.byref(fl), _stream(stream))
+    _check("mmattn_mfma_ceiling", rc)
+    return fl.value
 
 
 def stage_events(stage: int, ev_start: int, ev_stop: int):

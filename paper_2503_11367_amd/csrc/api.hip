@@ -39,6 +39,14 @@ int mmattn_stage_events(int stage, void* ev_start, void* ev_stop) {
     return MMATTN_OK;
 }
 
+int mmattn_mfma_ceiling(int32_t iters, int32_t random_operands, void* d_sink, size_t sink_bytes,
+                        double* flops, void* stream) {
+    if (!d_sink) return MMATTN_ERR_NULL;
+    if (iters < 1 || iters > (1 << 24)) return MMATTN_ERR_SHAPE;
+    if (sink_bytes < 2048) return MMATTN_ERR_WORKSPACE;
+    return launch_mfma_ceiling(iters, random_operands, (float*)d_sink, flops, (hipStream_t)stream);
+}
+
 const char* mmattn_version(void) { return "mmattn 0.1 (gfx950)"; }
 
 size_t mmattn_workspace_size(int op, int64_t S, int32_t n_blocks, int32_t block, int32_t Hq,

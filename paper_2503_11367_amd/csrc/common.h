@@ -50,6 +50,8 @@ __device__ __forceinline__ int64_t row_pos(const int32_t* blocks, int32_t block,
 }
 
 // ---- entry points implemented per translation unit (host side) -------------
+int launch_mfma_ceiling(int32_t iters, int32_t random_operands, float* sink, double* flops,
+                        hipStream_t st);
 int launch_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* sample_off,
                   int32_t n_samples, int64_t S, uint64_t* d_bits, void* ws, hipStream_t st);
 int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
