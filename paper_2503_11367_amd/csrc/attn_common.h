@@ -31,11 +31,6 @@ __device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// position p (0..15) inside a stored group of 16  ->  logical index
-__host__ __device__ inline int perm16_index_of_pos(int p) {
-    return p < 4 ? p : (p < 8 ? p + 4 : (p < 12 ? p - 4 : p));
-}
-
 // row of a 32x32 C tile held in register r by a lane of half hh
 __device__ __forceinline__ int c_row(int r, int hh) { return 8 * (r >> 2) + 4 * hh + (r & 3); }
 

@@ -6,18 +6,19 @@
 //                                      Hq/Hkv query heads of the KV head)
 //   dQ = scale dS K
 // Launches:
-//   bwd_prep_kernel  Delta and LSE in base-2 units, padded to whole q-tiles, and
-//                  head-major copies of Q and dO for the key-outer pass;
+//   bwd_prep_kernel  Delta and LSE in base-2 units, padded to whole q-tiles, every
+//                  row's mask inputs, and head-major copies of Q and dO for the
+//                  key-outer pass;
 //   dkv_kernel     key-outer: a workgroup owns 128 keys of one KV head and streams
-//                  the active 32-row query tiles of every head of the group
-//                  through an LDS ring; per 32-key block one wavefront forms P
-//                  and accumulates dV^T, its partner takes P one step later and
-//                  accumulates dK^T.  When there are too few (k-tile, KV head) units to fill
-//                  the chip, a unit's step list is cut into chunks that run as
-//                  separate workgroups (the intra-GPU balancing idea of paper
-//                  section 3.2.2 applied to the key-outer pass: split the work
-//                  of a block, write partial results, aggregate in one more
-//                  launch); the partials are fp32 and summed in a fixed order;
+//                  the active 64-row query tiles of its share of the group's heads
+//                  through LDS rings; per 32-key block one wavefront forms P and
+//                  accumulates dV^T, its partner takes P one step later and
+//                  accumulates dK^T.  When there are too few (k-tile, KV head) units
+//                  to fill the chip, a unit's heads are split over several workgroups
+//                  (the intra-GPU balancing idea of paper section 3.2.2 applied to
+//                  the key-outer pass: split the work of a block, write partial
+//                  results, aggregate in one more launch); the partials are fp32 and
+//                  summed in a fixed order by dkv_reduce_kernel;
 //   dq_kernel      query-outer, same shape as the forward kernel.
 // All contractions are 32x32x16 bf16 MFMAs.  Tiles go global -> LDS directly
 // (no registers) into rotation-swizzled layouts; a tile that is needed both as
@@ -736,10 +737,37 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         }
     };
 
-    RowFragAddr<KT, D> krow;
-    TrFragAddr<KT, D> ktr;
-    krow.init(lane);
-    ktr.init(lane);
+    // fragment addresses (LDS byte addresses at ring stage 0): K and V rows share the lane
+    // pattern (same tile layout) but live in different rings; K is also read transposed
+    constexpr int PER = 16 * KT::RPS, NV = PER / 8;
+    uint32_t krow_a[NDS], vrow_a[NDS], ktr_a[NDB][NV];
+    {
+        RowFragAddr<KT, D> fr;
+        TrFragAddr<KT, D> ft;
+        fr.init(lane);
+        ft.init(lane);
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) {
+            krow_a[ds] = lds_addr_of(sm.k[0]) + (uint32_t)fr.off[ds];
+            vrow_a[ds] = lds_addr_of(sm.v[0]) + (uint32_t)fr.off[ds];
+        }
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int v = 0; v < NV; ++v) ktr_a[db][v] = lds_addr_of(sm.k[0]) + (uint32_t)ft.off[db][v];
+    }
+    const uint32_t kss_a = lds_addr_of(sm.kss) + hh * 16;     // key words of rows 8*q4 + 4*hh + 0..3
+    auto read_row = [&](uint32_t a, int imm) __attribute__((always_inline)) -> bf16x8 {
+        return __builtin_bit_cast(bf16x8, *(lds_u4)(uintptr_t)(a + (uint32_t)imm));
+    };
+    auto read_tr = [&](int imm, int ks, int db) __attribute__((always_inline)) -> bf16x8 {
+        const int r_lo = ks * 16, r_hi = ks * 16 + 8;
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)(
+            ktr_a[db][(r_lo % PER) / 8] + (uint32_t)(imm + (r_lo / PER) * PER * RB)));
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)(
+            ktr_a[db][(r_hi % PER) / 8] + (uint32_t)(imm + (r_hi / PER) * PER * RB)));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
 
     uint32_t list_chunk = lane < n_active ? klist[lane] : 0u;
     auto entry_at = [&](int it) -> uint32_t {
@@ -758,73 +786,79 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         }
     }
 
-    int st = 0;
-    for (int it = 0; it < n_active; ++it) {
-        const uint32_t entry = pend[0];
-        const bool partial = (entry & kPartialFlag) != 0;
-        const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kDqBN;
-        const int younger = min(NST - 2, n_active - 1 - it);
-        if (younger >= 2) wait_vmcnt<(NST > 3 ? 4 * NI : 0)>();
-        else if (younger == 1) wait_vmcnt<(NST > 2 ? 2 * NI : 0)>();
-        else wait_vmcnt<0>();
-        __syncthreads();
-        uint32_t fresh = 0u;
-        if (it + NST - 1 < n_active) {
-            if (((it + NST - 1) & 63) == 0) {
-                const int j = it + NST - 1 + lane;
-                list_chunk = j < n_active ? klist[j] : 0u;
-                wait_vmcnt<0>();           // awaited here so that no wait is needed after the branch
-            }
-            fresh = entry_at(it + NST - 1);
-            int sn = st + NST - 1;
-            if (sn >= NST) sn -= NST;
-            issue_tile(fresh, sn);
-        }
+    // The ring position of tile `it` is it mod NST; the loop is unrolled NST-fold so that
+    // every LDS offset is an immediate.
+    for (int it0 = 0; it0 < n_active; it0 += NST) {
 #pragma unroll
-        for (int j = 0; j + 1 < NST - 1; ++j) pend[j] = pend[j + 1];
-        pend[NST - 2] = fresh;
-        if (partial) {
-            if (tid < kDqBN) sm.kss[tid] = word_ss(bits[k0 + tid]);
+        for (int st = 0; st < NST; ++st) {
+            const int it = it0 + st;
+            if (it >= n_active) break;
+            const int sn = (st + NST - 1) % NST;
+            const uint32_t entry = pend[0];
+            const bool partial = (entry & kPartialFlag) != 0;
+            const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kDqBN;
+            const int younger = min(NST - 2, n_active - 1 - it);
+            if (younger >= 2) wait_vmcnt<(NST > 3 ? 4 * NI : 0)>();
+            else if (younger == 1) wait_vmcnt<(NST > 2 ? 2 * NI : 0)>();
+            else wait_vmcnt<0>();
             __syncthreads();
-        }
-        const unsigned char* kb_base = sm.k[st];
-        const unsigned char* vb_base = sm.v[st];
-
-        bf16x8 dsf[4];
-        auto half = [&](auto KB) __attribute__((always_inline)) {
-            constexpr int kb = decltype(KB)::value;
-            floatx16 s, dp;
+            uint32_t fresh = 0u;
+            if (it + NST - 1 < n_active) {
+                if (((it + NST - 1) & 63) == 0) {
+                    const int j = it + NST - 1 + lane;
+                    list_chunk = j < n_active ? klist[j] : 0u;
+                    wait_vmcnt<0>();       // awaited here so that no wait is needed after the branch
+                }
+                fresh = entry_at(it + NST - 1);
+                issue_tile(fresh, sn);
+            }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-            for (int ds = 0; ds < NDS; ++ds)
-                s = mfma32(krow.read(kb_base, kb, ds), qf[ds], s);
-#pragma unroll
-            for (int ds = 0; ds < NDS; ++ds)
-                dp = mfma32(krow.read(vb_base, kb, ds), dof[ds], dp);
+            for (int j = 0; j + 1 < NST - 1; ++j) pend[j] = pend[j + 1];
+            pend[NST - 2] = fresh;
             if (partial) {
+                if (tid < kDqBN) sm.kss[tid] = word_ss(bits[k0 + tid]);
+                __syncthreads();
+            }
+            constexpr int kHalf = 32 * RB;
+            const int tile = st * kStageBytes;
+
+            bf16x8 dsf[4];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                floatx16 s, dp;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+                // two independent accumulation chains, alternated
+#pragma unroll
+                for (int ds = 0; ds < NDS; ++ds) {
+                    s = mfma32(read_row(krow_a[ds], tile + kb * kHalf), qf[ds], s);
+                    dp = mfma32(read_row(vrow_a[ds], tile + kb * kHalf), dof[ds], dp);
+                }
+                if (partial) {
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const u32x4 kw = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(kb * 128 + q4 * 32));
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
+                            if (!visible(q_ss, q_causal, q_pos, kw[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
+                        }
+                    }
+                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int kl = kb * 32 + c_row(r, hh);
-                    if (!visible(q_ss, q_causal, q_pos, sm.kss[kl], k0 + kl)) s[r] = -INFINITY;
+                    // masked entries are -inf: exp2 gives 0 (padding rows have LSE = +inf)
+                    const float p = __builtin_amdgcn_exp2f(s[r] * scale_log2 - my_lse2);
+                    dsf[kb * 2 + (r >> 3)][r & 7] = (__bf16)(p * (dp[r] - my_delta));
                 }
             }
+            // dQ^T += K^T dS^T
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                // masked entries are -inf: exp2 gives 0 (padding rows have LSE = +inf)
-                const float p = __builtin_amdgcn_exp2f(s[r] * scale_log2 - my_lse2);
-                dsf[kb * 2 + (r >> 3)][r & 7] = (__bf16)(p * (dp[r] - my_delta));
-            }
-        };
-        half(std::integral_constant<int, 0>{});
-        half(std::integral_constant<int, 1>{});
-        // dQ^T += K^T dS^T
+            for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-                dq[db] = mfma32(ktr.read(kb_base, ks, db), dsf[ks], dq[db]);
-        if (++st == NST) st = 0;
+                for (int db = 0; db < NDB; ++db)
+                    dq[db] = mfma32(read_tr(tile, ks, db), dsf[ks], dq[db]);
+        }
     }
 
     if (row_ok) {
