@@ -171,6 +171,12 @@ struct TilePlan {
     int32_t* ticket;     // zeroed counter used by the list builder (one per plan)
 };
 
+// slices of a q-tile's active k-tile list (forward): cmax slices of csz list entries;
+// cmax == 1 means the list is not split
+struct FwdSplit {
+    int32_t cmax, csz;
+};
+
 // transposed plan for key-outer kernels: for each k-tile the active q-tiles
 struct TilePlanT {
     int32_t nq, nk, tq, tk;

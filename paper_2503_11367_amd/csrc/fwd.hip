@@ -27,6 +27,7 @@
 // slot by slot (see `step`).
 // FULL tiles skip the predicate; PARTIAL tiles evaluate it per element from the
 // 64-bit words (query word in registers, key words from LDS).
+#include <algorithm>
 #include "attn_common.h"
 
 namespace mm {
@@ -51,8 +52,9 @@ __global__ void __launch_bounds__(256 * HPW, 2)
 fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
            const ushort_t* __restrict__ V, const uint64_t* __restrict__ bits,
            const int32_t* __restrict__ blocks, int32_t block, int64_t n_loc, int64_t S,
-           int32_t Hq, int32_t Hkv, float scale_log2, TilePlan plan,
-           const int32_t* __restrict__ err, ushort_t* __restrict__ O, float* __restrict__ LSE) {
+           int32_t Hq, int32_t Hkv, float scale_log2, TilePlan plan, FwdSplit split,
+           const int32_t* __restrict__ err, ushort_t* __restrict__ O, float* __restrict__ LSE,
+           float* __restrict__ Opart, float* __restrict__ MLpart) {
     constexpr int NDS = D / 16;           // contraction steps over head_dim
     constexpr int NDB = D / 32;           // 32-wide output blocks over head_dim
     constexpr int NW = 4 * HPW;           // wavefronts per workgroup
@@ -69,8 +71,10 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // round-robin to the 8 XCDs) so that one head's K/V stays in one L2 --------
     const int rep = Hq / Hkv;
     int tile_rank, h0;                    // h0: first of the HPW heads of this workgroup
+    const int items = gridDim.x / split.cmax;
+    const int chunk = blockIdx.x / items; // which slice of the q-tile's k-tile list (0 when not split)
     {
-        const int bid = blockIdx.x;
+        const int bid = blockIdx.x - chunk * items;
         if (Hkv % 8 == 0) {
             const int x = bid & 7, slot = bid >> 3, hx = Hq / 8 / HPW;
             tile_rank = slot / hx;
@@ -84,8 +88,12 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     }
     const int g = h0 / rep;
     const int qt = plan.qorder[tile_rank];
-    const int n_active = plan.kcount[qt];
-    const uint32_t* klist = plan.klist + (int64_t)qt * plan.nk;
+    // this workgroup's slice of the active list: split.csz entries from chunk * csz on
+    const int kc_total = plan.kcount[qt];
+    const int nchunk = max(1, (kc_total + split.csz - 1) / split.csz);
+    if (chunk >= nchunk) return;          // workgroup-uniform
+    const int n_active = max(0, min(kc_total - chunk * split.csz, split.csz));
+    const uint32_t* klist = plan.klist + (int64_t)qt * plan.nk + chunk * split.csz;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -409,34 +417,120 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #undef MM_SLOT_END
     // ---- epilogue -----------------------------------------------------------------
     const float l_tot = l_run + __shfl_xor(l_run, 32);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (row_ok) {
-        ushort_t* op = O + (row * Hq + h) * (int64_t)D + 4 * hh;
+    if (!row_ok) return;
+    if (nchunk > 1) {
+        // partial result of this slice: unnormalised O^T, the shift and the row sum
+        const int64_t rows = (int64_t)plan.nq * kFwdBM;
+        const int64_t pr = ((int64_t)chunk * rows + row) * Hq + h;
+        float* op = Opart + pr * D + 4 * hh;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                bf16x4 out;
+                floatx4 out;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) out[u] = (__bf16)(o[db][c * 4 + u] * inv);
-                *(u32x2*)(op + db * 32 + c * 8) = __builtin_bit_cast(u32x2, out);
+                for (int u = 0; u < 4; ++u) out[u] = o[db][c * 4 + u];
+                *(floatx4*)(op + db * 32 + c * 8) = out;
             }
-        if (hh == 0)
-            LSE[(int64_t)h * n_loc + row] =
-                l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+        if (hh == 0) {
+            MLpart[pr * 2] = m_run;
+            MLpart[pr * 2 + 1] = l_tot;
+        }
+        return;
     }
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    ushort_t* op = O + (row * Hq + h) * (int64_t)D + 4 * hh;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            bf16x4 out;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) out[u] = (__bf16)(o[db][c * 4 + u] * inv);
+            *(u32x2*)(op + db * 32 + c * 8) = __builtin_bit_cast(u32x2, out);
+        }
+    if (hh == 0)
+        LSE[(int64_t)h * n_loc + row] =
+            l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+}
+
+// Aggregation of the slices of split q-tiles (paper section 3.2.2: partial results of
+// the sub-blocks are combined by one more kernel): with shift m_c, row sum l_c and
+// unnormalised output o_c per slice, O = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m)
+// for m = max m_c.  One thread per (row, head, 4 head-dim values).
+__global__ void __launch_bounds__(256)
+fwd_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int32_t Hq, int32_t D,
+                   const int32_t* __restrict__ err, const float* __restrict__ Opart,
+                   const float* __restrict__ MLpart, ushort_t* __restrict__ O,
+                   float* __restrict__ LSE) {
+    if (*err) return;
+    const int dq4 = D / 4;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t rh = gid / dq4;
+    const int d0 = (int)(gid % dq4) * 4;
+    const int64_t row = rh / Hq;
+    const int h = (int)(rh % Hq);
+    if (row >= n_loc) return;
+    const int kc_total = plan.kcount[row / kFwdBM];
+    const int nchunk = max(1, (kc_total + split.csz - 1) / split.csz);
+    if (nchunk == 1) return;              // written by the attention kernel itself
+    const int64_t rows = (int64_t)plan.nq * kFwdBM;
+    float m = -INFINITY;
+    for (int c = 0; c < nchunk; ++c) {
+        const float* ml = MLpart + (((int64_t)c * rows + row) * Hq + h) * 2;
+        if (ml[1] > 0.f) m = fmaxf(m, ml[0]);
+    }
+    floatx4 num = {0.f, 0.f, 0.f, 0.f};
+    float den = 0.f;
+    for (int c = 0; c < nchunk; ++c) {
+        const int64_t pr = ((int64_t)c * rows + row) * Hq + h;
+        const float lc = MLpart[pr * 2 + 1];
+        if (!(lc > 0.f)) continue;
+        const float w = __builtin_amdgcn_exp2f(MLpart[pr * 2] - m);
+        const floatx4 oc = *(const floatx4*)(Opart + pr * D + d0);
+        num += oc * w;
+        den += lc * w;
+    }
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+    bf16x4 out;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) out[u] = (__bf16)(num[u] * inv);
+    *(u32x2*)(O + (row * Hq + h) * (int64_t)D + d0) = __builtin_bit_cast(u32x2, out);
+    if (d0 == 0)
+        LSE[(int64_t)h * n_loc + row] = den > 0.f ? (m + __builtin_amdgcn_logf(den)) * kLn2 : -INFINITY;
 }
 
 // ---- host side ---------------------------------------------------------------------
 struct FwdLayout {
-    size_t err, clean_blocks, cls, kcount, klist, qorder, total;
+    size_t err, clean_blocks, cls, kcount, klist, qorder, opart, mlpart, total;
     int32_t nq, nk;
+    FwdSplit split;
 };
 
-static FwdLayout fwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks) {
+// Intra-GPU balancing (paper section 3.2.2): when a share has too few (q-tile, head
+// group) work items to fill the chip, every q-tile's active k-tile list is cut into
+// slices of `csz` tiles that run as separate workgroups and write partial results.
+static FwdSplit fwd_split(int32_t nq, int32_t nk, int32_t Hq, int32_t Hkv) {
+    const int hpw = (Hq / Hkv) % 2 == 0 ? 2 : 1;
+    const int64_t items = (int64_t)nq * (Hq / hpw);
+    int64_t cmax = 1;
+    if (items < 512) {
+        cmax = (1024 + items - 1) / items;            // aim at about 1024 workgroups
+        cmax = std::min<int64_t>(cmax, std::max(1, nk / 2));   // at least two tiles per slice
+        cmax = std::min<int64_t>(cmax, 64);
+    }
+    FwdSplit sp;
+    sp.csz = (int32_t)((nk + cmax - 1) / cmax);
+    sp.cmax = (nk + sp.csz - 1) / sp.csz;            // no empty trailing slices
+    return sp;
+}
+
+static FwdLayout fwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t Hq, int32_t Hkv,
+                            int32_t D) {
     FwdLayout L;
     L.nq = (int32_t)((n_loc + kFwdBM - 1) / kFwdBM);
     L.nk = (int32_t)(S / kFwdBN);
+    L.split = fwd_split(L.nq, L.nk, Hq, Hkv);
     size_t off = 0;
     L.err = off;          off += 256;
     L.clean_blocks = off; off += align_up((size_t)n_blocks * 4, 256);
@@ -444,29 +538,35 @@ static FwdLayout fwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks) {
     L.kcount = off;       off += align_up((size_t)L.nq * 4, 256);
     L.klist = off;        off += align_up((size_t)L.nq * L.nk * 4, 256);
     L.qorder = off;       off += align_up((size_t)L.nq * 4, 256);
+    const size_t prow = L.split.cmax > 1 ? (size_t)L.split.cmax * L.nq * kFwdBM * Hq : 0;
+    L.opart = off;        off += align_up(prow * D * 4, 256);
+    L.mlpart = off;       off += align_up(prow * 8, 256);
     L.total = off;
     return L;
 }
 
 size_t fwd_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t D) {
-    (void)Hq; (void)Hkv; (void)D;
     // n_blocks is not known here; n_loc/16 bounds it (block >= 16)
-    return fwd_layout(S, n_loc, (int32_t)(n_loc / 16 + 1)).total;
+    return fwd_layout(S, n_loc, (int32_t)(n_loc / 16 + 1), Hq, Hkv, D).total;
 }
 
 template <int D, int HPW, int NST>
 static void launch_fwd_kernel(const AttnArgs& a, int64_t n_loc, int32_t nq, float scale_log2,
-                              const int32_t* clean, const TilePlan& plan, const int32_t* err, void* o,
-                              float* lse, hipStream_t st) {
-    const unsigned grid = (unsigned)((int64_t)nq * a.Hq / HPW);
+                              const int32_t* clean, const TilePlan& plan, const FwdSplit& split,
+                              const int32_t* err, void* o, float* lse, float* opart, float* mlpart,
+                              hipStream_t st) {
+    const unsigned grid = (unsigned)((int64_t)nq * a.Hq / HPW * split.cmax);
     hipLaunchKernelGGL((fwd_kernel<D, HPW, NST>), dim3(grid), dim3(256 * HPW), 0, st,
                        (const ushort_t*)a.q, (const ushort_t*)a.k, (const ushort_t*)a.v, a.bits, clean,
-                       a.block, n_loc, a.S, a.Hq, a.Hkv, scale_log2, plan, err, (ushort_t*)o, lse);
+                       a.block, n_loc, a.S, a.Hq, a.Hkv, scale_log2, plan, split, err, (ushort_t*)o,
+                       lse, opart, mlpart);
 }
 
 int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st) {
     const int64_t n_loc = (int64_t)a.n_blocks * a.block;
-    const FwdLayout L = fwd_layout(a.S, n_loc, (int32_t)(n_loc / 16 + 1));
+    const FwdLayout L = fwd_layout(a.S, n_loc, (int32_t)(n_loc / 16 + 1), a.Hq, a.Hkv, a.D);
+    float* opart = (float*)((char*)ws + L.opart);
+    float* mlpart = (float*)((char*)ws + L.mlpart);
     char* base = (char*)ws;
     int32_t* err = (int32_t*)(base + L.err);
     int32_t* clean = (int32_t*)(base + L.clean_blocks);
@@ -490,11 +590,16 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
     const bool pair = (a.Hq / a.Hkv) % 2 == 0;     // two heads of a KV group per workgroup
     stage_begin(MMATTN_STAGE_FWD, st);
     if (a.D == 128) {
-        if (pair) launch_fwd_kernel<128, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
-        else      launch_fwd_kernel<128, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
+        if (pair) launch_fwd_kernel<128, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, o, lse, opart, mlpart, st);
+        else      launch_fwd_kernel<128, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, o, lse, opart, mlpart, st);
     } else {
-        if (pair) launch_fwd_kernel<64, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
-        else      launch_fwd_kernel<64, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, err, o, lse, st);
+        if (pair) launch_fwd_kernel<64, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, o, lse, opart, mlpart, st);
+        else      launch_fwd_kernel<64, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, o, lse, opart, mlpart, st);
+    }
+    if (L.split.cmax > 1) {
+        const int64_t threads = n_loc * a.Hq * (a.D / 4);
+        hipLaunchKernelGGL(fwd_combine_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           plan, L.split, n_loc, a.Hq, a.D, err, opart, mlpart, (ushort_t*)o, lse);
     }
     stage_end(MMATTN_STAGE_FWD, st);
     MM_LAUNCH_CHECK();

@@ -74,6 +74,15 @@ def test_random_layouts(seed, D):
     run_case(lay, blocks, block, Hq=4, Hkv=2, D=D, seed=20 + seed)
 
 
+def test_few_work_items_split_into_list_slices():
+    """Shares with few (q-tile, head) work items cut every q-tile's k-tile list
+    into slices run by separate workgroups and aggregate the partial results:
+    4096 keys, 2 head pairs -> 16 slices of 4 tiles, ragged at the diagonal."""
+    lay = wl.layout_random(91, S=4096, n_samples=2, noncausal_prob=0.0)
+    run_case(lay, list(range(0, 32, 3)), 128, Hq=4, Hkv=2, D=128, seed=51)
+    run_case(lay, [31, 2, 17], 128, Hq=2, Hkv=2, D=64, seed=52)
+
+
 def test_unsorted_block_list_and_mha():
     lay = wl.layout_random(77, S=512, n_samples=2)
     run_case(lay, [5, 0, 3], 64, Hq=2, Hkv=2, D=128, seed=31)
