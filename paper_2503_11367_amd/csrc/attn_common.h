@@ -176,6 +176,25 @@ struct TilePlan {
 struct FwdSplit {
     int32_t cmax, csz;
 };
+// Intra-GPU balancing (paper section 3.2.2) for the query-outer kernels: when a share
+// has too few (q-tile, head group) work items to fill the chip, every q-tile's active
+// k-tile list is cut into slices of `csz` tiles that run as separate workgroups and
+// write partial results, aggregated by one more launch.
+inline FwdSplit list_split(int32_t nq, int32_t nk, int32_t Hq, int32_t Hkv) {
+    const int hpw = (Hq / Hkv) % 2 == 0 ? 2 : 1;
+    const int64_t items = (int64_t)nq * (Hq / hpw);
+    int64_t cmax = 1;
+    if (items < 512) {
+        cmax = (1024 + items - 1) / items;                    // aim at about 1024 workgroups
+        const int64_t most = nk / 2 > 1 ? nk / 2 : 1;         // at least two tiles per slice
+        if (cmax > most) cmax = most;
+        if (cmax > 64) cmax = 64;
+    }
+    FwdSplit sp;
+    sp.csz = (int32_t)((nk + cmax - 1) / cmax);
+    sp.cmax = (nk + sp.csz - 1) / sp.csz;                     // no empty trailing slices
+    return sp;
+}
 
 // transposed plan for key-outer kernels: for each k-tile the active q-tiles
 struct TilePlanT {

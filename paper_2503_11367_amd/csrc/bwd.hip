@@ -647,7 +647,8 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
           const uint64_t* __restrict__ bits, const int32_t* __restrict__ blocks, int32_t block,
           int64_t n_loc, int64_t n_pad, int64_t S, int32_t Hq, int32_t Hkv, float scale,
           float scale_log2, const float* __restrict__ ld_g,
-          TilePlan plan, const int32_t* __restrict__ err, ushort_t* __restrict__ dQ) {
+          TilePlan plan, FwdSplit split, const int32_t* __restrict__ err,
+          ushort_t* __restrict__ dQ, float* __restrict__ dQpart) {
     constexpr int NDS = D / 16, NDB = D / 32;
     constexpr int NW = 4 * HPW;
     constexpr int RB = D * 2;
@@ -661,8 +662,10 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 
     const int rep = Hq / Hkv;
     int tile_rank, h0;
+    const int items = gridDim.x / split.cmax;
+    const int chunk = blockIdx.x / items; // which slice of the q-tile's k-tile list (0 when not split)
     {
-        const int bid = blockIdx.x;
+        const int bid = blockIdx.x - chunk * items;
         if (Hkv % 8 == 0) {
             const int x = bid & 7, slot = bid >> 3, hx = Hq / 8 / HPW;
             tile_rank = slot / hx;
@@ -676,8 +679,11 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     }
     const int g = h0 / rep;
     const int qt = plan.qorder[tile_rank];
-    const int n_active = plan.kcount[qt];
-    const uint32_t* klist = plan.klist + (int64_t)qt * plan.nk;
+    const int kc_total = plan.kcount[qt];
+    const int nchunk = max(1, (kc_total + split.csz - 1) / split.csz);
+    if (chunk >= nchunk) return;          // workgroup-uniform
+    const int n_active = max(0, min(kc_total - chunk * split.csz, split.csz));
+    const uint32_t* klist = plan.klist + (int64_t)qt * plan.nk + chunk * split.csz;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -861,27 +867,66 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         }
     }
 
-    if (row_ok) {
-        ushort_t* op = dQ + (row * Hq + h) * (int64_t)D + 4 * hh;
+    if (!row_ok) return;
+    if (nchunk > 1) {
+        // this slice's partial sum, fp32, summed over the slices by dq_combine_kernel
+        float* op = dQpart + (((int64_t)chunk * n_pad + row) * Hq + h) * D + 4 * hh;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                bf16x4 out;
+                floatx4 out;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) out[u] = (__bf16)(dq[db][c * 4 + u] * scale);
-                *(u32x2*)(op + db * 32 + c * 8) = __builtin_bit_cast(u32x2, out);
+                for (int u = 0; u < 4; ++u) out[u] = dq[db][c * 4 + u] * scale;
+                *(floatx4*)(op + db * 32 + c * 8) = out;
             }
+        return;
     }
+    ushort_t* op = dQ + (row * Hq + h) * (int64_t)D + 4 * hh;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            bf16x4 out;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) out[u] = (__bf16)(dq[db][c * 4 + u] * scale);
+            *(u32x2*)(op + db * 32 + c * 8) = __builtin_bit_cast(u32x2, out);
+        }
+}
+
+// sums the slices of split q-tiles in a fixed order; one thread per 4 elements
+__global__ void __launch_bounds__(256)
+dq_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int64_t n_pad, int32_t Hq, int32_t D,
+                  const int32_t* __restrict__ err, const float* __restrict__ dQpart,
+                  ushort_t* __restrict__ dQ) {
+    if (*err) return;
+    const int dq4 = D / 4;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t rh = gid / dq4;
+    const int d0 = (int)(gid % dq4) * 4;
+    const int64_t row = rh / Hq;
+    const int h = (int)(rh % Hq);
+    if (row >= n_loc) return;
+    const int kc_total = plan.kcount[row / kDqBM];
+    const int nchunk = max(1, (kc_total + split.csz - 1) / split.csz);
+    if (nchunk == 1) return;              // written by dq_kernel itself
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < nchunk; ++c)
+        acc += *(const floatx4*)(dQpart + (((int64_t)c * n_pad + row) * Hq + h) * D + d0);
+    bf16x4 out;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) out[u] = (__bf16)acc[u];
+    *(u32x2*)(dQ + (row * Hq + h) * (int64_t)D + d0) = __builtin_bit_cast(u32x2, out);
 }
 
 // ---------------------------------------------------------------- host -------
 struct BwdLayout {
     size_t err, clean_blocks, ld, qh, doh, cls_a, kcount, klist, qorder, cls_b, qcount, qlist,
-        korder, acc_k, acc_v, total;
+        korder, acc_k, acc_v, dq_part, total;
     int32_t nq_a, nk_a, nq_b, nk_b;
     int64_t n_pad;
     KvChunking ch;
+    FwdSplit split;                   // list slices of the query-outer (dQ) pass
 };
 
 // Split the query heads of a (k-tile, KV head) unit over several workgroups only
@@ -926,6 +971,8 @@ static BwdLayout bwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     const size_t acc = L.ch.cmax > 1 ? (size_t)L.ch.cmax * S * Hkv * D * 4 : 0;
     L.acc_k = take(acc);
     L.acc_v = take(acc);
+    L.split = list_split(L.nq_a, L.nk_a, Hq, Hkv);
+    L.dq_part = take(L.split.cmax > 1 ? (size_t)L.split.cmax * L.n_pad * Hq * D * 4 : 0);
     L.total = off;
     return L;
 }
@@ -937,13 +984,13 @@ size_t bwd_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t 
 template <int D, int HPW, int NST>
 static void launch_dq_kernel(const AttnArgs& a, const void* d_o, int64_t n_loc, const BwdLayout& L,
                              float scale_log2, const int32_t* clean, const float* ld,
-                             const TilePlan& pa, const int32_t* err, void* dq,
+                             const TilePlan& pa, const int32_t* err, void* dq, float* dq_part,
                              hipStream_t st) {
-    const unsigned grid = (unsigned)((int64_t)L.nq_a * a.Hq / HPW);
+    const unsigned grid = (unsigned)((int64_t)L.nq_a * a.Hq / HPW * L.split.cmax);
     hipLaunchKernelGGL((dq_kernel<D, HPW, NST>), dim3(grid), dim3(256 * HPW), 0, st,
                        (const ushort_t*)a.q, (const ushort_t*)a.k, (const ushort_t*)a.v,
                        (const ushort_t*)d_o, a.bits, clean, a.block, n_loc, L.n_pad, a.S, a.Hq, a.Hkv,
-                       a.scale, scale_log2, ld, pa, err, (ushort_t*)dq);
+                       a.scale, scale_log2, ld, pa, L.split, err, (ushort_t*)dq, dq_part);
 }
 
 template <int D>
@@ -1007,8 +1054,14 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     stage_end(MMATTN_STAGE_DKV, st);
     const bool pair = rep % 2 == 0;
     stage_begin(MMATTN_STAGE_DQ, st);
-    if (pair) launch_dq_kernel<D, 2, 3>(a, d_o, n_loc, L, scale_log2, clean, ld, pa, err, dq, st);
-    else      launch_dq_kernel<D, 1, 2>(a, d_o, n_loc, L, scale_log2, clean, ld, pa, err, dq, st);
+    float* dq_part = (float*)(base + L.dq_part);
+    if (pair) launch_dq_kernel<D, 2, 3>(a, d_o, n_loc, L, scale_log2, clean, ld, pa, err, dq, dq_part, st);
+    else      launch_dq_kernel<D, 1, 2>(a, d_o, n_loc, L, scale_log2, clean, ld, pa, err, dq, dq_part, st);
+    if (L.split.cmax > 1) {
+        const int64_t threads = n_loc * a.Hq * (D / 4);
+        hipLaunchKernelGGL(dq_combine_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           pa, L.split, n_loc, L.n_pad, a.Hq, D, err, dq_part, (ushort_t*)dq);
+    }
     stage_end(MMATTN_STAGE_DQ, st);
     MM_LAUNCH_CHECK();
     return MMATTN_OK;

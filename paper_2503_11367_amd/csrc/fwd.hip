@@ -27,7 +27,6 @@
 // slot by slot (see `step`).
 // FULL tiles skip the predicate; PARTIAL tiles evaluate it per element from the
 // 64-bit words (query word in registers, key words from LDS).
-#include <algorithm>
 #include "attn_common.h"
 
 namespace mm {
@@ -507,30 +506,12 @@ struct FwdLayout {
     FwdSplit split;
 };
 
-// Intra-GPU balancing (paper section 3.2.2): when a share has too few (q-tile, head
-// group) work items to fill the chip, every q-tile's active k-tile list is cut into
-// slices of `csz` tiles that run as separate workgroups and write partial results.
-static FwdSplit fwd_split(int32_t nq, int32_t nk, int32_t Hq, int32_t Hkv) {
-    const int hpw = (Hq / Hkv) % 2 == 0 ? 2 : 1;
-    const int64_t items = (int64_t)nq * (Hq / hpw);
-    int64_t cmax = 1;
-    if (items < 512) {
-        cmax = (1024 + items - 1) / items;            // aim at about 1024 workgroups
-        cmax = std::min<int64_t>(cmax, std::max(1, nk / 2));   // at least two tiles per slice
-        cmax = std::min<int64_t>(cmax, 64);
-    }
-    FwdSplit sp;
-    sp.csz = (int32_t)((nk + cmax - 1) / cmax);
-    sp.cmax = (nk + sp.csz - 1) / sp.csz;            // no empty trailing slices
-    return sp;
-}
-
 static FwdLayout fwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t Hq, int32_t Hkv,
                             int32_t D) {
     FwdLayout L;
     L.nq = (int32_t)((n_loc + kFwdBM - 1) / kFwdBM);
     L.nk = (int32_t)(S / kFwdBN);
-    L.split = fwd_split(L.nq, L.nk, Hq, Hkv);
+    L.split = list_split(L.nq, L.nk, Hq, Hkv);
     size_t off = 0;
     L.err = off;          off += 256;
     L.clean_blocks = off; off += align_up((size_t)n_blocks * 4, 256);
