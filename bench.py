@@ -129,7 +129,7 @@ def cpu_baseline(w, blocks, host_q, host_k, host_v, host_do, n_heads, pairs):
     from oracle import mask as om
     from paper_2503_11367_amd import workloads as wl
     lay = w.layout
-    f = om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal)
+    f = om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny)
     rows = oa.rows_of_blocks(blocks, w.N_B)
     cvt = lambda b: wl.bf16_bits_to_f32(b).astype(np.float64)
     Q, dO = cvt(host_q[:, :n_heads]), cvt(host_do[:, :n_heads])

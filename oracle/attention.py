@@ -59,7 +59,7 @@ def probabilities(Qh, Kg, vis, scale):
     return P, lse
 
 
-def forward(Q_loc, K, V, rows, sample, span, causal, scale=None, chunk=512):
+def forward(Q_loc, K, V, rows, sample, span, causal, scale=None, chunk=512, modality=None, attend=None):
     """Q_loc [n,Hq,D], K,V [S,Hkv,D] float64; rows[n] global positions.
     Returns O [n,Hq,D] and LSE [Hq,n]."""
     n, Hq, D = Q_loc.shape
@@ -71,7 +71,7 @@ def forward(Q_loc, K, V, rows, sample, span, causal, scale=None, chunk=512):
     k_idx = np.arange(S)
     for a in range(0, n, chunk):
         b = min(n, a + chunk)
-        vis = visible(rows[a:b], k_idx, sample, span, causal)
+        vis = visible(rows[a:b], k_idx, sample, span, causal, modality, attend)
         for h in range(Hq):
             g = h // rep
             P, lse = probabilities(Q_loc[a:b, h], K[:, g], vis, scale)
@@ -80,7 +80,8 @@ def forward(Q_loc, K, V, rows, sample, span, causal, scale=None, chunk=512):
     return O, LSE
 
 
-def backward(Q_loc, K, V, dO, rows, sample, span, causal, scale=None, chunk=512):
+def backward(Q_loc, K, V, dO, rows, sample, span, causal, scale=None, chunk=512, modality=None,
+             attend=None):
     """Returns dQ [n,Hq,D], dK [S,Hkv,D], dV [S,Hkv,D] (this rank's partial
     sums), all float64."""
     n, Hq, D = Q_loc.shape
@@ -93,7 +94,7 @@ def backward(Q_loc, K, V, dO, rows, sample, span, causal, scale=None, chunk=512)
     k_idx = np.arange(S)
     for a in range(0, n, chunk):
         b = min(n, a + chunk)
-        vis = visible(rows[a:b], k_idx, sample, span, causal)
+        vis = visible(rows[a:b], k_idx, sample, span, causal, modality, attend)
         for h in range(Hq):
             g = h // rep
             P, _ = probabilities(Q_loc[a:b, h], K[:, g], vis, scale)

@@ -14,6 +14,14 @@ Text is causal, a modality span is bidirectional within itself (and causal
 to what precedes it when its causal bit is set), packed samples never see
 each other.
 
+Generalisation with the attend-set of section 4.2 (the word records which
+modalities the token attends to): a span may be given a `deny` mask of
+modalities its tokens do not attend; its attend-set is then all ones minus
+those bits and the backward-looking term becomes
+  [causal(q) and k<=q and attend(q) has bit modality(k)].
+Tokens of the own span stay visible (same-span term).  With no deny masks
+every attend-set is all ones and the predicate is the one above.
+
 Word layout (LSB first, section 4.2: low bits = LLM and modality encoders,
 bit 63 = causal bit):
   bits 0-7   attend-set, bit m set = may attend modality m   (all set here)
@@ -26,7 +34,9 @@ Pins: tests/test_oracle_mask.py -- closed-form pair totals
 sum L(L+1)/2 + sum n(n-1)/2, all-text = lower triangle, one span covering
 everything = all ones, packed = block diagonal, the section-4.2 worked example
 (encoder tokens without the causal bit see only their own encoder's tokens;
-text tokens see every earlier token), encode/decode round trip.
+text tokens see every earlier token), encode/decode round trip; for the
+attend-set generalisation a mask written out by hand and the pair count
+(P1 count minus the denied backward pairs, counted by a separate loop).
 """
 import numpy as np
 
@@ -34,17 +44,21 @@ ATTEND_ALL = 0xFF
 CAUSAL_BIT = 63
 
 
-def token_fields(S, spans, sample_off, noncausal=None):
-    """Expand a layout into per-token arrays (sample, span, causal, modality).
+def token_fields(S, spans, sample_off, noncausal=None, deny=None):
+    """Expand a layout into per-token arrays (sample, span, causal, modality,
+    attend).
 
     spans: iterable of (start, len, modality) in increasing start order.
     sample_off: n_samples+1 offsets with [0]=0 and [-1]=S.
     noncausal: optional per-span flag; 1 clears the causal bit of that span.
+    deny: optional per-span 8-bit mask of modalities the span's tokens do not
+          attend (cleared from their attend-set).
     """
     sample = np.zeros(S, dtype=np.int64)
     span = np.zeros(S, dtype=np.int64)
     causal = np.ones(S, dtype=np.int64)
     modality = np.zeros(S, dtype=np.int64)
+    attend = np.full(S, ATTEND_ALL, dtype=np.int64)
     for i in range(len(sample_off) - 1):
         sample[sample_off[i]:sample_off[i + 1]] = i
     for j, (start, n, mod) in enumerate(spans):
@@ -52,22 +66,30 @@ def token_fields(S, spans, sample_off, noncausal=None):
         modality[start:start + n] = mod
         if noncausal is not None and noncausal[j]:
             causal[start:start + n] = 0
-    return sample, span, causal, modality
+        if deny is not None and deny[j]:
+            attend[start:start + n] = ATTEND_ALL & ~int(deny[j])
+    return sample, span, causal, modality, attend
 
 
-def visible(q_idx, k_idx, sample, span, causal):
-    """Boolean matrix vis[q,k] for global token index arrays q_idx, k_idx."""
+def visible(q_idx, k_idx, sample, span, causal, modality=None, attend=None):
+    """Boolean matrix vis[q,k] for global token index arrays q_idx, k_idx.
+    Without modality/attend every attend-set is taken as all ones."""
     q = np.asarray(q_idx)[:, None]
     k = np.asarray(k_idx)[None, :]
     same_sample = sample[q] == sample[k]
     back = (causal[q] == 1) & (k <= q)
+    if attend is not None:
+        back &= ((attend[q] >> modality[k]) & 1) == 1
     same_span = (span[q] != 0) & (span[q] == span[k])
     return same_sample & (back | same_span)
 
 
-def encode(sample, span, causal, modality):
+def encode(sample, span, causal, modality, attend=None):
     """Per-token 64-bit word from the fields, as uint64."""
-    w = np.full(sample.shape, ATTEND_ALL, dtype=np.uint64)
+    if attend is None:
+        w = np.full(sample.shape, ATTEND_ALL, dtype=np.uint64)
+    else:
+        w = attend.astype(np.uint64)
     w |= modality.astype(np.uint64) << np.uint64(8)
     w |= span.astype(np.uint64) << np.uint64(12)
     w |= sample.astype(np.uint64) << np.uint64(28)
@@ -76,10 +98,11 @@ def encode(sample, span, causal, modality):
 
 
 def decode(bits):
-    """Inverse of encode: (sample, span, causal, modality)."""
+    """Inverse of encode: (sample, span, causal, modality, attend)."""
     b = np.asarray(bits, dtype=np.uint64)
+    attend = (b & np.uint64(0xFF)).astype(np.int64)
     modality = ((b >> np.uint64(8)) & np.uint64(0xF)).astype(np.int64)
     span = ((b >> np.uint64(12)) & np.uint64(0xFFFF)).astype(np.int64)
     sample = ((b >> np.uint64(28)) & np.uint64(0xFFFF)).astype(np.int64)
     causal = ((b >> np.uint64(CAUSAL_BIT)) & np.uint64(1)).astype(np.int64)
-    return sample, span, causal, modality
+    return sample, span, causal, modality, attend

@@ -5,7 +5,8 @@
  * tests/test_oracle_tilemap.py.
  *
  *   vis(q,k) = sample[q]==sample[k] &&
- *              ((causal[q] && k<=q) || (span[q]!=0 && span[q]==span[k]))
+ *              ((causal[q] && k<=q && bit modality[k] of attend[q]) ||
+ *               (span[q]!=0 && span[q]==span[k]))
  *   cnt[i][j] = number of visible pairs in q-tile i x k-tile j
  *   cls = 0 EMPTY (cnt==0), 1 FULL (cnt==tq*tk), 2 PARTIAL
  *   W[i] = sum_j cnt[i][j]
@@ -13,7 +14,7 @@
 #include <stdint.h>
 
 int tilemap_ref(const int64_t* sample, const int64_t* span, const int64_t* causal,
-                int64_t S, int32_t tq, int32_t tk,
+                const int64_t* modality, const int64_t* attend, int64_t S, int32_t tq, int32_t tk,
                 uint8_t* cls, uint32_t* cnt, uint64_t* W)
 {
     if (S % tq || S % tk) return -1;
@@ -26,7 +27,7 @@ int tilemap_ref(const int64_t* sample, const int64_t* span, const int64_t* causa
             for (int64_t q = i * tq; q < (i + 1) * tq; ++q)
                 for (int64_t k = j * tk; k < (j + 1) * tk; ++k) {
                     int same_sample = sample[q] == sample[k];
-                    int back = causal[q] && k <= q;
+                    int back = causal[q] && k <= q && ((attend[q] >> modality[k]) & 1);
                     int same_span = span[q] != 0 && span[q] == span[k];
                     c += (uint32_t)(same_sample && (back || same_span));
                 }

@@ -28,10 +28,17 @@ class Layout:
     spans: List[Tuple[int, int, int]]          # (start, len, modality), sorted, disjoint
     sample_off: List[int]                      # n_samples+1 offsets, [0]=0, [-1]=S
     noncausal: List[int] = field(default_factory=list)   # per-span flag (0 = causal bit set)
+    deny: List[int] = field(default_factory=list)        # per-span mask of modalities NOT attended
 
     def __post_init__(self):
         if not self.noncausal:
             self.noncausal = [0] * len(self.spans)
+        if not self.deny:
+            self.deny = [0] * len(self.spans)
+
+    def span_flags(self) -> List[int]:
+        """Per-span flag words of the C ABI: bit 0 non-causal, bits 8-15 deny mask."""
+        return [int(n) | (int(d) << 8) for n, d in zip(self.noncausal, self.deny)]
 
 
 @dataclass
@@ -152,7 +159,7 @@ def layout_packed(seed: int = 1005, S: int = 65536, n_samples: int = 16,
 
 
 def layout_random(seed: int, S: int, n_samples: int = 1, max_spans: int = 4,
-                  noncausal_prob: float = 0.0) -> Layout:
+                  noncausal_prob: float = 0.0, deny_prob: float = 0.0) -> Layout:
     """Small randomised layout for parity sweeps: ragged, tile-unaligned spans."""
     rng = np.random.default_rng(seed)
     if n_samples > 1:
@@ -160,7 +167,7 @@ def layout_random(seed: int, S: int, n_samples: int = 1, max_spans: int = 4,
     else:
         cuts = []
     offs = [0] + cuts + [S]
-    spans, nc = [], []
+    spans, nc, dn = [], [], []
     for a, b in zip(offs[:-1], offs[1:]):
         L = b - a
         n_sp = int(rng.integers(0, max_spans + 1))
@@ -173,7 +180,12 @@ def layout_random(seed: int, S: int, n_samples: int = 1, max_spans: int = 4,
         sp, _ = _interleave(gaps, [(n, int(rng.integers(1, 3))) for n in sl], base=a)
         spans += sp
         nc += [int(rng.random() < noncausal_prob) for _ in sp]
-    return Layout(S, spans, offs, nc)
+        if deny_prob > 0.0:
+            # a denied set drawn from {text, image, audio}: bits 0..2
+            dn += [int(rng.integers(1, 8)) if rng.random() < deny_prob else 0 for _ in sp]
+        else:
+            dn += [0 for _ in sp]
+    return Layout(S, spans, offs, nc, dn)
 
 
 def workload(c: int) -> Workload:

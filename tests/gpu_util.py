@@ -10,7 +10,7 @@ DEV = "cuda"
 
 
 def fields(lay):
-    return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal)
+    return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny)
 
 
 def gpu_bits(lay):

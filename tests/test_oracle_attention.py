@@ -10,7 +10,7 @@ from paper_2503_11367_amd import workloads as wl
 
 def setup(lay, Hq, Hkv, D, seed, rows=None):
     rng = np.random.default_rng(seed)
-    f = om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal)
+    f = om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny)
     rows = np.arange(lay.S) if rows is None else rows
     Q = rng.standard_normal((len(rows), Hq, D))
     K = rng.standard_normal((lay.S, Hkv, D))

@@ -91,7 +91,7 @@ def test_causal_zigzag_balanced_and_lpt_converges():
     (up to the diagonal); section 3.2.1: LPT approaches perfect balance as the
     number of blocks grows."""
     lay = wl.Layout(4096, [], [0, 4096])
-    sample, span, causal, _ = om.token_fields(lay.S, lay.spans, lay.sample_off)
+    sample, span, causal = om.token_fields(lay.S, lay.spans, lay.sample_off)[:3]
     _, _, W = ot.tile_map_c(sample, span, causal, 64, 64)
     _, zl = ob.zigzag(W, 4)
     assert ob.imbalance(zl) < 1.001

@@ -10,12 +10,14 @@ from paper_2503_11367_amd import workloads as wl
 
 
 def fields(lay):
-    return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal)
+    return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny)
 
 
 def dense(lay):
-    sample, span, causal, _ = fields(lay)
+    sample, span, causal, modality, attend = fields(lay)
     idx = np.arange(lay.S)
+    if any(lay.deny):
+        return om.visible(idx, idx, sample, span, causal, modality, attend)
     return om.visible(idx, idx, sample, span, causal)
 
 
@@ -72,15 +74,75 @@ def test_paper_bitfield_example():
     assert v[3].tolist() == [False, False, True, True, False, False]
     assert v[4].tolist() == [True, True, True, True, True, False]
     assert v[5].tolist() == [True] * 6
-    sample, span, causal, modality = fields(lay)
+    sample, span, causal, modality, attend = fields(lay)
     bits = om.encode(sample, span, causal, modality)
     assert (int(bits[2]) >> 63) == 0 and (int(bits[4]) >> 63) == 1
     assert (int(bits[2]) >> 8) & 0xF == wl.IMAGE and (int(bits[4]) >> 8) & 0xF == wl.TEXT
     assert int(bits[4]) & 0xFF == 0xFF        # text attends all modalities
 
 
+def test_attend_set_rows_by_hand():
+    """text[0:2] audio[2:4] text[4:5] image[5:8] text[8:9]; the image span does not
+    attend audio: its rows lose the two audio columns, nothing else changes
+    (text rows still see the audio tokens, the span still sees itself)."""
+    lay = wl.Layout(9, [(2, 2, wl.AUDIO), (5, 3, wl.IMAGE)], [0, 9], deny=[0, 1 << wl.AUDIO])
+    expect = np.array([
+        [1, 0, 0, 0, 0, 0, 0, 0, 0],
+        [1, 1, 0, 0, 0, 0, 0, 0, 0],
+        [1, 1, 1, 1, 0, 0, 0, 0, 0],
+        [1, 1, 1, 1, 0, 0, 0, 0, 0],
+        [1, 1, 1, 1, 1, 0, 0, 0, 0],
+        [1, 1, 0, 0, 1, 1, 1, 1, 0],
+        [1, 1, 0, 0, 1, 1, 1, 1, 0],
+        [1, 1, 0, 0, 1, 1, 1, 1, 0],
+        [1, 1, 1, 1, 1, 1, 1, 1, 1]], dtype=bool)
+    assert np.array_equal(dense(lay), expect)
+    bits = om.encode(*fields(lay))
+    assert int(bits[5]) & 0xFF == 0xFF & ~(1 << wl.AUDIO) and int(bits[2]) & 0xFF == 0xFF
+
+
+def test_denying_own_modality_keeps_the_span_itself():
+    """A span that denies its own modality still sees its own tokens (same-span
+    term) but not an earlier span of that modality."""
+    lay = wl.Layout(8, [(1, 2, wl.IMAGE), (4, 3, wl.IMAGE)], [0, 8], deny=[0, 1 << wl.IMAGE])
+    v = dense(lay)
+    assert v[5].tolist() == [True, False, False, True, True, True, True, False]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_attend_set_pair_count(seed):
+    """Pairs under the attend-set predicate = pairs of the plain predicate minus
+    the backward pairs (query in a span, earlier key of a denied modality, same
+    sample, different span), counted here by an explicit loop over spans."""
+    lay = wl.layout_random(30 + seed, S=320, n_samples=1 + seed % 3, deny_prob=0.6)
+    sample, span, causal, modality, attend = fields(lay)
+    idx = np.arange(lay.S)
+    plain = int(om.visible(idx, idx, sample, span, causal).sum())
+    lost = 0
+    for j, (start, n, _) in enumerate(lay.spans):
+        if not lay.deny[j]:
+            continue
+        s0 = max(a for a in lay.sample_off if a <= start)        # the span's sample starts here
+        for k in range(s0, start):                                # keys before the span, same sample
+            if (lay.deny[j] >> int(modality[k])) & 1:
+                lost += n                                         # every token of the span loses key k
+    assert any(lay.deny) or lost == 0
+    assert int(dense(lay).sum()) == plain - lost
+
+
+def test_tile_map_c_with_attend_sets():
+    lay = wl.layout_random(44, S=512, n_samples=2, deny_prob=0.7)
+    f = fields(lay)
+    a = ot.tile_map(f[0], f[1], f[2], 64, 32, f[3], f[4])
+    b = ot.tile_map_c(f[0], f[1], f[2], 64, 32, f[3], f[4])
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    assert int(a[2].sum()) == int(dense(lay).sum())
+
+
 def test_encode_decode_round_trip():
     lay = wl.layout_packed(seed=7, S=4096, n_samples=5, span_lo=40, span_hi=300)
+    lay.deny = [(i % 3) << 1 for i in range(len(lay.spans))]
     f = fields(lay)
     bits = om.encode(*f)
     assert bits.dtype == np.uint64
@@ -102,7 +164,7 @@ def test_tiny_golden(golden_dir):
         elif line.startswith("C "):
             rows.append(line.split()[1])
     lay = wl.layout_tiny()
-    sample, span, causal, _ = fields(lay)
+    sample, span, causal = fields(lay)[:3]
     cls, cnt, Wo = ot.tile_map(sample, span, causal, 64, 64)
     assert Wo.tolist() == W and sum(W) == 163968 == closed_form_pairs(lay)
     sym = {ot.EMPTY: "E", ot.FULL: "F", ot.PARTIAL: "P"}
@@ -113,7 +175,7 @@ def test_tiny_golden(golden_dir):
 
 def test_all_text_tile_classes():
     lay = wl.Layout(256, [], [0, 256])
-    sample, span, causal, _ = fields(lay)
+    sample, span, causal = fields(lay)[:3]
     cls, cnt, W = ot.tile_map(sample, span, causal, 32, 32)
     for i in range(8):
         for j in range(8):
@@ -124,7 +186,7 @@ def test_all_text_tile_classes():
 
 def test_rect_tiles_and_dense_agree():
     lay = wl.layout_random(11, S=512, n_samples=2)
-    sample, span, causal, _ = fields(lay)
+    sample, span, causal = fields(lay)[:3]
     v = dense(lay)
     cls, cnt, W = ot.tile_map(sample, span, causal, 128, 64)
     ref = v.reshape(4, 128, 8, 64).sum(axis=(1, 3))
@@ -145,7 +207,7 @@ def test_c_tilemap_matches_numpy(seed):
 @pytest.mark.parametrize("c", [2, 3, 5])
 def test_workload_totals_closed_form(c):
     w = wl.workload(c)
-    sample, span, causal, _ = fields(w.layout)
+    sample, span, causal = fields(w.layout)[:3]
     cls, cnt, W = ot.tile_map_c(sample, span, causal, w.N_B, w.N_B)
     assert int(W.sum()) == closed_form_pairs(w.layout)
     if c == 2:
