@@ -50,7 +50,7 @@ def plan_on_gpu(w, device):
     the per-rank loads/offsets (the one readback on the path)."""
     from paper_2503_11367_amd import binding as mb
     lay = w.layout
-    bits = mb.mask_encode(lay.spans, lay.sample_off, lay.S, device=device, flags=lay.noncausal)
+    bits = mb.mask_encode(lay.spans, lay.sample_off, lay.S, device=device, flags=lay.span_flags())
     _, _, W = mb.tile_map(bits, w.N_B, w.N_B, want_cls=False)
     _, _, _, rblocks, load_h, off_h = mb.balance(W, w.P, host=True)
     return bits, W, rblocks, load_h, off_h

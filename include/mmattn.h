@@ -24,9 +24,11 @@
  * bits 8-11 own modality, bits 12-27 span id (0 = not in a bidirectional
  * span), bits 28-43 sample id, bit 63 causal bit.  Visibility of key k to
  * query q:
- *   sample(q)==sample(k) && ( (causal(q) && k<=q) ||
+ *   sample(q)==sample(k) && ( (causal(q) && k<=q && attend(q)[modality(k)]) ||
  *                             (span(q)!=0 && span(q)==span(k)) )
- * The attend-set and modality fields are carried but not consulted.
+ * Text tokens attend every modality; a span's attend-set is all ones minus its
+ * deny mask, so with no deny masks the backward term is plain causal
+ * visibility.  The attend-set has 8 bits: modalities are 0 (text) .. 7.
  *
  * Ownership: the caller owns every buffer and the stream.  The library
  * allocates no device memory, never synchronises the stream and keeps no
@@ -73,9 +75,12 @@ enum { MMATTN_TILE_EMPTY = 0, MMATTN_TILE_FULL = 1, MMATTN_TILE_PARTIAL = 2 };
 /* A bidirectional (image/audio/...) span.  Tokens outside every span are
  * causal text.  flags bit 0 (MMATTN_SPAN_NONCAUSAL) clears the causal bit of
  * the span's tokens: they then see only their own span (section 4.2's
- * encoder tokens "without the causal bit"). */
+ * encoder tokens "without the causal bit").  flags bits 8-15: mask of
+ * modalities (bit m = modality m, m in 0..7) that the span's tokens do not
+ * attend among the earlier tokens; their own span stays visible. */
 typedef struct { int64_t start, len; int32_t modality, flags; } mmattn_span;
 #define MMATTN_SPAN_NONCAUSAL 1
+#define MMATTN_SPAN_DENY_SHIFT 8   /* flags bits 8-15: modalities the span's tokens do NOT attend */
 #define MMATTN_MAX_SPANS   65535
 #define MMATTN_MAX_SAMPLES 65535
 #define MMATTN_MAX_BLOCKS  16384   /* nB accepted by mmattn_balance */
@@ -90,7 +95,7 @@ size_t mmattn_workspace_size(int op, int64_t S, int32_t n_blocks, int32_t block,
 
 /* Section 4.2: build the per-token 64-bit mask words.
  *   spans      host, n_spans entries sorted by start, disjoint, inside one
- *              sample each, modality in 1..15; span id = index+1
+ *              sample each, modality in 1..7; span id = index+1
  *   sample_off host, n_samples+1 increasing offsets, [0]=0, [n_samples]=S
  *   d_bits     device, S words, overwritten
  *   ws         device scratch (staging of the two host lists)

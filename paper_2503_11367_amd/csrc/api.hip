@@ -81,7 +81,8 @@ int mmattn_mask_encode(const mmattn_span* spans, int32_t n_spans, const int64_t*
     for (int j = 0; j < n_spans; ++j) {
         const mmattn_span& sp = spans[j];
         if (sp.len <= 0 || sp.start < prev_end || sp.start + sp.len > S) return MMATTN_ERR_LAYOUT;
-        if (sp.modality < 1 || sp.modality > 15) return MMATTN_ERR_LAYOUT;
+        if (sp.modality < 1 || sp.modality > 7) return MMATTN_ERR_LAYOUT;     // one attend bit each
+        if (sp.flags & ~(MMATTN_SPAN_NONCAUSAL | (0xFF << MMATTN_SPAN_DENY_SHIFT))) return MMATTN_ERR_LAYOUT;
         while (sample_off[smp + 1] <= sp.start) ++smp;
         if (sp.start + sp.len > sample_off[smp + 1]) return MMATTN_ERR_LAYOUT;   // crosses samples
         prev_end = sp.start + sp.len;

@@ -34,7 +34,7 @@ namespace mm {
 //   ld[Hq][2][n_pad] = LSE in base-2 units, then Delta = rowsum(dO o O), per head; rows
 //                      n_loc .. n_pad-1 are padding: LSE = +inf (probability 0), Delta = 0;
 //                      followed by [3][n_pad] uint32: every local row's sample/span field,
-//                      causal flag and sequence position (the mask inputs of the key-outer pass)
+//                      attend-set (0 without the causal bit) and sequence position (the mask inputs of the key-outer pass)
 //   qh, doh [Hq][n_pad][D]  head-major copies of Q and dO (padding rows zero) for the
 //                      key-outer pass: there a tile is 64 consecutive rows of ONE head,
 //                      which in the token-major layout are Hq*D*2 bytes apart -- a
@@ -84,7 +84,7 @@ bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
                     pos = row_pos(blocks, block, row);
                     const uint64_t w = bits[pos];
                     ss = word_ss(w);
-                    ca = word_causal(w);
+                    ca = word_att(w);
                 }
                 info[0] = ss;
                 info[n_pad] = ca;
@@ -206,7 +206,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     // this lane's key; the role's resident operand (B operand, 8 head-dim values per step):
     // V role keeps K (for S = Q K^T), K role keeps V (for dP = dO V^T)
     const int64_t key = (int64_t)kt * kKvBN + kblk * 32 + li;
-    const uint32_t k_ss = word_ss(bits[key]);
+    const uint32_t k_ss = word_ss(bits[key]), k_mod = word_mod(bits[key]);
     bf16x8 res[NDS];
     {
         const ushort_t* src = k_role ? V : K;
@@ -349,7 +349,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             const u32x4 ps = *(lds_u4)(uintptr_t)(info_addr + (uint32_t)(imm + q4 * 32 + 8 * kKvBM));
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (!visible(ss[j], ca[j], (int64_t)ps[j], k_ss, key)) x[q4 * 4 + j] = -INFINITY;
+                if (!visible(ss[j], ca[j], (int64_t)ps[j], k_ss, k_mod, key)) x[q4 * 4 + j] = -INFINITY;
         }
     };
     // One unit: NS slots, each one MFMA, one fragment request and a share of the
@@ -637,7 +637,7 @@ template <int D, int NST>
 struct DqSmem {
     alignas(1024) unsigned char k[NST][kDqBN * D * 2];    // MODE 0: rows (S^T) and transpose (dQ^T)
     alignas(1024) unsigned char v[NST][kDqBN * D * 2];    // same layout: rows (dP^T)
-    uint32_t kss[kDqBN];
+    uint32_t kss[2][kDqBN];                               // sample/span field and modality of a PARTIAL tile's keys
 };
 
 template <int D, int HPW, int NST>
@@ -706,7 +706,7 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         q_pos = row_pos(blocks, block, row);
         const uint64_t w = bits[q_pos];
         q_ss = word_ss(w);
-        q_causal = word_causal(w);
+        q_causal = word_att(w);
         const int64_t off = (row * Hq + h) * (int64_t)D + hh * 8;
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds) {
@@ -822,7 +822,11 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             for (int j = 0; j + 1 < NST - 1; ++j) pend[j] = pend[j + 1];
             pend[NST - 2] = fresh;
             if (partial) {
-                if (tid < kDqBN) sm.kss[tid] = word_ss(bits[k0 + tid]);
+                if (tid < kDqBN) {
+                    const uint64_t wk = bits[k0 + tid];
+                    sm.kss[0][tid] = word_ss(wk);
+                    sm.kss[1][tid] = word_mod(wk);
+                }
                 __syncthreads();
             }
             constexpr int kHalf = 32 * RB;
@@ -844,10 +848,11 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
                     for (int q4 = 0; q4 < 4; ++q4) {
                         const u32x4 kw = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(kb * 128 + q4 * 32));
+                        const u32x4 km = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(4 * kDqBN + kb * 128 + q4 * 32));
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
-                            if (!visible(q_ss, q_causal, q_pos, kw[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
+                            if (!visible(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
                         }
                     }
                 }

@@ -25,18 +25,23 @@ constexpr int kSpanShift = 12;
 constexpr int kSampleShift = 28;
 constexpr int kCausalBit = 63;
 
-// Compact 33-bit view used by the kernels: low 16 bits span id, next 16 bits
-// sample id, plus the causal flag.  Equal `ss` words mean same sample AND
-// same span.
+// Compact views used by the kernels.  `ss`: low 16 bits span id, next 16 bits
+// sample id; equal `ss` words mean same sample AND same span.  Query side `att`:
+// the attend-set (bits 0-7 of the word) if the causal bit is set, else 0.  Key
+// side `mod`: the token's own modality (bits 8-11).
 __host__ __device__ inline uint32_t word_ss(uint64_t w) { return (uint32_t)(w >> kSpanShift); }
-__host__ __device__ inline uint32_t word_causal(uint64_t w) { return (uint32_t)(w >> kCausalBit); }
+__host__ __device__ inline uint32_t word_att(uint64_t w) {
+    return (w >> kCausalBit) ? (uint32_t)(w & 0xFFu) : 0u;
+}
+__host__ __device__ inline uint32_t word_mod(uint64_t w) { return (uint32_t)(w >> 8) & 0xFu; }
 
-// vis(q,k) = same_sample && ((causal(q) && k<=q) || (span(q)!=0 && span(q)==span(k)))
-__device__ __forceinline__ bool visible(uint32_t ss_q, uint32_t causal_q, int64_t q,
-                                        uint32_t ss_k, int64_t k) {
+// vis(q,k) = same_sample && ((causal(q) && k<=q && attend(q)[modality(k)]) ||
+//                            (span(q)!=0 && span(q)==span(k)))
+__device__ __forceinline__ bool visible(uint32_t ss_q, uint32_t att_q, int64_t q,
+                                        uint32_t ss_k, uint32_t mod_k, int64_t k) {
     bool same_sample = (ss_q >> 16) == (ss_k >> 16);
     bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_k;
-    return same_span || (same_sample && causal_q && k <= q);
+    return same_span || (same_sample && ((att_q >> mod_k) & 1u) && k <= q);
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

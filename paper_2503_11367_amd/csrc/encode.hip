@@ -33,6 +33,8 @@ encode_kernel(const DevSpan* __restrict__ spans, int32_t n_spans,
         w |= (uint64_t)(a + 1) << kSpanShift;
         w |= (uint64_t)(spans[a].modality & 0xF) << 8;
         if (spans[a].flags & MMATTN_SPAN_NONCAUSAL) causal = 0;
+        // attend-set: all modalities minus the span's deny mask (flags bits 8-15)
+        w &= ~(uint64_t)((spans[a].flags >> MMATTN_SPAN_DENY_SHIFT) & 0xFF);
     }
     bits[t] = w | (causal << kCausalBit);
 }

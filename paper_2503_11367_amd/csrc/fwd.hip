@@ -42,7 +42,7 @@ template <int D, int NST>
 struct FwdSmem {
     alignas(1024) unsigned char k[NST][kFwdBN * D * 2];   // rotated tiles, see SwzTile
     alignas(1024) unsigned char v[NST][kFwdBN * D * 2];
-    uint32_t kss[2][kFwdBN];                              // sample/span fields of a PARTIAL tile's keys, by tile parity
+    uint32_t kss[2][2][kFwdBN];                           // sample/span field and modality of a PARTIAL tile's keys, by tile parity
 };
 
 // HPW query heads per workgroup (4 wavefronts each), NST LDS stages.
@@ -103,13 +103,13 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     const int64_t row = (int64_t)qt * kFwdBM + w4 * 32 + li;
     const bool row_ok = row < n_loc;
     int64_t q_pos = 0;
-    uint32_t q_ss = 0, q_causal = 0;
+    uint32_t q_ss = 0, q_causal = 0;     // q_causal: the attend-set if the causal bit is set, else 0
     bf16x8 qf[NDS];
     if (row_ok) {
         q_pos = row_pos(blocks, block, row);
         const uint64_t w = bits[q_pos];
         q_ss = word_ss(w);
-        q_causal = word_causal(w);
+        q_causal = word_att(w);
         const ushort_t* qp = Q + (row * Hq + h) * (int64_t)D + hh * 8;
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds)
@@ -218,13 +218,21 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] *= scale_log2;
     };
+    // key words of rows 8*q4 + 4*hh + 0..3 (+32 per half tile), 16 bytes per read
+    const uint32_t kss_a = lds_addr_of(sm.kss) + hh * 16;
     auto mask_scores = [&](uint32_t entry, int parity, int kb, floatx16& s) __attribute__((always_inline)) {
         if (entry & kPartialFlag) {            // workgroup-uniform
             const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kl = kb * 32 + c_row(r, hh);
-                if (!visible(q_ss, q_causal, q_pos, sm.kss[parity][kl], k0 + kl)) s[r] = -INFINITY;
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const uint32_t a = kss_a + (uint32_t)(parity * (8 * kFwdBN) + kb * 128 + q4 * 32);
+                const u32x4 kw = *(lds_u4)(uintptr_t)a;
+                const u32x4 km = *(lds_u4)(uintptr_t)(a + 4 * kFwdBN);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
+                    if (!visible(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
+                }
             }
         }
     };
@@ -258,7 +266,11 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     auto stage_keys = [&](uint32_t entry, int parity) __attribute__((always_inline)) {
         if (entry & kPartialFlag) {            // workgroup-uniform
             const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
-            if (tid < kFwdBN) sm.kss[parity][tid] = word_ss(bits[k0 + tid]);
+            if (tid < kFwdBN) {
+                const uint64_t wk = bits[k0 + tid];
+                sm.kss[parity][0][tid] = word_ss(wk);
+                sm.kss[parity][1][tid] = word_mod(wk);
+            }
             __syncthreads();
         }
     };

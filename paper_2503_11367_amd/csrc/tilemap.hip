@@ -5,7 +5,7 @@
 //
 // Integer ALU work.  One wavefront per tile pair, four k-tiles per workgroup
 // sharing the q-tile's words in LDS.  When both the q-tile and the k-tile are
-// "uniform" (every token carries the same sample/span/causal fields -- the
+// "uniform" (every token carries the same sample/span/attend fields -- the
 // common case inside a text run or a modality span) the count has a closed
 // form in the tile coordinates; otherwise the wave evaluates the predicate for
 // every pair.  Both paths are exact.
@@ -32,7 +32,7 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
                 int32_t tq, int32_t tk, int32_t nk,
                 uint8_t* __restrict__ cls, uint32_t* __restrict__ cnt) {
     __shared__ uint32_t q_ss[kTmQChunk];
-    __shared__ uint32_t q_causal[kTmQChunk];
+    __shared__ uint32_t q_att[kTmQChunk];
     __shared__ int64_t q_pos[kTmQChunk];
     __shared__ int s_flags[4];      // [0] q uniform, [1] q positions contiguous
 
@@ -46,10 +46,11 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
     const int64_t k0 = j * tk;
 
     // key-side words of this wave's k-tile, tk/64 per lane, and their uniformity
-    uint32_t k_first = 0;
+    uint32_t k_first = 0, k_mod_first = 0;  // equal ss words imply equal modality (same span, or text)
     bool k_uniform = true;
     if (wave_active) {
         k_first = word_ss(bits[k0]);
+        k_mod_first = word_mod(bits[k0]);
         bool same = true;
         for (int64_t k = k0 + lane; k < k0 + tk; k += kWave) same &= word_ss(bits[k]) == k_first;
         k_uniform = __all(same);
@@ -64,21 +65,21 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
             uint64_t w = bits[p];
             q_pos[threadIdx.x] = p;
             q_ss[threadIdx.x] = word_ss(w);
-            q_causal[threadIdx.x] = word_causal(w);
+            q_att[threadIdx.x] = word_att(w);
         }
         __syncthreads();
         // chunk-level uniformity of the q side (fields equal, positions contiguous)
         bool ok = true;
         if ((int)threadIdx.x < n)
-            ok = q_ss[threadIdx.x] == q_ss[0] && q_causal[threadIdx.x] == q_causal[0] &&
+            ok = q_ss[threadIdx.x] == q_ss[0] && q_att[threadIdx.x] == q_att[0] &&
                  q_pos[threadIdx.x] == q_pos[0] + threadIdx.x;
         const bool q_uniform = __syncthreads_and(ok);
         if (!wave_active) continue;
 
         if (q_uniform && k_uniform) {
-            const uint32_t ss_q = q_ss[0], ca_q = q_causal[0];
+            const uint32_t ss_q = q_ss[0], at_q = q_att[0];
             const bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == k_first;
-            const bool back = (ss_q >> 16) == (k_first >> 16) && ca_q;
+            const bool back = (ss_q >> 16) == (k_first >> 16) && ((at_q >> k_mod_first) & 1u);
             if (same_span) {
                 total += (uint32_t)n * (uint32_t)tk;
             } else if (back) {
@@ -93,9 +94,10 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
         } else {
             uint32_t part = 0;
             for (int64_t k = k0 + lane; k < k0 + tk; k += kWave) {
-                const uint32_t ss_k = word_ss(bits[k]);
+                const uint64_t wk = bits[k];
+                const uint32_t ss_k = word_ss(wk), mod_k = word_mod(wk);
                 for (int r = 0; r < n; ++r)
-                    part += visible(q_ss[r], q_causal[r], q_pos[r], ss_k, k) ? 1u : 0u;
+                    part += visible(q_ss[r], q_att[r], q_pos[r], ss_k, mod_k, k) ? 1u : 0u;
             }
             total += wave_sum(part);
         }

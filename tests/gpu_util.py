@@ -14,7 +14,7 @@ def fields(lay):
 
 
 def gpu_bits(lay):
-    return mb.mask_encode(lay.spans, lay.sample_off, lay.S, device=DEV, flags=lay.noncausal)
+    return mb.mask_encode(lay.spans, lay.sample_off, lay.S, device=DEV, flags=lay.span_flags())
 
 
 def oracle_bits(lay):

@@ -35,15 +35,24 @@ def run_case(lay, blocks, block, Hq, Hkv, D, seed):
     o, lse, dq, dk, dv = gpu_fwd_bwd(lay, blocks, block, t)
     rows = oa.rows_of_blocks(blocks, block)
     Q, K, V, dO = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"]), f64(t["do_bits"])
-    dq_ref, dk_ref, dv_ref = oa.backward(Q, K, V, dO, rows, f[0], f[1], f[2])
+    dq_ref, dk_ref, dv_ref = oa.backward(Q, K, V, dO, rows, f[0], f[1], f[2], modality=f[3], attend=f[4])
     for name, got, ref in (("dq", dq, dq_ref), ("dk", dk, dk_ref), ("dv", dv, dv_ref)):
         g = bf16_to_f64(got)
         assert np.isfinite(g).all(), name
         assert rel_l2(g, ref) < TOL, (name, rel_l2(g, ref))
     # keys that no row of the share sees get exactly zero
     from oracle import mask as om
-    seen = om.visible(rows, np.arange(lay.S), f[0], f[1], f[2]).any(axis=0)
+    seen = om.visible(rows, np.arange(lay.S), f[0], f[1], f[2], f[3], f[4]).any(axis=0)
     assert (bf16_to_f64(dk)[~seen] == 0).all() and (bf16_to_f64(dv)[~seen] == 0).all()
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_attend_sets(seed):
+    lay = wl.layout_random(70 + seed, S=1024, n_samples=1 + seed % 2, max_spans=6, noncausal_prob=0.2,
+                           deny_prob=0.8)
+    assert any(lay.deny)
+    blocks = list(range(lay.S // 64)) if seed != 1 else list(range(1, lay.S // 64, 2))
+    run_case(lay, blocks, 64, Hq=2 + 2 * (seed % 2), Hkv=2, D=[128, 64, 128][seed], seed=60 + seed)
 
 
 def test_tiny_every_rank_share():

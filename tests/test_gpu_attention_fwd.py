@@ -42,7 +42,7 @@ def run_case(lay, blocks, block, Hq, Hkv, D, seed, heads=None, rows_sample=None)
     lse_ref = np.zeros_like(lse_gpu)
     for j, h in enumerate(hs):
         g = h // rep
-        oo, ll = oa.forward(Q[sel][:, h:h + 1], K[:, g:g + 1], V[:, g:g + 1], rows[sel], f[0], f[1], f[2])
+        oo, ll = oa.forward(Q[sel][:, h:h + 1], K[:, g:g + 1], V[:, g:g + 1], rows[sel], f[0], f[1], f[2], modality=f[3], attend=f[4])
         o_ref[:, j] = oo[:, 0]
         lse_ref[j] = ll[0]
     assert np.isfinite(o_gpu).all()
@@ -83,6 +83,16 @@ def test_few_work_items_split_into_list_slices():
     run_case(lay, [31, 2, 17], 128, Hq=2, Hkv=2, D=64, seed=52)
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_attend_sets(seed):
+    """Spans that do not attend some modalities (section 4.2's attend-set): the
+    backward-looking term is gated by attend(q)[modality(k)]."""
+    lay = wl.layout_random(70 + seed, S=1024, n_samples=1 + seed % 2, max_spans=6, noncausal_prob=0.2,
+                           deny_prob=0.8)
+    assert any(lay.deny)
+    run_case(lay, list(range(lay.S // 64)), 64, Hq=2 + 2 * (seed % 2), Hkv=2, D=[128, 64, 128][seed], seed=60 + seed)
+
+
 def test_unsorted_block_list_and_mha():
     lay = wl.layout_random(77, S=512, n_samples=2)
     run_case(lay, [5, 0, 3], 64, Hq=2, Hkv=2, D=128, seed=31)
@@ -92,6 +102,9 @@ def test_all_text_all_span_packed():
     run_case(wl.Layout(512, [], [0, 512]), list(range(4)), 128, 2, 1, 128, seed=41)
     run_case(wl.Layout(512, [(0, 512, 1)], [0, 512]), list(range(4)), 128, 2, 1, 128, seed=42)
     run_case(wl.Layout(768, [(300, 100, 2)], [0, 200, 768]), list(range(6)), 128, 2, 2, 64, seed=43)
+    # "prepended" family: modality tokens first, then text; audio does not attend image
+    run_case(wl.Layout(1024, [(0, 300, wl.IMAGE), (300, 150, wl.AUDIO)], [0, 1024], deny=[0, 1 << wl.IMAGE]),
+             list(range(8)), 128, 4, 2, 128, seed=44)
 
 
 def test_zero_q_reads_back_the_mask():
@@ -144,14 +157,14 @@ def test_workload2_full_sequence():
     torch.cuda.synchronize()
     Q, K, V = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"])
     rows = np.arange(w.layout.S)
-    o_ref, lse_ref = oa.forward(Q[:, 12:16], K[:, 3:4], V[:, 3:4], rows, f[0], f[1], f[2])
+    o_ref, lse_ref = oa.forward(Q[:, 12:16], K[:, 3:4], V[:, 3:4], rows, f[0], f[1], f[2], modality=f[3], attend=f[4])
     og = bf16_to_f64(o)
     assert max_abs(og[:, 12:16], o_ref) < TOL_MAX and rel_l2(og[:, 12:16], o_ref) < TOL_L2
     assert max_abs(lse.cpu().numpy()[12:16].astype(np.float64), lse_ref) < TOL_LSE
     sel = np.sort(np.random.default_rng(0).choice(w.layout.S, size=96, replace=False))
     for h in range(1, w.Hq, 4):
         g = h // 4
-        o_s, _ = oa.forward(Q[sel][:, h:h + 1], K[:, g:g + 1], V[:, g:g + 1], sel, f[0], f[1], f[2])
+        o_s, _ = oa.forward(Q[sel][:, h:h + 1], K[:, g:g + 1], V[:, g:g + 1], sel, f[0], f[1], f[2], modality=f[3], attend=f[4])
         assert max_abs(og[sel][:, h:h + 1], o_s) < TOL_MAX
 
 

@@ -22,6 +22,18 @@ def layouts_small():
     return out
 
 
+def layouts_attend():
+    """Layouts whose spans deny some modalities (attend-set generalisation)."""
+    out = [wl.Layout(9 * 64, [(128, 128, wl.AUDIO), (320, 192, wl.IMAGE)], [0, 576], deny=[0, 1 << wl.AUDIO])]
+    # "prepended" family (App. C): all modality tokens first, then the text; the audio
+    # encoder's tokens do not attend the image tokens before them
+    out.append(wl.Layout(1024, [(0, 300, wl.IMAGE), (300, 150, wl.AUDIO)], [0, 1024], deny=[0, 1 << wl.IMAGE]))
+    for seed in range(1, 5):
+        out.append(wl.layout_random(60 + seed, S=1024, n_samples=1 + seed % 3, max_spans=6,
+                                    noncausal_prob=0.2, deny_prob=0.7))
+    return out
+
+
 @pytest.mark.parametrize("idx", range(10))
 def test_encode_small(idx):
     lay = layouts_small()[idx]
@@ -38,7 +50,7 @@ def check_tile_map(lay, tq, tk, use_c):
     f = fields(lay)
     bits = torch.from_numpy(oracle_bits(lay).view(np.int64)).to(DEV)      # oracle-encoded input
     cls, cnt, rp = mb.tile_map(bits, tq, tk)
-    ref = (ot.tile_map_c if use_c else ot.tile_map)(f[0], f[1], f[2], tq, tk)
+    ref = (ot.tile_map_c if use_c else ot.tile_map)(f[0], f[1], f[2], tq, tk, f[3], f[4])
     assert np.array_equal(cls.cpu().numpy(), ref[0])
     assert np.array_equal(cnt.cpu().numpy().view(np.uint32), ref[1])
     assert np.array_equal(rp.cpu().numpy().view(np.uint64), ref[2])
@@ -51,6 +63,16 @@ def test_tile_map_small(idx, tile):
     if lay.S % tile[0] or lay.S % tile[1]:
         pytest.skip("tile does not divide S")
     check_tile_map(lay, tile[0], tile[1], use_c=False)
+
+
+@pytest.mark.parametrize("idx", range(6))
+def test_encode_and_tile_map_with_attend_sets(idx):
+    lay = layouts_attend()[idx]
+    assert any(lay.deny)
+    assert np.array_equal(to_np_u64(gpu_bits(lay)), oracle_bits(lay))
+    for tile in ((64, 64), (128, 64), (64, 128)):
+        if lay.S % tile[0] == 0 and lay.S % tile[1] == 0:
+            check_tile_map(lay, tile[0], tile[1], use_c=False)
 
 
 @pytest.mark.parametrize("c", [1, 2, 3, 4, 5])
