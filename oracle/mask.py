@@ -22,6 +22,12 @@ those bits and the backward-looking term becomes
 Tokens of the own span stay visible (same-span term).  With no deny masks
 every attend-set is all ones and the predicate is the one above.
 
+A span may also be marked `nobidir`: its tokens carry the modality and the
+attend-set but span id 0, so only the backward-looking term applies to them.
+This expresses the "shared question" pattern of the paper's comparison with
+DCP (section 5.5 and its appendix): answers are nobidir spans of distinct modalities that attend
+the text modality (the question) and their own.
+
 Word layout (LSB first, section 4.2: low bits = LLM and modality encoders,
 bit 63 = causal bit):
   bits 0-7   attend-set, bit m set = may attend modality m   (all set here)
@@ -36,7 +42,10 @@ everything = all ones, packed = block diagonal, the section-4.2 worked example
 (encoder tokens without the causal bit see only their own encoder's tokens;
 text tokens see every earlier token), encode/decode round trip; for the
 attend-set generalisation a mask written out by hand and the pair count
-(P1 count minus the denied backward pairs, counted by a separate loop).
+(P1 count minus the denied backward pairs, counted by a separate loop); for
+nobidir spans a shared-question mask written out by hand and its closed-form
+pair count; tests/test_oracle_attention.py checks that every answer's rows
+equal plain causal attention over [question, that answer].
 """
 import numpy as np
 
@@ -44,7 +53,7 @@ ATTEND_ALL = 0xFF
 CAUSAL_BIT = 63
 
 
-def token_fields(S, spans, sample_off, noncausal=None, deny=None):
+def token_fields(S, spans, sample_off, noncausal=None, deny=None, nobidir=None):
     """Expand a layout into per-token arrays (sample, span, causal, modality,
     attend).
 
@@ -53,6 +62,8 @@ def token_fields(S, spans, sample_off, noncausal=None, deny=None):
     noncausal: optional per-span flag; 1 clears the causal bit of that span.
     deny: optional per-span 8-bit mask of modalities the span's tokens do not
           attend (cleared from their attend-set).
+    nobidir: optional per-span flag; 1 leaves the span id of its tokens at 0
+          (no bidirectional term; modality and attend-set still apply).
     """
     sample = np.zeros(S, dtype=np.int64)
     span = np.zeros(S, dtype=np.int64)
@@ -62,7 +73,8 @@ def token_fields(S, spans, sample_off, noncausal=None, deny=None):
     for i in range(len(sample_off) - 1):
         sample[sample_off[i]:sample_off[i + 1]] = i
     for j, (start, n, mod) in enumerate(spans):
-        span[start:start + n] = j + 1
+        if nobidir is None or not nobidir[j]:
+            span[start:start + n] = j + 1
         modality[start:start + n] = mod
         if noncausal is not None and noncausal[j]:
             causal[start:start + n] = 0

@@ -29,16 +29,21 @@ class Layout:
     sample_off: List[int]                      # n_samples+1 offsets, [0]=0, [-1]=S
     noncausal: List[int] = field(default_factory=list)   # per-span flag (0 = causal bit set)
     deny: List[int] = field(default_factory=list)        # per-span mask of modalities NOT attended
+    nobidir: List[int] = field(default_factory=list)     # per-span flag (1 = no bidirectional term)
 
     def __post_init__(self):
         if not self.noncausal:
             self.noncausal = [0] * len(self.spans)
         if not self.deny:
             self.deny = [0] * len(self.spans)
+        if not self.nobidir:
+            self.nobidir = [0] * len(self.spans)
 
     def span_flags(self) -> List[int]:
-        """Per-span flag words of the C ABI: bit 0 non-causal, bits 8-15 deny mask."""
-        return [int(n) | (int(d) << 8) for n, d in zip(self.noncausal, self.deny)]
+        """Per-span flag words of the C ABI: bit 0 non-causal, bit 1 no
+        bidirectional term, bits 8-15 deny mask."""
+        return [int(n) | (int(u) << 1) | (int(d) << 8)
+                for n, u, d in zip(self.noncausal, self.nobidir, self.deny)]
 
 
 @dataclass
@@ -186,6 +191,29 @@ def layout_random(seed: int, S: int, n_samples: int = 1, max_spans: int = 4,
         else:
             dn += [0 for _ in sp]
     return Layout(S, spans, offs, nc, dn)
+
+
+def layout_shared_question(n_question: int, answer_lens: List[int], n_tail: int = 0) -> Layout:
+    """One question followed by up to seven answers and optional trailing text
+    (the "shared question" pattern of the paper's comparison with DCP): answer
+    a is a span of modality a without the bidirectional term whose tokens
+    attend the text modality and their own, i.e. the question and the earlier
+    tokens of the same answer, never another answer."""
+    assert 1 <= len(answer_lens) <= 7
+    spans, deny, pos = [], [], n_question
+    for a, n in enumerate(answer_lens, start=1):
+        spans.append((pos, n, a))
+        deny.append(0xFE & ~(1 << a))
+        pos += n
+    S = pos + n_tail
+    return Layout(S, spans, [0, S], deny=deny, nobidir=[1] * len(spans))
+
+
+def layout_block_causal(S: int, block: int) -> Layout:
+    """Causal blockwise pattern read from its name: bidirectional inside each
+    block of `block` tokens, causal across blocks (every block is a span)."""
+    spans = [(a, min(block, S - a), IMAGE) for a in range(0, S, block)]
+    return Layout(S, spans, [0, S])
 
 
 def workload(c: int) -> Workload:

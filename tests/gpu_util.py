@@ -10,7 +10,7 @@ DEV = "cuda"
 
 
 def fields(lay):
-    return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny)
+    return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny, lay.nobidir)
 
 
 def gpu_bits(lay):

@@ -10,7 +10,7 @@ from paper_2503_11367_amd import workloads as wl
 
 def setup(lay, Hq, Hkv, D, seed, rows=None):
     rng = np.random.default_rng(seed)
-    f = om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny)
+    f = om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny, lay.nobidir)
     rows = np.arange(lay.S) if rows is None else rows
     Q = rng.standard_normal((len(rows), Hq, D))
     K = rng.standard_normal((lay.S, Hkv, D))
@@ -35,6 +35,21 @@ def test_all_text_equals_causal_sdpa():
     f, rows, Q, K, V, _ = setup(lay, 4, 2, 16, 0)
     O, _ = oa.forward(Q, K, V, rows, f[0], f[1], f[2], chunk=40)
     assert np.allclose(O, sdpa(Q, K, V, True), atol=1e-12)
+
+
+def test_shared_question_equals_causal_sdpa_per_answer():
+    """Rows of answer a (and of the question) equal plain causal attention over
+    the concatenation [question, answer a]."""
+    nq, answers = 11, [7, 13, 5]
+    lay = wl.layout_shared_question(nq, answers)
+    f, rows, Q, K, V, _ = setup(lay, 4, 2, 16, 3)
+    O, _ = oa.forward(Q, K, V, rows, f[0], f[1], f[2], modality=f[3], attend=f[4], chunk=16)
+    pos = nq
+    for n in answers:
+        sel = np.r_[0:nq, pos:pos + n]
+        ref = sdpa(Q[sel], K[sel], V[sel], True)
+        assert np.allclose(O[sel], ref, atol=1e-12)
+        pos += n
 
 
 def test_single_span_equals_full_sdpa():

@@ -10,13 +10,13 @@ from paper_2503_11367_amd import workloads as wl
 
 
 def fields(lay):
-    return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny)
+    return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny, lay.nobidir)
 
 
 def dense(lay):
     sample, span, causal, modality, attend = fields(lay)
     idx = np.arange(lay.S)
-    if any(lay.deny):
+    if any(lay.deny) or any(lay.nobidir):
         return om.visible(idx, idx, sample, span, causal, modality, attend)
     return om.visible(idx, idx, sample, span, causal)
 
@@ -107,6 +107,41 @@ def test_denying_own_modality_keeps_the_span_itself():
     lay = wl.Layout(8, [(1, 2, wl.IMAGE), (4, 3, wl.IMAGE)], [0, 8], deny=[0, 1 << wl.IMAGE])
     v = dense(lay)
     assert v[5].tolist() == [True, False, False, True, True, True, True, False]
+
+
+def test_shared_question_rows_by_hand():
+    """question[0:2], answers [2:4] and [4:7], trailing text [7:8]: an answer sees
+    the question and its own earlier tokens, never the other answer; the
+    trailing text sees everything before it."""
+    lay = wl.layout_shared_question(2, [2, 3], n_tail=1)
+    expect = np.array([
+        [1, 0, 0, 0, 0, 0, 0, 0],
+        [1, 1, 0, 0, 0, 0, 0, 0],
+        [1, 1, 1, 0, 0, 0, 0, 0],
+        [1, 1, 1, 1, 0, 0, 0, 0],
+        [1, 1, 0, 0, 1, 0, 0, 0],
+        [1, 1, 0, 0, 1, 1, 0, 0],
+        [1, 1, 0, 0, 1, 1, 1, 0],
+        [1, 1, 1, 1, 1, 1, 1, 1]], dtype=bool)
+    assert np.array_equal(dense(lay), expect)
+    sample, span, causal, modality, attend = fields(lay)
+    assert not span.any() and modality.tolist() == [0, 0, 1, 1, 2, 2, 2, 0]
+    assert attend[2] == 0b00000011 and attend[4] == 0b00000101 and attend[7] == 0xFF
+
+
+@pytest.mark.parametrize("nq,answers", [(5, [3]), (17, [9, 1, 30]), (64, [40] * 7)])
+def test_shared_question_pair_count(nq, answers):
+    """pairs = nq(nq+1)/2 + sum over answers of n*nq + n(n+1)/2."""
+    lay = wl.layout_shared_question(nq, answers)
+    want = nq * (nq + 1) // 2 + sum(n * nq + n * (n + 1) // 2 for n in answers)
+    assert int(dense(lay).sum()) == want
+
+
+def test_block_causal_is_block_lower_triangle():
+    lay = wl.layout_block_causal(40, 16)        # ragged last block of 8
+    v = dense(lay)
+    blk = np.arange(40) // 16
+    assert np.array_equal(v, blk[:, None] >= blk[None, :])
 
 
 @pytest.mark.parametrize("seed", range(6))
