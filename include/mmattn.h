@@ -77,9 +77,15 @@ enum { MMATTN_TILE_EMPTY = 0, MMATTN_TILE_FULL = 1, MMATTN_TILE_PARTIAL = 2 };
  * the span's tokens: they then see only their own span (section 4.2's
  * encoder tokens "without the causal bit").  flags bits 8-15: mask of
  * modalities (bit m = modality m, m in 0..7) that the span's tokens do not
- * attend among the earlier tokens; their own span stays visible. */
+ * attend among the earlier tokens; their own span stays visible.  flags bit 1
+ * (MMATTN_SPAN_NOBIDIR): the span's tokens keep span id 0, so they see only
+ * earlier tokens of the modalities they attend (an answer of section 5.5's
+ * shared-question pattern: attends text and its own modality); such a span
+ * must keep the causal bit and must attend its own modality, so that every
+ * token sees at least itself (else MMATTN_ERR_LAYOUT). */
 typedef struct { int64_t start, len; int32_t modality, flags; } mmattn_span;
 #define MMATTN_SPAN_NONCAUSAL 1
+#define MMATTN_SPAN_NOBIDIR   2
 #define MMATTN_SPAN_DENY_SHIFT 8   /* flags bits 8-15: modalities the span's tokens do NOT attend */
 #define MMATTN_MAX_SPANS   65535
 #define MMATTN_MAX_SAMPLES 65535

@@ -22,6 +22,7 @@ ERR_NAMES = {0: "OK", -1: "ERR_NULL", -2: "ERR_SHAPE", -3: "ERR_UNSUPPORTED",
 OP_ENCODE, OP_TILE_MAP, OP_BALANCE, OP_FWD, OP_BWD = range(5)
 TILE_EMPTY, TILE_FULL, TILE_PARTIAL = 0, 1, 2
 SPAN_NONCAUSAL = 1
+SPAN_NOBIDIR = 2
 BF16 = 0
 
 

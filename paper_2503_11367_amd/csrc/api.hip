@@ -82,7 +82,14 @@ int mmattn_mask_encode(const mmattn_span* spans, int32_t n_spans, const int64_t*
         const mmattn_span& sp = spans[j];
         if (sp.len <= 0 || sp.start < prev_end || sp.start + sp.len > S) return MMATTN_ERR_LAYOUT;
         if (sp.modality < 1 || sp.modality > 7) return MMATTN_ERR_LAYOUT;     // one attend bit each
-        if (sp.flags & ~(MMATTN_SPAN_NONCAUSAL | (0xFF << MMATTN_SPAN_DENY_SHIFT))) return MMATTN_ERR_LAYOUT;
+        if (sp.flags & ~(MMATTN_SPAN_NONCAUSAL | MMATTN_SPAN_NOBIDIR | (0xFF << MMATTN_SPAN_DENY_SHIFT)))
+            return MMATTN_ERR_LAYOUT;
+        // without the bidirectional term a token sees itself only through the
+        // backward-looking term: causal bit set and own modality attended
+        if ((sp.flags & MMATTN_SPAN_NOBIDIR) &&
+            ((sp.flags & MMATTN_SPAN_NONCAUSAL) ||
+             ((sp.flags >> MMATTN_SPAN_DENY_SHIFT) >> sp.modality & 1)))
+            return MMATTN_ERR_LAYOUT;
         while (sample_off[smp + 1] <= sp.start) ++smp;
         if (sp.start + sp.len > sample_off[smp + 1]) return MMATTN_ERR_LAYOUT;   // crosses samples
         prev_end = sp.start + sp.len;

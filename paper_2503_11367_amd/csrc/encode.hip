@@ -30,7 +30,7 @@ encode_kernel(const DevSpan* __restrict__ spans, int32_t n_spans,
         if (spans[mid].start <= t) a = mid; else b = mid;
     }
     if (a >= 0 && t < spans[a].start + spans[a].len) {
-        w |= (uint64_t)(a + 1) << kSpanShift;
+        if (!(spans[a].flags & MMATTN_SPAN_NOBIDIR)) w |= (uint64_t)(a + 1) << kSpanShift;
         w |= (uint64_t)(spans[a].modality & 0xF) << 8;
         if (spans[a].flags & MMATTN_SPAN_NONCAUSAL) causal = 0;
         // attend-set: all modalities minus the span's deny mask (flags bits 8-15)

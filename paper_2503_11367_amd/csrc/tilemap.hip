@@ -5,7 +5,7 @@
 //
 // Integer ALU work.  One wavefront per tile pair, four k-tiles per workgroup
 // sharing the q-tile's words in LDS.  When both the q-tile and the k-tile are
-// "uniform" (every token carries the same sample/span/attend fields -- the
+// "uniform" (every token carries the same sample/span/modality/attend fields -- the
 // common case inside a text run or a modality span) the count has a closed
 // form in the tile coordinates; otherwise the wave evaluates the predicate for
 // every pair.  Both paths are exact.
@@ -46,13 +46,16 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
     const int64_t k0 = j * tk;
 
     // key-side words of this wave's k-tile, tk/64 per lane, and their uniformity
-    uint32_t k_first = 0, k_mod_first = 0;  // equal ss words imply equal modality (same span, or text)
+    uint32_t k_first = 0, k_mod_first = 0;
     bool k_uniform = true;
     if (wave_active) {
         k_first = word_ss(bits[k0]);
         k_mod_first = word_mod(bits[k0]);
         bool same = true;
-        for (int64_t k = k0 + lane; k < k0 + tk; k += kWave) same &= word_ss(bits[k]) == k_first;
+        for (int64_t k = k0 + lane; k < k0 + tk; k += kWave) {
+            const uint64_t w = bits[k];
+            same &= word_ss(w) == k_first && word_mod(w) == k_mod_first;
+        }
         k_uniform = __all(same);
     }
 

@@ -52,6 +52,10 @@ def test_encode_validation():
     assert encode_rc([(60, 8, 1, 0)], [0, 64], 64) == -5                    # past the end
     assert encode_rc([(28, 8, 1, 0)], [0, 32, 64], 64) == -5                # crosses samples
     assert encode_rc([(8, 8, 0, 0)], [0, 64], 64) == -5                     # modality 0 is text
+    assert encode_rc([(8, 8, 8, 0)], [0, 64], 64) == -5                     # one attend bit per modality
+    assert encode_rc([(8, 8, 1, 4)], [0, 64], 64) == -5                     # unknown flag bit
+    assert encode_rc([(8, 8, 1, 2 | 1)], [0, 64], 64) == -5                 # no bidirectional term, no causal bit
+    assert encode_rc([(8, 8, 1, 2 | (2 << 8))], [0, 64], 64) == -5          # ... or own modality denied
     assert encode_rc([(8, 8, 1, 0)], [0, 64], 64, ws=0) == -4
     assert encode_rc([(8, 8, 1, 0)], [0, 64], 64, ws_bytes=8) == -4
     assert encode_rc([(8, 8, 1, 0)], [0, 64], 64, ws=FAKE + 8) == -4        # misaligned

@@ -52,6 +52,16 @@ def run_case(lay, blocks, block, Hq, Hkv, D, seed, heads=None, rows_sample=None)
     return o, lse, t
 
 
+def test_shared_question_and_block_causal():
+    """Two patterns named in section 5.5: answers that see the question and
+    themselves only (spans without the bidirectional term), and blocks that are
+    bidirectional inside and causal across (block length not a tile multiple)."""
+    run_case(wl.layout_shared_question(200, [130, 64, 257, 100], n_tail=145), list(range(7)), 128,
+             Hq=4, Hkv=2, D=128, seed=81)
+    run_case(wl.layout_shared_question(64, [128] * 7, n_tail=64), [7, 2, 12, 5], 64, Hq=2, Hkv=1, D=64, seed=82)
+    run_case(wl.layout_block_causal(1024, 96), list(range(8)), 128, Hq=2, Hkv=2, D=128, seed=83)
+
+
 def test_tiny_every_rank_share():
     w = wl.workload(1)
     f = fields(w.layout)

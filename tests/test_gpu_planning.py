@@ -28,6 +28,9 @@ def layouts_attend():
     # "prepended" family (App. C): all modality tokens first, then the text; the audio
     # encoder's tokens do not attend the image tokens before them
     out.append(wl.Layout(1024, [(0, 300, wl.IMAGE), (300, 150, wl.AUDIO)], [0, 1024], deny=[0, 1 << wl.IMAGE]))
+    # shared question (section 5.5): answers attend the question and themselves only
+    out.append(wl.layout_shared_question(200, [130, 64, 257, 100], n_tail=145))
+    out.append(wl.layout_shared_question(64, [128] * 7, n_tail=64))
     for seed in range(1, 5):
         out.append(wl.layout_random(60 + seed, S=1024, n_samples=1 + seed % 3, max_spans=6,
                                     noncausal_prob=0.2, deny_prob=0.7))
@@ -65,7 +68,7 @@ def test_tile_map_small(idx, tile):
     check_tile_map(lay, tile[0], tile[1], use_c=False)
 
 
-@pytest.mark.parametrize("idx", range(6))
+@pytest.mark.parametrize("idx", range(8))
 def test_encode_and_tile_map_with_attend_sets(idx):
     lay = layouts_attend()[idx]
     assert any(lay.deny)
@@ -73,6 +76,12 @@ def test_encode_and_tile_map_with_attend_sets(idx):
     for tile in ((64, 64), (128, 64), (64, 128)):
         if lay.S % tile[0] == 0 and lay.S % tile[1] == 0:
             check_tile_map(lay, tile[0], tile[1], use_c=False)
+
+
+def test_tile_map_block_causal():
+    for blk in (96, 128, 50):
+        lay = wl.layout_block_causal(1024 if blk != 50 else 1000 + 24, blk)
+        check_tile_map(lay, 128, 64, use_c=False)
 
 
 @pytest.mark.parametrize("c", [1, 2, 3, 4, 5])
