@@ -67,7 +67,7 @@ typedef enum { MMATTN_BF16 = 0 } mmattn_dtype;
 
 typedef enum {
     MMATTN_OP_ENCODE = 0, MMATTN_OP_TILE_MAP = 1, MMATTN_OP_BALANCE = 2,
-    MMATTN_OP_FWD = 3, MMATTN_OP_BWD = 4
+    MMATTN_OP_FWD = 3, MMATTN_OP_BWD = 4, MMATTN_OP_FWD_HEADS = 5
 } mmattn_op;
 
 enum { MMATTN_TILE_EMPTY = 0, MMATTN_TILE_FULL = 1, MMATTN_TILE_PARTIAL = 2 };
@@ -147,11 +147,34 @@ int mmattn_balance(const uint64_t* d_W, int32_t nB, int32_t P,
  *                          key gets O = 0 and LSE = -inf
  *   scale                  softmax scale (1/sqrt(D) usually), > 0
  * Requires S % 128 == 0, block % 16 == 0, S % block == 0, D in {64,128},
- * 16-byte aligned tensors. */
+ * 16-byte aligned tensors.  n_blocks may be 0 (Alg. 1 leaves a rank empty when
+ * there are more ranks than blocks): nothing is read or written, and q_loc,
+ * blocks, o_loc, lse may be null. */
 int mmattn_fwd(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
                const int32_t* blocks, int32_t n_blocks, int32_t block,
                int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,
                void* o_loc, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/* Section 4.3 (keys and values are gathered head by head and the attention of
+ * the heads already gathered overlaps the transfers of the next ones):
+ * mmattn_fwd restricted to the KV heads [kv_head_begin, kv_head_begin +
+ * kv_head_count) and their Hq/Hkv query heads each.  Tensors and layouts are
+ * those of mmattn_fwd (full Hq / Hkv strides); only the window's heads of k, v
+ * are read and only the window's heads of o_loc, lse are written, so the
+ * caller may still be filling the other heads of k, v on another stream.
+ *   plan_ready  0: build the share's tile plan in `ws` first (as mmattn_fwd
+ *               does); nonzero: reuse the plan left in `ws` by an earlier call
+ *               of this function with the same bits, blocks, block, S, Hq,
+ *               Hkv, D that has completed or precedes this call on `stream`
+ *   ws          mmattn_workspace_size(MMATTN_OP_FWD_HEADS, ...) bytes, valid
+ *               for every window
+ * Calls sharing one `ws` must be ordered (one stream, or events).
+ * MMATTN_ERR_SHAPE for a window outside [0, Hkv). */
+int mmattn_fwd_heads(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
+                     const int32_t* blocks, int32_t n_blocks, int32_t block,
+                     int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,
+                     int32_t kv_head_begin, int32_t kv_head_count, int32_t plan_ready,
+                     void* o_loc, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /* Backward of mmattn_fwd for the same rank share.
  *   o_loc, lse   what mmattn_fwd wrote;  do_loc upstream gradient
@@ -162,7 +185,9 @@ int mmattn_fwd(const void* q_loc, const void* k, const void* v, const uint64_t* 
  * With P = exp(S - LSE), Delta = rowsum(dO o O), dS = P o (dP - Delta):
  * dV = P^T dO, dK = scale dS^T Q, dQ = scale dS K.  When there are few key
  * tiles the query heads of a KV head are summed in two stages (fp32 partials
- * in `ws`, fixed order).  Same shape requirements as mmattn_fwd. */
+ * in `ws`, fixed order).  Same shape requirements as mmattn_fwd.  With
+ * n_blocks == 0 dk and dv are overwritten with zeros and the per-row
+ * arguments may be null. */
 int mmattn_bwd(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
                const int32_t* blocks, int32_t n_blocks, int32_t block,
                int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,

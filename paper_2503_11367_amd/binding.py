@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("MMATTN_LIB", os.path.join(_HERE, "libmmattn.so"))
 OK = 0
 ERR_NAMES = {0: "OK", -1: "ERR_NULL", -2: "ERR_SHAPE", -3: "ERR_UNSUPPORTED",
              -4: "ERR_WORKSPACE", -5: "ERR_LAYOUT", -6: "ERR_HIP"}
-OP_ENCODE, OP_TILE_MAP, OP_BALANCE, OP_FWD, OP_BWD = range(5)
+OP_ENCODE, OP_TILE_MAP, OP_BALANCE, OP_FWD, OP_BWD, OP_FWD_HEADS = range(6)
 TILE_EMPTY, TILE_FULL, TILE_PARTIAL = 0, 1, 2
 SPAN_NONCAUSAL = 1
 SPAN_NOBIDIR = 2
@@ -62,6 +62,9 @@ def lib() -> ctypes.CDLL:
         L.mmattn_fwd.restype = ctypes.c_int
         L.mmattn_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
                                  ctypes.c_int, _vp, _vp, _vp, _sz, _vp]
+        L.mmattn_fwd_heads.restype = ctypes.c_int
+        L.mmattn_fwd_heads.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
+                                       ctypes.c_int, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]
         L.mmattn_bwd.restype = ctypes.c_int
         L.mmattn_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
                                  ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -175,6 +178,22 @@ def fwd(q_loc: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bits: torch.Tenso
                           S, Hq, Hkv, D, scale, BF16, _ptr(o), _ptr(lse), _ptr(ws), ws.numel(),
                           _stream(stream))
     _check("mmattn_fwd", rc)
+    return o, lse
+
+
+def fwd_heads(q_loc, k, v, bits, blocks, block: int, kv_head_begin: int, kv_head_count: int,
+              plan_ready: bool, out, ws: torch.Tensor, scale: Optional[float] = None, stream=None):
+    """mmattn_fwd_heads: the forward for a window of KV heads, written into the
+    window's heads of out = (o_loc, lse); ws from workspace_size(OP_FWD_HEADS, ...)."""
+    n_loc, Hq, D = q_loc.shape
+    S, Hkv, _ = k.shape
+    scale = float(D) ** -0.5 if scale is None else float(scale)
+    o, lse = out
+    rc = lib().mmattn_fwd_heads(_ptr(q_loc), _ptr(k), _ptr(v), _ptr(bits), _ptr(blocks), blocks.numel(),
+                                block, S, Hq, Hkv, D, scale, BF16, kv_head_begin, kv_head_count,
+                                int(bool(plan_ready)), _ptr(o), _ptr(lse), _ptr(ws), ws.numel(),
+                                _stream(stream))
+    _check("mmattn_fwd_heads", rc)
     return o, lse
 
 

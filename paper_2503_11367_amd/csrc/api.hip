@@ -11,9 +11,9 @@ bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 int check_attn(const void* q, const void* k, const void* v, const uint64_t* bits,
                const int32_t* blocks, int32_t n_blocks, int32_t block, int64_t S, int32_t Hq,
                int32_t Hkv, int32_t D, float scale, int dtype) {
-    if (!q || !k || !v || !bits || !blocks) return MMATTN_ERR_NULL;
+    if (!k || !v || !bits || (n_blocks > 0 && (!q || !blocks))) return MMATTN_ERR_NULL;
     if (dtype != MMATTN_BF16) return MMATTN_ERR_UNSUPPORTED;
-    if (S <= 0 || n_blocks <= 0 || block <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0)
+    if (S <= 0 || n_blocks < 0 || block <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0)
         return MMATTN_ERR_SHAPE;
     if (Hq % Hkv != 0 || S % block != 0 || (int64_t)n_blocks > S / block) return MMATTN_ERR_SHAPE;
     if (!(scale > 0.0f)) return MMATTN_ERR_SHAPE;
@@ -59,6 +59,10 @@ size_t mmattn_workspace_size(int op, int64_t S, int32_t n_blocks, int32_t block,
         case MMATTN_OP_FWD:
             if (Hq <= 0 || Hkv <= 0 || D <= 0 || block <= 0 || n_blocks <= 0) return 0;
             return fwd_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D);
+        case MMATTN_OP_FWD_HEADS:
+            if (Hq <= 0 || Hkv <= 0 || D <= 0 || block <= 0 || n_blocks <= 0) return 0;
+            if (Hq % Hkv != 0) return 0;
+            return fwd_heads_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D);
         case MMATTN_OP_BWD:
             if (Hq <= 0 || Hkv <= 0 || D <= 0 || block <= 0 || n_blocks <= 0) return 0;
             return bwd_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D);
@@ -123,13 +127,33 @@ int mmattn_fwd(const void* q_loc, const void* k, const void* v, const uint64_t* 
                const int32_t* blocks, int32_t n_blocks, int32_t block, int64_t S, int32_t Hq,
                int32_t Hkv, int32_t D, float scale, int dtype, void* o_loc, float* lse, void* ws,
                size_t ws_bytes, void* stream) {
-    if (!o_loc || !lse) return MMATTN_ERR_NULL;
+    if (n_blocks > 0 && (!o_loc || !lse)) return MMATTN_ERR_NULL;
     int rc = check_attn(q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale, dtype);
     if (rc != MMATTN_OK) return rc;
     if (!aligned(o_loc, 16) || !aligned(lse, 4)) return MMATTN_ERR_SHAPE;
+    if (n_blocks == 0) return MMATTN_OK;          // a rank that received no block: no rows, no output
     const size_t need = fwd_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D);
     if (!ws || !aligned(ws, 256) || ws_bytes < need) return MMATTN_ERR_WORKSPACE;
-    AttnArgs a{q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale};
+    AttnArgs a{q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale, 0, Hkv, 0};
+    return launch_fwd(a, o_loc, lse, ws, (hipStream_t)stream);
+}
+
+int mmattn_fwd_heads(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
+                     const int32_t* blocks, int32_t n_blocks, int32_t block, int64_t S, int32_t Hq,
+                     int32_t Hkv, int32_t D, float scale, int dtype, int32_t kv_head_begin,
+                     int32_t kv_head_count, int32_t plan_ready, void* o_loc, float* lse, void* ws,
+                     size_t ws_bytes, void* stream) {
+    if (n_blocks > 0 && (!o_loc || !lse)) return MMATTN_ERR_NULL;
+    int rc = check_attn(q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale, dtype);
+    if (rc != MMATTN_OK) return rc;
+    if (kv_head_begin < 0 || kv_head_count < 1 || kv_head_begin > Hkv - kv_head_count)
+        return MMATTN_ERR_SHAPE;
+    if (!aligned(o_loc, 16) || !aligned(lse, 4)) return MMATTN_ERR_SHAPE;
+    if (n_blocks == 0) return MMATTN_OK;
+    const size_t need = fwd_heads_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D);
+    if (!ws || !aligned(ws, 256) || ws_bytes < need) return MMATTN_ERR_WORKSPACE;
+    AttnArgs a{q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale,
+               kv_head_begin, kv_head_count, plan_ready != 0};
     return launch_fwd(a, o_loc, lse, ws, (hipStream_t)stream);
 }
 
@@ -138,12 +162,14 @@ int mmattn_bwd(const void* q_loc, const void* k, const void* v, const uint64_t* 
                int32_t Hkv, int32_t D, float scale, int dtype, const void* o_loc, const float* lse,
                const void* do_loc, void* dq_loc, void* dk, void* dv, void* ws, size_t ws_bytes,
                void* stream) {
-    if (!o_loc || !lse || !do_loc || !dq_loc || !dk || !dv) return MMATTN_ERR_NULL;
+    if (!dk || !dv || (n_blocks > 0 && (!o_loc || !lse || !do_loc || !dq_loc))) return MMATTN_ERR_NULL;
     int rc = check_attn(q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale, dtype);
     if (rc != MMATTN_OK) return rc;
     if (!aligned(o_loc, 16) || !aligned(do_loc, 16) || !aligned(dq_loc, 16) || !aligned(dk, 16) ||
         !aligned(dv, 16) || !aligned(lse, 4))
         return MMATTN_ERR_SHAPE;
+    if (n_blocks == 0)                            // no rows: this rank's partial dK, dV are zero
+        return launch_zero_kv(dk, dv, (size_t)S * Hkv * D * 2, (hipStream_t)stream);
     const size_t need = bwd_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D);
     if (!ws || !aligned(ws, 256) || ws_bytes < need) return MMATTN_ERR_WORKSPACE;
     AttnArgs a{q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale};

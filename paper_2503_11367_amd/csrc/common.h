@@ -83,10 +83,15 @@ struct AttnArgs {
     int64_t S;
     int32_t Hq, Hkv, D;
     float scale;
+    // forward only: the window of KV heads to run (with their query heads), and whether
+    // the plan in the workspace is the one an earlier call built for the same share
+    int32_t kv_begin, kv_count, plan_ready;
 };
 size_t fwd_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t D);
+size_t fwd_heads_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t D);
 size_t bwd_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t D);
 int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st);
+int launch_zero_kv(void* dk, void* dv, size_t bytes_each, hipStream_t st);
 int launch_bwd(const AttnArgs& a, const void* o, const float* lse, const void* d_o,
                void* dq, void* dk, void* dv, void* ws, hipStream_t st);
 

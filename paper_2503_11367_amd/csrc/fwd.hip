@@ -51,9 +51,12 @@ __global__ void __launch_bounds__(256 * HPW, 2)
 fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
            const ushort_t* __restrict__ V, const uint64_t* __restrict__ bits,
            const int32_t* __restrict__ blocks, int32_t block, int64_t n_loc, int64_t S,
-           int32_t Hq, int32_t Hkv, float scale_log2, TilePlan plan, FwdSplit split,
-           const int32_t* __restrict__ err, ushort_t* __restrict__ O, float* __restrict__ LSE,
-           float* __restrict__ Opart, float* __restrict__ MLpart) {
+           int32_t Hq, int32_t Hkv, int32_t Hq_s, int32_t Hkv_s, float scale_log2, TilePlan plan,
+           FwdSplit split, const int32_t* __restrict__ err, ushort_t* __restrict__ O,
+           float* __restrict__ LSE, float* __restrict__ Opart, float* __restrict__ MLpart) {
+    // Hq, Hkv: heads this launch runs (a window of KV heads and their query heads, the
+    // tensor pointers already advanced to its first head); Hq_s, Hkv_s: heads per token
+    // in memory
     constexpr int NDS = D / 16;           // contraction steps over head_dim
     constexpr int NDB = D / 32;           // 32-wide output blocks over head_dim
     constexpr int NW = 4 * HPW;           // wavefronts per workgroup
@@ -110,7 +113,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         const uint64_t w = bits[q_pos];
         q_ss = word_ss(w);
         q_causal = word_att(w);
-        const ushort_t* qp = Q + (row * Hq + h) * (int64_t)D + hh * 8;
+        const ushort_t* qp = Q + (row * Hq_s + h) * (int64_t)D + hh * 8;
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds)
             qf[ds] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qp + ds * 16));
@@ -133,16 +136,16 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         const int R = 4 * (wave * NI + i) + (lane >> 4), p = lane & 15;
         int r, c;
         KT::src_of(R, p, r, c);
-        gk[i] = (uint32_t)(((r * Hkv + g) * D + c * 8) * 2);
+        gk[i] = (uint32_t)(((r * Hkv_s + g) * D + c * 8) * 2);
         VT::src_of(R, p, r, c);
-        gv[i] = (uint32_t)(((r * Hkv + g) * D + c * 8) * 2);
+        gv[i] = (uint32_t)(((r * Hkv_s + g) * D + c * 8) * 2);
     }
     const uint32_t lds_k = lds_addr_of(sm.k[0]) + (wave * NI) * 1024;
     const uint32_t lds_v = lds_addr_of(sm.v[0]) + (wave * NI) * 1024;
     auto issue_tile = [&](uint32_t entry, int stage) {
         const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
-        const ushort_t* kt = K + k0 * Hkv * D;         // wave-uniform tile bases
-        const ushort_t* vt = V + k0 * Hkv * D;
+        const ushort_t* kt = K + k0 * Hkv_s * D;       // wave-uniform tile bases
+        const ushort_t* vt = V + k0 * Hkv_s * D;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             dma16(kt, gk[i], lds_k + stage * kStageBytes + i * 1024);
@@ -450,7 +453,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         return;
     }
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    ushort_t* op = O + (row * Hq + h) * (int64_t)D + 4 * hh;
+    ushort_t* op = O + (row * Hq_s + h) * (int64_t)D + 4 * hh;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -470,7 +473,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 // unnormalised output o_c per slice, O = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m)
 // for m = max m_c.  One thread per (row, head, 4 head-dim values).
 __global__ void __launch_bounds__(256)
-fwd_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int32_t Hq, int32_t D,
+fwd_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int32_t Hq, int32_t Hq_s, int32_t D,
                    const int32_t* __restrict__ err, const float* __restrict__ Opart,
                    const float* __restrict__ MLpart, ushort_t* __restrict__ O,
                    float* __restrict__ LSE) {
@@ -506,12 +509,14 @@ fwd_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int32_t Hq, int
     bf16x4 out;
 #pragma unroll
     for (int u = 0; u < 4; ++u) out[u] = (__bf16)(num[u] * inv);
-    *(u32x2*)(O + (row * Hq + h) * (int64_t)D + d0) = __builtin_bit_cast(u32x2, out);
+    *(u32x2*)(O + (row * Hq_s + h) * (int64_t)D + d0) = __builtin_bit_cast(u32x2, out);
     if (d0 == 0)
         LSE[(int64_t)h * n_loc + row] = den > 0.f ? (m + __builtin_amdgcn_logf(den)) * kLn2 : -INFINITY;
 }
 
 // ---- host side ---------------------------------------------------------------------
+// Workspace: the plan (independent of which heads run) first, then the partial
+// results of split q-tile lists for `Hkv_run` KV heads run in one launch.
 struct FwdLayout {
     size_t err, clean_blocks, cls, kcount, klist, qorder, opart, mlpart, total;
     int32_t nq, nk;
@@ -519,11 +524,12 @@ struct FwdLayout {
 };
 
 static FwdLayout fwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t Hq, int32_t Hkv,
-                            int32_t D) {
+                            int32_t D, int32_t Hkv_run) {
     FwdLayout L;
+    const int32_t Hq_run = Hq / Hkv * Hkv_run;
     L.nq = (int32_t)((n_loc + kFwdBM - 1) / kFwdBM);
     L.nk = (int32_t)(S / kFwdBN);
-    L.split = list_split(L.nq, L.nk, Hq, Hkv);
+    L.split = list_split(L.nq, L.nk, Hq_run, Hkv_run);
     size_t off = 0;
     L.err = off;          off += 256;
     L.clean_blocks = off; off += align_up((size_t)n_blocks * 4, 256);
@@ -531,7 +537,7 @@ static FwdLayout fwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     L.kcount = off;       off += align_up((size_t)L.nq * 4, 256);
     L.klist = off;        off += align_up((size_t)L.nq * L.nk * 4, 256);
     L.qorder = off;       off += align_up((size_t)L.nq * 4, 256);
-    const size_t prow = L.split.cmax > 1 ? (size_t)L.split.cmax * L.nq * kFwdBM * Hq : 0;
+    const size_t prow = L.split.cmax > 1 ? (size_t)L.split.cmax * L.nq * kFwdBM * Hq_run : 0;
     L.opart = off;        off += align_up(prow * D * 4, 256);
     L.mlpart = off;       off += align_up(prow * 8, 256);
     L.total = off;
@@ -540,7 +546,15 @@ static FwdLayout fwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
 
 size_t fwd_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t D) {
     // n_blocks is not known here; n_loc/16 bounds it (block >= 16)
-    return fwd_layout(S, n_loc, (int32_t)(n_loc / 16 + 1), Hq, Hkv, D).total;
+    return fwd_layout(S, n_loc, (int32_t)(n_loc / 16 + 1), Hq, Hkv, D, Hkv).total;
+}
+
+size_t fwd_heads_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t D) {
+    // any window of KV heads: fewer heads per launch split the lists further
+    size_t most = 0;
+    for (int32_t c = 1; c <= Hkv; ++c)
+        most = std::max(most, fwd_layout(S, n_loc, (int32_t)(n_loc / 16 + 1), Hq, Hkv, D, c).total);
+    return most;
 }
 
 template <int D, int HPW, int NST>
@@ -548,16 +562,19 @@ static void launch_fwd_kernel(const AttnArgs& a, int64_t n_loc, int32_t nq, floa
                               const int32_t* clean, const TilePlan& plan, const FwdSplit& split,
                               const int32_t* err, void* o, float* lse, float* opart, float* mlpart,
                               hipStream_t st) {
-    const unsigned grid = (unsigned)((int64_t)nq * a.Hq / HPW * split.cmax);
+    const int32_t rep = a.Hq / a.Hkv, Hq_run = rep * a.kv_count;
+    const int64_t qo = (int64_t)a.kv_begin * rep * a.D, ko = (int64_t)a.kv_begin * a.D;
+    const unsigned grid = (unsigned)((int64_t)nq * Hq_run / HPW * split.cmax);
     hipLaunchKernelGGL((fwd_kernel<D, HPW, NST>), dim3(grid), dim3(256 * HPW), 0, st,
-                       (const ushort_t*)a.q, (const ushort_t*)a.k, (const ushort_t*)a.v, a.bits, clean,
-                       a.block, n_loc, a.S, a.Hq, a.Hkv, scale_log2, plan, split, err, (ushort_t*)o,
-                       lse, opart, mlpart);
+                       (const ushort_t*)a.q + qo, (const ushort_t*)a.k + ko, (const ushort_t*)a.v + ko,
+                       a.bits, clean, a.block, n_loc, a.S, Hq_run, a.kv_count, a.Hq, a.Hkv, scale_log2,
+                       plan, split, err, (ushort_t*)o + qo, lse + (int64_t)a.kv_begin * rep * n_loc,
+                       opart, mlpart);
 }
 
 int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st) {
     const int64_t n_loc = (int64_t)a.n_blocks * a.block;
-    const FwdLayout L = fwd_layout(a.S, n_loc, (int32_t)(n_loc / 16 + 1), a.Hq, a.Hkv, a.D);
+    const FwdLayout L = fwd_layout(a.S, n_loc, (int32_t)(n_loc / 16 + 1), a.Hq, a.Hkv, a.D, a.kv_count);
     float* opart = (float*)((char*)ws + L.opart);
     float* mlpart = (float*)((char*)ws + L.mlpart);
     char* base = (char*)ws;
@@ -571,16 +588,19 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
     plan.qorder = (int32_t*)(base + L.qorder);
     plan.ticket = err + 1;
 
-    int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
-    if (rc) return rc;
-    rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kFwdBM, kFwdBN, plan.cls, nullptr,
-                         nullptr, st);
-    if (rc) return rc;
-    rc = launch_compact_rows(plan, st);
-    if (rc) return rc;
+    if (!a.plan_ready) {
+        int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
+        if (rc) return rc;
+        rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kFwdBM, kFwdBN, plan.cls, nullptr,
+                             nullptr, st);
+        if (rc) return rc;
+        rc = launch_compact_rows(plan, st);
+        if (rc) return rc;
+    }
 
     const float scale_log2 = a.scale * kLog2e;
-    const bool pair = (a.Hq / a.Hkv) % 2 == 0;     // two heads of a KV group per workgroup
+    const int32_t rep = a.Hq / a.Hkv;
+    const bool pair = rep % 2 == 0;                // two heads of a KV group per workgroup
     stage_begin(MMATTN_STAGE_FWD, st);
     if (a.D == 128) {
         if (pair) launch_fwd_kernel<128, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, o, lse, opart, mlpart, st);
@@ -590,9 +610,12 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
         else      launch_fwd_kernel<64, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, o, lse, opart, mlpart, st);
     }
     if (L.split.cmax > 1) {
-        const int64_t threads = n_loc * a.Hq * (a.D / 4);
+        const int32_t Hq_run = rep * a.kv_count;
+        const int64_t threads = n_loc * Hq_run * (a.D / 4);
         hipLaunchKernelGGL(fwd_combine_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                           plan, L.split, n_loc, a.Hq, a.D, err, opart, mlpart, (ushort_t*)o, lse);
+                           plan, L.split, n_loc, Hq_run, a.Hq, a.D, err, opart, mlpart,
+                           (ushort_t*)o + (int64_t)a.kv_begin * rep * a.D,
+                           lse + (int64_t)a.kv_begin * rep * n_loc);
     }
     stage_end(MMATTN_STAGE_FWD, st);
     MM_LAUNCH_CHECK();

@@ -81,6 +81,25 @@ compact_kernel(const uint8_t* __restrict__ cls, int32_t n_lines, int32_t n_items
     }
 }
 
+// zero fill of two equally sized buffers (a kernel rather than a memset node, so
+// that the call can sit inside a captured graph)
+__global__ void __launch_bounds__(256)
+zero_pair_kernel(u32x4* __restrict__ a, u32x4* __restrict__ b, size_t n16) {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+        a[i] = z;
+        b[i] = z;
+    }
+}
+
+int launch_zero_kv(void* dk, void* dv, size_t bytes_each, hipStream_t st) {
+    const size_t n16 = bytes_each / 16;           // S*Hkv*D*2 with D in {64,128}: a multiple of 16
+    const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 4096);
+    hipLaunchKernelGGL(zero_pair_kernel, dim3(grid), dim3(256), 0, st, (u32x4*)dk, (u32x4*)dv, n16);
+    MM_LAUNCH_CHECK();
+    return MMATTN_OK;
+}
+
 int launch_compact_rows(const TilePlan& p, hipStream_t st) {
     hipLaunchKernelGGL(compact_kernel, dim3(p.nq), dim3(64), 0, st, p.cls, p.nq, p.nk,
                        (int64_t)p.nk, (int64_t)1, p.kcount, p.klist, p.qorder, p.ticket);

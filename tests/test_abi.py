@@ -98,6 +98,25 @@ def test_fwd_validation():
     assert fwd_rc(q=FAKE + 2) == -2           # alignment
     assert fwd_rc(ws=0) == -4
     assert fwd_rc(ws_bytes=16) == -4
+    # an empty share is valid, needs no per-row buffers and launches nothing
+    assert fwd_rc(n_blocks=0, q=0, blocks=0, o=0, lse=0, ws=0, ws_bytes=0) == 0
+    assert fwd_rc(n_blocks=0, k=0) == -1 and fwd_rc(n_blocks=-1) == -2
+
+
+def test_fwd_heads_validation():
+    f = mb.lib().mmattn_fwd_heads
+
+    def rc(begin, count, n_blocks=4, ws_bytes=1 << 30):
+        return f(FAKE, FAKE, FAKE, FAKE, FAKE, n_blocks, 128, 1024, 8, 4, 128, 0.1, 0, begin, count, 0,
+                 FAKE, FAKE, FAKE, ws_bytes, 0)
+    assert rc(-1, 1) == -2 and rc(0, 0) == -2 and rc(3, 2) == -2 and rc(4, 1) == -2
+    assert rc(0, 5) == -2
+    assert rc(1, 2, ws_bytes=64) == -4
+    assert rc(1, 2, n_blocks=0) == 0              # empty share: nothing to do
+    # one workspace serves every window, and is at least the whole-launch one
+    w_all = mb.workspace_size(mb.OP_FWD, 1024, 4, 128, 8, 4, 128)
+    w_win = mb.workspace_size(mb.OP_FWD_HEADS, 1024, 4, 128, 8, 4, 128)
+    assert w_win >= w_all > 0
 
 
 def test_bwd_validation():

@@ -93,6 +93,23 @@ def test_special_masks():
     run_case(wl.Layout(768, [(300, 100, 2)], [0, 200, 768]), [4, 1, 5], 128, 2, 2, 64, seed=43)
 
 
+def test_empty_share():
+    """A rank that received no block (more ranks than blocks): forward does
+    nothing, backward overwrites its partial dK, dV with zeros."""
+    lay = wl.Layout(512, [(100, 200, 1)], [0, 512])
+    t = make_tensors(5, 0, lay.S, 4, 2, 128)
+    bits = gpu_bits(lay)
+    bl = torch.zeros(0, dtype=torch.int32, device=DEV)
+    o, lse = mb.fwd(t["q"], t["k"], t["v"], bits, bl, 64)
+    assert o.shape == (0, 4, 128) and lse.shape == (4, 0)
+    dk = torch.full_like(t["k"], 3.0)
+    dv = torch.full_like(t["v"], -2.0)
+    dq = torch.empty_like(t["q"])
+    mb.bwd(t["q"], t["k"], t["v"], bits, bl, 64, o, lse, t["do"], out=(dq, dk, dv))
+    torch.cuda.synchronize()
+    assert (dk == 0).all() and (dv == 0).all()
+
+
 def test_rank_partials_sum_to_full():
     """Summing the ranks' partial dK/dV reproduces the single-rank result."""
     w = wl.workload(1)

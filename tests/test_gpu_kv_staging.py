@@ -1,0 +1,107 @@
+"""GPU parity of the head-window forward (mmattn_fwd_heads) and of the
+head-pipelined K/V staging built on it (paper section 4.3), against the float64
+oracle and against the whole-launch forward.  Tolerances as for mmattn_fwd."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from paper_2503_11367_amd import binding as mb
+from paper_2503_11367_amd import staging
+from paper_2503_11367_amd import workloads as wl
+
+from gpu_util import (DEV, bf16_to_f64, f64, fields, gpu_bits, make_tensors, max_abs, rel_l2)
+
+pytestmark = pytest.mark.gpu
+
+TOL_MAX, TOL_L2, TOL_LSE = 2e-2, 5e-3, 4.5e-3
+
+
+def oracle_fwd(lay, blocks, block, t, Hq, Hkv):
+    f = fields(lay)
+    rows = oa.rows_of_blocks(blocks, block)
+    Q, K, V = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"])
+    return oa.forward(Q, K, V, rows, f[0], f[1], f[2], modality=f[3], attend=f[4])
+
+
+def check(o, lse, o_ref, lse_ref):
+    og, lg = bf16_to_f64(o), lse.cpu().numpy().astype(np.float64)
+    assert np.isfinite(og).all()
+    assert max_abs(og, o_ref) < TOL_MAX and rel_l2(og, o_ref) < TOL_L2
+    assert max_abs(lg, lse_ref) < TOL_LSE
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,hps", [(8, 4, 128, 1), (8, 4, 64, 2), (4, 4, 128, 1), (12, 2, 128, 1)])
+def test_pipelined_equals_oracle(Hq, Hkv, D, hps):
+    lay = wl.layout_random(120 + Hq + D, S=1024, n_samples=2, max_spans=5, deny_prob=0.3)
+    blocks = [9, 1, 4, 6, 14, 3]
+    t = make_tensors(300 + Hq, len(blocks) * 64, lay.S, Hq, Hkv, D)
+    bits = gpu_bits(lay)
+    bl = torch.tensor(blocks, dtype=torch.int32, device=DEV)
+    # the staging buffers start as NaN: a kernel that ran ahead of its window's
+    # arrival would read them
+    ks = torch.full_like(t["k"], float("nan"))
+    vs = torch.full_like(t["v"], float("nan"))
+    o, lse = staging.fwd_head_pipelined(t["q"], t["k"], t["v"], bits, bl, 64, heads_per_stage=hps,
+                                        k_stage=ks, v_stage=vs)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle_fwd(lay, blocks, 64, t, Hq, Hkv)
+    check(o, lse, o_ref, lse_ref)
+    assert torch.equal(ks, t["k"]) and torch.equal(vs, t["v"])
+    # same share through the whole-launch entry point: same values up to the
+    # summation order of split lists
+    o2, lse2 = mb.fwd(t["q"], t["k"], t["v"], bits, bl, 64)
+    assert max_abs(bf16_to_f64(o), bf16_to_f64(o2)) < TOL_MAX
+    assert max_abs(lse.cpu().numpy().astype(np.float64), lse2.cpu().numpy().astype(np.float64)) < 1e-4
+
+
+def test_window_touches_only_its_heads():
+    """Heads outside the window are neither read (NaN there is harmless) nor
+    written (sentinel survives); windows in any order, plan reused."""
+    Hq, Hkv, D = 8, 4, 128
+    lay = wl.layout_random(131, S=512, n_samples=1, max_spans=3)
+    blocks = list(range(8))
+    t = make_tensors(77, 512, lay.S, Hq, Hkv, D)
+    bits = gpu_bits(lay)
+    bl = torch.tensor(blocks, dtype=torch.int32, device=DEV)
+    o_ref, lse_ref = oracle_fwd(lay, blocks, 64, t, Hq, Hkv)
+    ws = torch.empty(mb.workspace_size(mb.OP_FWD_HEADS, lay.S, 8, 64, Hq, Hkv, D), dtype=torch.uint8, device=DEV)
+    o = torch.full_like(t["q"], 7.0)
+    lse = torch.full((Hq, 512), 7.0, dtype=torch.float32, device=DEV)
+    for n, (g0, c) in enumerate([(2, 1), (0, 2), (3, 1)]):
+        k = torch.full_like(t["k"], float("nan"))
+        v = torch.full_like(t["v"], float("nan"))
+        k[:, g0:g0 + c] = t["k"][:, g0:g0 + c]
+        v[:, g0:g0 + c] = t["v"][:, g0:g0 + c]
+        before = o.clone()
+        mb.fwd_heads(t["q"], k, v, bits, bl, 64, g0, c, plan_ready=n > 0, out=(o, lse), ws=ws)
+        torch.cuda.synchronize()
+        hs = slice(2 * g0, 2 * (g0 + c))
+        outside = torch.ones(Hq, dtype=torch.bool)
+        outside[hs] = False
+        assert torch.equal(o[:, outside], before[:, outside])
+        check(o[:, hs], lse[hs], o_ref[:, hs], lse_ref[hs])
+    check(o, lse, o_ref, lse_ref)
+
+
+def test_workload2_pipelined_sampled():
+    """The 8k workload in the configuration bench.py times: whole sequence,
+    one KV head per stage; sampled rows and heads against the oracle."""
+    w = wl.workload(2)
+    lay = w.layout
+    nb = lay.S // w.N_B
+    t = make_tensors(w.tensor_seed, lay.S, lay.S, w.Hq, w.Hkv, w.D)
+    bits = gpu_bits(lay)
+    bl = torch.arange(nb, dtype=torch.int32, device=DEV)
+    o, lse = staging.fwd_head_pipelined(t["q"], t["k"], t["v"], bits, bl, w.N_B, heads_per_stage=1)
+    torch.cuda.synchronize()
+    f = fields(lay)
+    rng = np.random.default_rng(5)
+    sel = np.sort(rng.choice(lay.S, size=192, replace=False))
+    Q, K, V = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"])
+    rep = w.Hq // w.Hkv
+    for h in (0, 13, 31):
+        g = h // rep
+        o_ref, lse_ref = oa.forward(Q[sel][:, h:h + 1], K[:, g:g + 1], V[:, g:g + 1], sel, f[0], f[1], f[2],
+                                    modality=f[3], attend=f[4])
+        check(o[sel][:, h:h + 1], lse[h:h + 1][:, sel], o_ref, lse_ref)
