@@ -122,6 +122,46 @@ def mfma_ceiling(device):
     return res
 
 
+def kv_staging_report(dev, bits, bl, w, reps=5):
+    """Forward with K/V arriving head by head on a copy stream (section 4.3 on one
+    GPU, mmattn_fwd_staged) against copying everything first and then running
+    the whole-launch forward; milliseconds per forward, HIP events on the
+    compute stream."""
+    import torch
+    from paper_2503_11367_amd import binding as mb
+    ks, vs = torch.empty_like(dev["k"]), torch.empty_like(dev["v"])
+    copy = torch.cuda.Stream()
+    S, nb = dev["k"].shape[0], bl.numel()
+    ws = torch.empty(mb.workspace_size(mb.OP_FWD_HEADS, S, nb, w.N_B, w.Hq, w.Hkv, w.D),
+                     dtype=torch.uint8, device=ks.device)
+    out = (torch.empty_like(dev["q"]),
+           torch.empty((w.Hq, dev["q"].shape[0]), dtype=torch.float32, device=ks.device))
+
+    def sequential():
+        ks.copy_(dev["k"]); vs.copy_(dev["v"])
+        mb.fwd(dev["q"], ks, vs, bits, bl, w.N_B, ws=ws, out=out)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    res = {"copy_then_fwd_ms": timed(sequential)}
+    for hps in (1, 2, 4):
+        if w.Hkv % hps == 0 and hps < w.Hkv:
+            res[f"staged_{hps}_kv_heads_per_stage_ms"] = timed(
+                lambda: mb.fwd_staged(dev["q"], dev["k"], dev["v"], ks, vs, bits, bl, w.N_B, hps, copy,
+                                      out=out, ws=ws))
+    return res
+
+
 def cpu_baseline(w, blocks, host_q, host_k, host_v, host_do, n_heads, pairs):
     """Time the float64 oracle (forward + backward) on the Q heads of one KV
     group, all rows of the share."""
@@ -276,6 +316,7 @@ def main():
     out["planning_us"] = (time.perf_counter() - tp0) / 10 * 1e6
     out["imbalance"] = imbalance_report(device)
     out["mfma_ceiling_tflops"] = mfma_ceiling(device)
+    out["kv_staging"] = kv_staging_report(dev, bits, rblocks[int(off_h[g]):int(off_h[g + 1])], w)
 
     if not args.no_cpu_baseline:
         blocks = rblocks[int(off_h[g]):int(off_h[g + 1])].cpu().numpy()

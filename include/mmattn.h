@@ -33,7 +33,8 @@
  * Ownership: the caller owns every buffer and the stream.  The library
  * allocates no device memory, never synchronises the stream and keeps no
  * state between calls (the one exception, the optional timing events of
- * mmattn_stage_events, is stated there); scratch comes in through `ws` (size
+ * mmattn_stage_events, is stated there; mmattn_fwd_staged creates and destroys
+ * HIP events inside the call); scratch comes in through `ws` (size
  * from mmattn_workspace_size, 256-byte aligned) and may be reused by the next
  * call on the same stream.  Host pointers are read before the call returns.
  * Results are deterministic: no atomics on floating-point data, every sum is
@@ -175,6 +176,29 @@ int mmattn_fwd_heads(const void* q_loc, const void* k, const void* v, const uint
                      int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,
                      int32_t kv_head_begin, int32_t kv_head_count, int32_t plan_ready,
                      void* o_loc, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/* Section 4.3 on one GPU: the forward with K/V arriving head by head.  For
+ * each window of `heads_per_stage` KV heads, in order, the window's heads of
+ * k_src, v_src are copied into k_stage, v_stage on `copy_stream` (a stand-in
+ * for the arrival of the gathered heads) and `stream` waits for that window
+ * only before running mmattn_fwd_heads on it, so the transfers of the later
+ * windows overlap the attention of the earlier ones.
+ *   k_src, v_src      device [S,Hkv,D], read on copy_stream once everything
+ *                     enqueued on `stream` before this call has completed
+ *   k_stage, v_stage  device [S,Hkv,D], overwritten with k_src, v_src
+ *   copy_stream       a HIP stream other than `stream`, default priority
+ *   ws                mmattn_workspace_size(MMATTN_OP_FWD_HEADS, ...) bytes
+ * When the call returns, all work has been enqueued; `stream` has been made to
+ * wait for every copy, so later work on `stream` may reuse all buffers.
+ * Creates and destroys up to Hkv/heads_per_stage + 1 HIP events (no device
+ * memory).  Hkv % heads_per_stage == 0, at most MMATTN_MAX_STAGES windows. */
+#define MMATTN_MAX_STAGES 64
+int mmattn_fwd_staged(const void* q_loc, const void* k_src, const void* v_src,
+                      void* k_stage, void* v_stage, const uint64_t* bits,
+                      const int32_t* blocks, int32_t n_blocks, int32_t block,
+                      int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,
+                      int32_t heads_per_stage, void* o_loc, float* lse,
+                      void* ws, size_t ws_bytes, void* copy_stream, void* stream);
 
 /* Backward of mmattn_fwd for the same rank share.
  *   o_loc, lse   what mmattn_fwd wrote;  do_loc upstream gradient

@@ -65,6 +65,9 @@ def lib() -> ctypes.CDLL:
         L.mmattn_fwd_heads.restype = ctypes.c_int
         L.mmattn_fwd_heads.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
                                        ctypes.c_int, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]
+        L.mmattn_fwd_staged.restype = ctypes.c_int
+        L.mmattn_fwd_staged.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32,
+                                        _i32, _f32, ctypes.c_int, _i32, _vp, _vp, _vp, _sz, _vp, _vp]
         L.mmattn_bwd.restype = ctypes.c_int
         L.mmattn_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
                                  ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -195,6 +198,28 @@ def fwd_heads(q_loc, k, v, bits, blocks, block: int, kv_head_begin: int, kv_head
                                 _stream(stream))
     _check("mmattn_fwd_heads", rc)
     return o, lse
+
+
+def fwd_staged(q_loc, k_src, v_src, k_stage, v_stage, bits, blocks, block: int, heads_per_stage: int,
+               copy_stream, out=None, ws: Optional[torch.Tensor] = None, scale: Optional[float] = None,
+               stream=None):
+    """mmattn_fwd_staged: forward with K/V copied window by window on copy_stream
+    while the windows already copied are attended on `stream`."""
+    n_loc, Hq, D = q_loc.shape
+    S, Hkv, _ = k_src.shape
+    scale = float(D) ** -0.5 if scale is None else float(scale)
+    if out is None:
+        out = (torch.empty_like(q_loc), torch.empty((Hq, n_loc), dtype=torch.float32, device=q_loc.device))
+    if ws is None:
+        ws = _workspace(workspace_size(OP_FWD_HEADS, S, blocks.numel(), block, Hq, Hkv, D), q_loc.device)
+    rc = lib().mmattn_fwd_staged(_ptr(q_loc), _ptr(k_src), _ptr(v_src), _ptr(k_stage), _ptr(v_stage),
+                                 _ptr(bits), _ptr(blocks), blocks.numel(), block, S, Hq, Hkv, D, scale,
+                                 BF16, heads_per_stage, _ptr(out[0]), _ptr(out[1]), _ptr(ws), ws.numel(),
+                                 _stream(copy_stream), _stream(stream))
+    _check("mmattn_fwd_staged", rc)
+    for t in (k_src, v_src, k_stage, v_stage):
+        t.record_stream(copy_stream)
+    return out
 
 
 def bwd(q_loc, k, v, bits, blocks, block: int, o_loc, lse, do_loc, scale: Optional[float] = None,

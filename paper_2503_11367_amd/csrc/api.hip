@@ -157,6 +157,58 @@ int mmattn_fwd_heads(const void* q_loc, const void* k, const void* v, const uint
     return launch_fwd(a, o_loc, lse, ws, (hipStream_t)stream);
 }
 
+int mmattn_fwd_staged(const void* q_loc, const void* k_src, const void* v_src, void* k_stage,
+                      void* v_stage, const uint64_t* bits, const int32_t* blocks, int32_t n_blocks,
+                      int32_t block, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale,
+                      int dtype, int32_t heads_per_stage, void* o_loc, float* lse, void* ws,
+                      size_t ws_bytes, void* copy_stream, void* stream) {
+    if (!k_src || !v_src || (n_blocks > 0 && (!o_loc || !lse))) return MMATTN_ERR_NULL;
+    int rc = check_attn(q_loc, k_stage, v_stage, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale, dtype);
+    if (rc != MMATTN_OK) return rc;
+    if (heads_per_stage < 1 || Hkv % heads_per_stage != 0) return MMATTN_ERR_SHAPE;
+    if (!aligned(o_loc, 16) || !aligned(lse, 4) || !aligned(k_src, 16) || !aligned(v_src, 16))
+        return MMATTN_ERR_SHAPE;
+    if (copy_stream == stream) return MMATTN_ERR_SHAPE;          // nothing would overlap
+    const size_t need = n_blocks > 0 ? fwd_heads_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D) : 0;
+    if (n_blocks > 0 && (!ws || !aligned(ws, 256) || ws_bytes < need)) return MMATTN_ERR_WORKSPACE;
+
+    hipStream_t cs = (hipStream_t)copy_stream, st = (hipStream_t)stream;
+    const int n_stage = Hkv / heads_per_stage;
+    const size_t pitch = (size_t)Hkv * D * 2, width = (size_t)heads_per_stage * D * 2;
+    hipEvent_t ready = nullptr, arrived[MMATTN_MAX_STAGES] = {};
+    if (n_stage > MMATTN_MAX_STAGES) return MMATTN_ERR_UNSUPPORTED;
+    rc = MMATTN_OK;
+    auto ok = [&](hipError_t e) { if (e != hipSuccess && rc == MMATTN_OK) rc = MMATTN_ERR_HIP; return e == hipSuccess; };
+    // the copy stream starts once the inputs and the staging buffers are free on `stream`
+    if (ok(hipEventCreateWithFlags(&ready, hipEventDisableTiming)) && ok(hipEventRecord(ready, st)))
+        ok(hipStreamWaitEvent(cs, ready, 0));
+    for (int i = 0; i < n_stage && rc == MMATTN_OK; ++i) {
+        const size_t off = (size_t)i * width;
+        ok(hipMemcpy2DAsync((char*)k_stage + off, pitch, (const char*)k_src + off, pitch, width,
+                            (size_t)S, hipMemcpyDeviceToDevice, cs));
+        ok(hipMemcpy2DAsync((char*)v_stage + off, pitch, (const char*)v_src + off, pitch, width,
+                            (size_t)S, hipMemcpyDeviceToDevice, cs));
+        if (ok(hipEventCreateWithFlags(&arrived[i], hipEventDisableTiming)))
+            ok(hipEventRecord(arrived[i], cs));
+    }
+    for (int i = 0; i < n_stage && rc == MMATTN_OK; ++i) {
+        if (!ok(hipStreamWaitEvent(st, arrived[i], 0))) break;
+        if (n_blocks == 0) continue;
+        AttnArgs a{q_loc, k_stage, v_stage, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale,
+                   i * heads_per_stage, heads_per_stage, i > 0};
+        rc = launch_fwd(a, o_loc, lse, ws, st);
+    }
+    // on an error part-way, `stream` still has to wait for whatever the copy stream was given
+    if (rc != MMATTN_OK)
+        for (int i = 0; i < n_stage; ++i)
+            if (arrived[i]) (void)hipStreamWaitEvent(st, arrived[i], 0);
+    // destroying a recorded event is deferred by the runtime until it has completed
+    if (ready) (void)hipEventDestroy(ready);
+    for (int i = 0; i < n_stage; ++i)
+        if (arrived[i]) (void)hipEventDestroy(arrived[i]);
+    return rc;
+}
+
 int mmattn_bwd(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
                const int32_t* blocks, int32_t n_blocks, int32_t block, int64_t S, int32_t Hq,
                int32_t Hkv, int32_t D, float scale, int dtype, const void* o_loc, const float* lse,

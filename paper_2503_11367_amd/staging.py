@@ -7,6 +7,12 @@ gathered K/V: it moves one window of KV heads after the other from a source
 buffer into the staging buffer the attention reads; the compute stream waits
 for each window's event and runs mmattn_fwd_heads on it.  The share's tile
 plan is built by the first call and reused by the others.
+
+A launch over one or two KV heads has few work items and leaves CUs idle
+towards its end; with `compute_streams` > 1 the windows are dealt round-robin
+to that many streams (each with its own workspace and plan), so the next
+window's kernel fills the CUs the previous one no longer uses -- the
+multiple-stream execution of the paper's appendix on context parallelism.
 """
 from __future__ import annotations
 
@@ -22,12 +28,15 @@ def fwd_head_pipelined(q_loc: torch.Tensor, k_src: torch.Tensor, v_src: torch.Te
                        heads_per_stage: int = 1, k_stage: Optional[torch.Tensor] = None,
                        v_stage: Optional[torch.Tensor] = None,
                        copy_stream: Optional[torch.cuda.Stream] = None,
-                       ws: Optional[torch.Tensor] = None, out=None, scale: Optional[float] = None):
+                       ws: Optional[torch.Tensor] = None, out=None, scale: Optional[float] = None,
+                       compute_streams: int = 1, side_streams=None, side_ws=None):
     """Forward for one rank share with K/V arriving window by window.
 
     k_src, v_src [S,Hkv,D]: where the gathered heads come from; k_stage,
     v_stage: the buffers the kernels read (allocated if not given).  Returns
-    (o_loc, lse) on the current stream, like binding.fwd."""
+    (o_loc, lse) on the current stream, like binding.fwd.  compute_streams > 1
+    adds side streams (side_streams / side_ws: reuse these instead of creating
+    compute_streams - 1 streams and workspaces per call)."""
     n_loc, Hq, D = q_loc.shape
     S, Hkv, _ = k_src.shape
     dev = q_loc.device
@@ -52,10 +61,26 @@ def fwd_head_pipelined(q_loc: torch.Tensor, k_src: torch.Tensor, v_src: torch.Te
             ev = torch.cuda.Event()
             ev.record(copy)
             arrived.append(ev)
+    n_side = max(0, compute_streams - 1)
+    if side_streams is None:
+        side_streams = [torch.cuda.Stream(device=dev) for _ in range(n_side)]
+    if side_ws is None:
+        side_ws = [torch.empty_like(ws) for _ in range(n_side)]
+    lanes = [(compute, ws)] + list(zip(side_streams[:n_side], side_ws[:n_side]))
+    for st, _ in lanes[1:]:
+        st.wait_stream(compute)                     # q_loc, bits, blocks, outputs are ready
+    used = [False] * len(lanes)
     for i, g0 in enumerate(range(0, Hkv, heads_per_stage)):
-        compute.wait_event(arrived[i])
+        j = i % len(lanes)
+        st, w = lanes[j]
+        st.wait_event(arrived[i])
         mb.fwd_heads(q_loc, k_stage, v_stage, bits, blocks, block, g0, heads_per_stage,
-                     plan_ready=i > 0, out=out, ws=ws, scale=scale, stream=compute)
+                     plan_ready=used[j], out=out, ws=w, scale=scale, stream=st)
+        used[j] = True
+    for st, w in lanes[1:]:
+        compute.wait_stream(st)
+        for t in (q_loc, bits, blocks, k_stage, v_stage, out[0], out[1], w):
+            t.record_stream(st)
     for t in (k_src, v_src, k_stage, v_stage):
         t.record_stream(copy)
     return out

@@ -119,6 +119,18 @@ def test_fwd_heads_validation():
     assert w_win >= w_all > 0
 
 
+def test_fwd_staged_validation():
+    f = mb.lib().mmattn_fwd_staged
+
+    def rc(hps=1, k_src=FAKE, copy=FAKE, stream=0, ws_bytes=1 << 30):
+        return f(FAKE, k_src, FAKE, FAKE, FAKE, FAKE, FAKE, 4, 128, 1024, 8, 4, 128, 0.1, 0, hps,
+                 FAKE, FAKE, FAKE, ws_bytes, copy, stream)
+    assert rc(k_src=0) == -1
+    assert rc(hps=0) == -2 and rc(hps=3) == -2
+    assert rc(copy=0, stream=0) == -2             # the two streams must differ
+    assert rc(ws_bytes=64) == -4
+
+
 def test_bwd_validation():
     f = mb.lib().mmattn_bwd
     args = [FAKE, FAKE, FAKE, FAKE, FAKE, 4, 128, 1024, 4, 2, 128, 0.1, 0,

@@ -31,8 +31,9 @@ def check(o, lse, o_ref, lse_ref):
     assert max_abs(lg, lse_ref) < TOL_LSE
 
 
-@pytest.mark.parametrize("Hq,Hkv,D,hps", [(8, 4, 128, 1), (8, 4, 64, 2), (4, 4, 128, 1), (12, 2, 128, 1)])
-def test_pipelined_equals_oracle(Hq, Hkv, D, hps):
+@pytest.mark.parametrize("Hq,Hkv,D,hps,ncs", [(8, 4, 128, 1, 1), (8, 4, 64, 2, 2), (4, 4, 128, 1, 3),
+                                              (12, 2, 128, 1, 2)])
+def test_pipelined_equals_oracle(Hq, Hkv, D, hps, ncs):
     lay = wl.layout_random(120 + Hq + D, S=1024, n_samples=2, max_spans=5, deny_prob=0.3)
     blocks = [9, 1, 4, 6, 14, 3]
     t = make_tensors(300 + Hq, len(blocks) * 64, lay.S, Hq, Hkv, D)
@@ -43,7 +44,7 @@ def test_pipelined_equals_oracle(Hq, Hkv, D, hps):
     ks = torch.full_like(t["k"], float("nan"))
     vs = torch.full_like(t["v"], float("nan"))
     o, lse = staging.fwd_head_pipelined(t["q"], t["k"], t["v"], bits, bl, 64, heads_per_stage=hps,
-                                        k_stage=ks, v_stage=vs)
+                                        k_stage=ks, v_stage=vs, compute_streams=ncs)
     torch.cuda.synchronize()
     o_ref, lse_ref = oracle_fwd(lay, blocks, 64, t, Hq, Hkv)
     check(o, lse, o_ref, lse_ref)
@@ -53,6 +54,26 @@ def test_pipelined_equals_oracle(Hq, Hkv, D, hps):
     o2, lse2 = mb.fwd(t["q"], t["k"], t["v"], bits, bl, 64)
     assert max_abs(bf16_to_f64(o), bf16_to_f64(o2)) < TOL_MAX
     assert max_abs(lse.cpu().numpy().astype(np.float64), lse2.cpu().numpy().astype(np.float64)) < 1e-4
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,hps", [(8, 4, 128, 1), (8, 4, 64, 2), (6, 2, 128, 2), (16, 8, 128, 1)])
+def test_staged_entry_point(Hq, Hkv, D, hps):
+    """mmattn_fwd_staged: copies and windows enqueued by the library itself."""
+    lay = wl.layout_random(140 + Hq + D, S=1024, n_samples=2, max_spans=5, deny_prob=0.3)
+    blocks = [2, 11, 4, 7, 15]
+    t = make_tensors(400 + Hq, len(blocks) * 64, lay.S, Hq, Hkv, D)
+    bits = gpu_bits(lay)
+    bl = torch.tensor(blocks, dtype=torch.int32, device=DEV)
+    ks = torch.full_like(t["k"], float("nan"))
+    vs = torch.full_like(t["v"], float("nan"))
+    copy = torch.cuda.Stream()
+    o_ref, lse_ref = oracle_fwd(lay, blocks, 64, t, Hq, Hkv)
+    for _ in range(2):                   # second call: buffers reused straight away
+        o, lse = mb.fwd_staged(t["q"], t["k"], t["v"], ks, vs, bits, bl, 64, hps, copy)
+        torch.cuda.synchronize()
+        check(o, lse, o_ref, lse_ref)
+        assert torch.equal(ks, t["k"]) and torch.equal(vs, t["v"])
+        ks.fill_(float("nan")); vs.fill_(float("nan"))
 
 
 def test_window_touches_only_its_heads():
@@ -93,7 +114,8 @@ def test_workload2_pipelined_sampled():
     t = make_tensors(w.tensor_seed, lay.S, lay.S, w.Hq, w.Hkv, w.D)
     bits = gpu_bits(lay)
     bl = torch.arange(nb, dtype=torch.int32, device=DEV)
-    o, lse = staging.fwd_head_pipelined(t["q"], t["k"], t["v"], bits, bl, w.N_B, heads_per_stage=1)
+    o, lse = staging.fwd_head_pipelined(t["q"], t["k"], t["v"], bits, bl, w.N_B, heads_per_stage=1,
+                                        compute_streams=2)
     torch.cuda.synchronize()
     f = fields(lay)
     rng = np.random.default_rng(5)
