@@ -148,7 +148,8 @@ int mmattn_balance(const uint64_t* d_W, int32_t nB, int32_t P,
  *                          key gets O = 0 and LSE = -inf
  *   scale                  softmax scale (1/sqrt(D) usually), > 0
  * Requires S % 128 == 0, block % 16 == 0, S % block == 0, D in {64,128},
- * 16-byte aligned tensors.  n_blocks may be 0 (Alg. 1 leaves a rank empty when
+ * 16-byte aligned tensors, S <= 2^30, Hq <= 4096, n_blocks * block <=
+ * 65535 * 64 (else MMATTN_ERR_UNSUPPORTED).  n_blocks may be 0 (Alg. 1 leaves a rank empty when
  * there are more ranks than blocks): nothing is read or written, and q_loc,
  * blocks, o_loc, lse may be null. */
 int mmattn_fwd(const void* q_loc, const void* k, const void* v, const uint64_t* bits,

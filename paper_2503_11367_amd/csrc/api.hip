@@ -20,6 +20,8 @@ int check_attn(const void* q, const void* k, const void* v, const uint64_t* bits
     if (D != 64 && D != 128) return MMATTN_ERR_UNSUPPORTED;
     if (S % 128 != 0 || block % 16 != 0) return MMATTN_ERR_UNSUPPORTED;
     if (S > ((int64_t)1 << 30) || Hq > 4096) return MMATTN_ERR_UNSUPPORTED;
+    // the plans put one 64-row q-tile per grid row (at most 65535 of them)
+    if ((int64_t)n_blocks * block > (int64_t)65535 * 64) return MMATTN_ERR_UNSUPPORTED;
     if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(bits, 8) ||
         !aligned(blocks, 4))
         return MMATTN_ERR_SHAPE;

@@ -9,10 +9,11 @@ namespace mm {
 struct DevSpan { int64_t start, len; int32_t modality, flags; };
 static_assert(sizeof(DevSpan) == sizeof(mmattn_span), "span layout");
 
-__global__ void __launch_bounds__(256)
-encode_kernel(const DevSpan* __restrict__ spans, int32_t n_spans,
-              const int64_t* __restrict__ sample_off, int32_t n_samples,
-              int64_t S, uint64_t* __restrict__ bits) {
+// the word of token t; spans / sample_off may live in global memory or in the
+// kernel-argument segment
+__device__ __forceinline__ void encode_token(const DevSpan* spans, int32_t n_spans,
+                                             const int64_t* sample_off, int32_t n_samples, int64_t S,
+                                             uint64_t* __restrict__ bits) {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= S) return;
     // sample = last i with sample_off[i] <= t
@@ -39,8 +40,40 @@ encode_kernel(const DevSpan* __restrict__ spans, int32_t n_spans,
     bits[t] = w | (causal << kCausalBit);
 }
 
+__global__ void __launch_bounds__(256)
+encode_kernel(const DevSpan* __restrict__ spans, int32_t n_spans,
+              const int64_t* __restrict__ sample_off, int32_t n_samples,
+              int64_t S, uint64_t* __restrict__ bits) {
+    encode_token(spans, n_spans, sample_off, n_samples, S, bits);
+}
+
+// Short lists travel by value in the kernel arguments: no staging copies, and the
+// call can be captured into a graph.
+constexpr int kInlineSpans = 64, kInlineSamples = 64;
+struct InlineLayout {
+    DevSpan spans[kInlineSpans];
+    int64_t sample_off[kInlineSamples + 1];
+};
+
+__global__ void __launch_bounds__(256)
+encode_inline_kernel(const InlineLayout lay, int32_t n_spans, int32_t n_samples, int64_t S,
+                     uint64_t* __restrict__ bits) {
+    encode_token(lay.spans, n_spans, lay.sample_off, n_samples, S, bits);
+}
+
 int launch_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* sample_off,
                   int32_t n_samples, int64_t S, uint64_t* d_bits, void* ws, hipStream_t st) {
+    const unsigned n_wg = (unsigned)((S + 255) / 256);
+    if (n_spans <= kInlineSpans && n_samples <= kInlineSamples) {
+        InlineLayout lay{};
+        for (int j = 0; j < n_spans; ++j)
+            lay.spans[j] = DevSpan{spans[j].start, spans[j].len, spans[j].modality, spans[j].flags};
+        for (int i = 0; i <= n_samples; ++i) lay.sample_off[i] = sample_off[i];
+        hipLaunchKernelGGL(encode_inline_kernel, dim3(n_wg), dim3(256), 0, st, lay, n_spans, n_samples, S,
+                           d_bits);
+        MM_LAUNCH_CHECK();
+        return MMATTN_OK;
+    }
     char* base = (char*)ws;
     DevSpan* d_spans = (DevSpan*)base;
     int64_t* d_off = (int64_t*)(base + align_up((size_t)n_spans * sizeof(DevSpan), 256));

@@ -41,6 +41,7 @@ int launch_validate_blocks(const int32_t* blocks, int32_t n_blocks, int64_t n_se
 // the line's non-empty tiles.  The wavefront that finishes last (a ticket counter,
 // zeroed by validate_blocks_kernel) then ranks the lines: order[rank] = line, by
 // (count descending, line ascending), so that heavy lines are scheduled first.
+constexpr int kCompactChunk = 2048;
 __global__ void __launch_bounds__(64)
 compact_kernel(const uint8_t* __restrict__ cls, int32_t n_lines, int32_t n_items,
                int64_t line_stride, int64_t item_stride, int32_t* __restrict__ count,
@@ -70,14 +71,26 @@ compact_kernel(const uint8_t* __restrict__ cls, int32_t n_lines, int32_t n_items
     }
     if (!__shfl(last, 0)) return;
     __threadfence();
-    for (int a = lane; a < n_lines; a += kWave) {
-        const int ca = __hip_atomic_load(&count[a], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // the counts go through LDS in chunks, so that the quadratic comparison reads
+    // (all lanes the same address: a broadcast) never go back to memory
+    __shared__ int32_t cnt_s[kCompactChunk];
+    for (int a0 = 0; a0 < n_lines; a0 += kWave) {
+        const int a = a0 + lane;
+        const int ca = a < n_lines
+                           ? __hip_atomic_load(&count[a], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
         int pos = 0;
-        for (int b = 0; b < n_lines; ++b) {
-            const int cb = __hip_atomic_load(&count[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            pos += (cb > ca || (cb == ca && b < a)) ? 1 : 0;
+        for (int b0 = 0; b0 < n_lines; b0 += kCompactChunk) {
+            const int nb = min(kCompactChunk, n_lines - b0);
+            __syncthreads();                 // single-wave workgroup: orders the LDS accesses
+            for (int b = lane; b < nb; b += kWave)
+                cnt_s[b] = __hip_atomic_load(&count[b0 + b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            for (int b = 0; b < nb; ++b) {
+                const int cb = cnt_s[b];
+                pos += (cb > ca || (cb == ca && b0 + b < a)) ? 1 : 0;
+            }
         }
-        order[pos] = a;
+        if (a < n_lines) order[pos] = a;
     }
 }
 

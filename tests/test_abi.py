@@ -95,6 +95,7 @@ def test_fwd_validation():
     assert fwd_rc(D=96) == -3
     assert fwd_rc(dtype=1) == -3
     assert fwd_rc(block=8, S=1024) == -3      # block % 16
+    assert fwd_rc(S=1 << 23, n_blocks=(65535 * 64) // 128 + 1) == -3      # share too long for one launch
     assert fwd_rc(q=FAKE + 2) == -2           # alignment
     assert fwd_rc(ws=0) == -4
     assert fwd_rc(ws_bytes=16) == -4

@@ -43,6 +43,15 @@ def test_encode_small(idx):
     assert np.array_equal(to_np_u64(gpu_bits(lay)), oracle_bits(lay))
 
 
+def test_encode_long_lists():
+    """More spans / samples than travel inside the kernel arguments: the lists
+    are staged through the workspace."""
+    for seed, ns in ((3, 80), (4, 200), (5, 30)):
+        lay = wl.layout_random(seed, S=8192, n_samples=ns, max_spans=4, noncausal_prob=0.2, deny_prob=0.2)
+        assert ns > 64 or len(lay.spans) > 64 or seed == 5
+        assert np.array_equal(to_np_u64(gpu_bits(lay)), oracle_bits(lay))
+
+
 @pytest.mark.parametrize("c", [1, 2, 3, 4, 5])
 def test_encode_workloads(c):
     lay = wl.workload(c).layout
