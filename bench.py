@@ -192,6 +192,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2, the metric's config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--path-only", action="store_true",
+                    help="skip the side reports (imbalance of the other workloads, matrix-pipe "
+                         "ceiling, staged forward) so that a profiler sees the timed path only")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a known-size kernel "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -314,9 +317,10 @@ def main():
         plan_on_gpu(w, device)
     torch.cuda.synchronize()
     out["planning_us"] = (time.perf_counter() - tp0) / 10 * 1e6
-    out["imbalance"] = imbalance_report(device)
-    out["mfma_ceiling_tflops"] = mfma_ceiling(device)
-    out["kv_staging"] = kv_staging_report(dev, bits, rblocks[int(off_h[g]):int(off_h[g + 1])], w)
+    if not args.path_only:
+        out["imbalance"] = imbalance_report(device)
+        out["mfma_ceiling_tflops"] = mfma_ceiling(device)
+        out["kv_staging"] = kv_staging_report(dev, bits, rblocks[int(off_h[g]):int(off_h[g + 1])], w)
 
     if not args.no_cpu_baseline:
         blocks = rblocks[int(off_h[g]):int(off_h[g + 1])].cpu().numpy()

@@ -120,6 +120,13 @@ def test_balance_paper_example_and_edges():
     check_balance([2 ** 63, 2 ** 62, 2 ** 62, 1], 2)     # needs full 64-bit loads
 
 
+def test_balance_maximum_sizes():
+    """MMATTN_MAX_BLOCKS blocks over MMATTN_MAX_RANKS ranks, many ties."""
+    rng = np.random.default_rng(99)
+    check_balance(rng.integers(0, 50, size=16384).tolist(), 1024)
+    check_balance(rng.integers(0, 2 ** 50, size=16384).tolist(), 1023)
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_balance_random(seed):
     rng = np.random.default_rng(seed)
