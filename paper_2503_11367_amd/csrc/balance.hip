@@ -6,10 +6,11 @@
 //
 //   phase 1  every thread ranks its blocks by counting the blocks that precede
 //            them in the visiting order (a total order, so ranks are a
-//            permutation);
+//            permutation); the workloads are staged in LDS when they fit;
 //   phase 2  wavefront 0 runs the greedy loop: lane l keeps the loads of ranks
-//            l, l+64, ... in registers and its own local minimum; a
-//            wave-level lexicographic min picks the receiving rank;
+//            l, l+64, ... in registers (SLOTS of them, a template parameter
+//            chosen from P) and its own local minimum; a wave-level
+//            lexicographic min picks the receiving rank;
 //   phase 3  per-rank CSR lists in ascending block index by counting, for each
 //            block, the earlier blocks of the same rank.
 #include "common.h"
@@ -17,7 +18,8 @@
 namespace mm {
 
 constexpr int kBalThreads = 1024;
-constexpr int kBalSlots = MMATTN_MAX_RANKS / kWave;   // ranks per lane
+constexpr int kBalSlots = MMATTN_MAX_RANKS / kWave;   // most ranks per lane
+constexpr int kBalLdsW = 8192;                        // workloads staged in LDS up to this many blocks
 
 struct MinKey { uint64_t load; uint32_t rank; };
 
@@ -56,22 +58,37 @@ __device__ __forceinline__ MinKey wave_min(MinKey k) {
     return r;
 }
 
+template <int SLOTS>
 __global__ void __launch_bounds__(kBalThreads)
 balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
                int32_t* __restrict__ rank_of_block, uint64_t* __restrict__ load,
                int32_t* __restrict__ rank_off, int32_t* __restrict__ rank_blocks) {
     __shared__ uint16_t rob[MMATTN_MAX_BLOCKS];
     __shared__ int32_t count[MMATTN_MAX_RANKS + 1];
+    __shared__ uint64_t w_lds[kBalLdsW];
     const int tid = threadIdx.x;
 
     // phase 1: visiting order, kept in rank_blocks until phase 3 overwrites it
     int32_t* order = rank_blocks;
+    const bool staged = nB <= kBalLdsW;                // workgroup-uniform
+    if (staged) {
+        for (int b = tid; b < nB; b += kBalThreads) w_lds[b] = W[b];
+        __syncthreads();
+    }
     for (int b = tid; b < nB; b += kBalThreads) {
-        const uint64_t wb = W[b];
         int pos = 0;
-        for (int c = 0; c < nB; ++c) {
-            const uint64_t wc = W[c];
-            pos += (wc > wb || (wc == wb && c < b)) ? 1 : 0;
+        if (staged) {
+            const uint64_t wb = w_lds[b];
+            for (int c = 0; c < nB; ++c) {
+                const uint64_t wc = w_lds[c];
+                pos += (wc > wb || (wc == wb && c < b)) ? 1 : 0;
+            }
+        } else {
+            const uint64_t wb = W[b];
+            for (int c = 0; c < nB; ++c) {
+                const uint64_t wc = W[c];
+                pos += (wc > wb || (wc == wb && c < b)) ? 1 : 0;
+            }
         }
         order[pos] = b;
     }
@@ -81,9 +98,9 @@ balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
     // phase 2: greedy assignment by wavefront 0
     if (tid < kWave) {
         const int lane = tid;
-        uint64_t mine[kBalSlots];
+        uint64_t mine[SLOTS];
 #pragma unroll
-        for (int s = 0; s < kBalSlots; ++s) mine[s] = 0;
+        for (int s = 0; s < SLOTS; ++s) mine[s] = 0;
         MinKey local;                       // this lane's least-loaded rank
         local.load = lane < P ? 0 : ~0ull;
         local.rank = lane < P ? (uint32_t)lane : 0xFFFFFFFFu;
@@ -97,18 +114,18 @@ balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
                 const uint32_t wlo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)my_w, u);
                 const uint32_t whi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(my_w >> 32), u);
                 const uint64_t w = ((uint64_t)whi << 32) | wlo;
-                const MinKey best = wave_min(local);
-                const uint32_t g = best.rank;
+                // with one rank there is nothing to choose
+                const uint32_t g = P == 1 ? 0u : wave_min(local).rank;
                 if ((int)(g & (kWave - 1)) == lane) {
                     const int slot = g / kWave;
 #pragma unroll
-                    for (int s = 0; s < kBalSlots; ++s)
+                    for (int s = 0; s < SLOTS; ++s)
                         if (s == slot) mine[s] += w;
                     // recompute the lane's local minimum over its ranks
                     local.load = ~0ull;
                     local.rank = 0xFFFFFFFFu;
 #pragma unroll
-                    for (int s = 0; s < kBalSlots; ++s) {
+                    for (int s = 0; s < SLOTS; ++s) {
                         const uint32_t r = (uint32_t)(lane + s * kWave);
                         if ((int)r < P) {
                             MinKey cand{mine[s], r};
@@ -121,7 +138,7 @@ balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
             }
         }
 #pragma unroll
-        for (int s = 0; s < kBalSlots; ++s) {
+        for (int s = 0; s < SLOTS; ++s) {
             const int r = lane + s * kWave;
             if (r < P) load[r] = mine[s];
         }
@@ -145,8 +162,16 @@ balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
 
 int launch_balance(const uint64_t* d_W, int32_t nB, int32_t P, int32_t* d_rank_of_block,
                    uint64_t* d_load, int32_t* d_rank_off, int32_t* d_rank_blocks, hipStream_t st) {
-    hipLaunchKernelGGL(balance_kernel, dim3(1), dim3(kBalThreads), 0, st, d_W, nB, P,
-                       d_rank_of_block, d_load, d_rank_off, d_rank_blocks);
+    // registers per lane for the rank loads: the smallest instantiation that holds P ranks
+    if (P <= kWave)
+        hipLaunchKernelGGL(balance_kernel<1>, dim3(1), dim3(kBalThreads), 0, st, d_W, nB, P,
+                           d_rank_of_block, d_load, d_rank_off, d_rank_blocks);
+    else if (P <= 4 * kWave)
+        hipLaunchKernelGGL(balance_kernel<4>, dim3(1), dim3(kBalThreads), 0, st, d_W, nB, P,
+                           d_rank_of_block, d_load, d_rank_off, d_rank_blocks);
+    else
+        hipLaunchKernelGGL(balance_kernel<kBalSlots>, dim3(1), dim3(kBalThreads), 0, st, d_W, nB, P,
+                           d_rank_of_block, d_load, d_rank_off, d_rank_blocks);
     MM_LAUNCH_CHECK();
     return MMATTN_OK;
 }

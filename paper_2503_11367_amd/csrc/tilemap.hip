@@ -4,11 +4,13 @@
 // the per-block workloads W_b that Alg. 1 balances.
 //
 // Integer ALU work.  One wavefront per tile pair, four k-tiles per workgroup
-// sharing the q-tile's words in LDS.  When both the q-tile and the k-tile are
-// "uniform" (every token carries the same sample/span/modality/attend fields -- the
-// common case inside a text run or a modality span) the count has a closed
-// form in the tile coordinates; otherwise the wave evaluates the predicate for
-// every pair.  Both paths are exact.
+// sharing the q-tile's words in LDS.  A k-tile is a handful of "runs" (maximal
+// stretches of keys with the same sample/span/modality fields: a text run, a
+// modality span); for one query row and one run the number of visible keys has
+// a closed form -- the whole run if it is the row's own span, the keys up to
+// the row's position if the row looks back at that modality in its sample,
+// else none -- so every lane takes a few rows and walks the runs.  Exact for
+// any layout; a tile whose keys all differ degenerates to one run per key.
 //
 // The same kernel serves the attention kernels' private maps: there the q rows
 // are a rank's local rows (positions looked up through its block list) and the
@@ -34,7 +36,6 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
     __shared__ uint32_t q_ss[kTmQChunk];
     __shared__ uint32_t q_att[kTmQChunk];
     __shared__ int64_t q_pos[kTmQChunk];
-    __shared__ int s_flags[4];      // [0] q uniform, [1] q positions contiguous
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
@@ -45,21 +46,7 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
     const bool wave_active = j < nk;
     const int64_t k0 = j * tk;
 
-    // key-side words of this wave's k-tile, tk/64 per lane, and their uniformity
-    uint32_t k_first = 0, k_mod_first = 0;
-    bool k_uniform = true;
-    if (wave_active) {
-        k_first = word_ss(bits[k0]);
-        k_mod_first = word_mod(bits[k0]);
-        bool same = true;
-        for (int64_t k = k0 + lane; k < k0 + tk; k += kWave) {
-            const uint64_t w = bits[k];
-            same &= word_ss(w) == k_first && word_mod(w) == k_mod_first;
-        }
-        k_uniform = __all(same);
-    }
-
-    uint32_t total = 0;
+    uint32_t part = 0;
     for (int64_t c0 = 0; c0 < rows; c0 += kTmQChunk) {
         const int n = (int)min((int64_t)kTmQChunk, rows - c0);
         __syncthreads();
@@ -71,40 +58,36 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
             q_att[threadIdx.x] = word_att(w);
         }
         __syncthreads();
-        // chunk-level uniformity of the q side (fields equal, positions contiguous)
-        bool ok = true;
-        if ((int)threadIdx.x < n)
-            ok = q_ss[threadIdx.x] == q_ss[0] && q_att[threadIdx.x] == q_att[0] &&
-                 q_pos[threadIdx.x] == q_pos[0] + threadIdx.x;
-        const bool q_uniform = __syncthreads_and(ok);
         if (!wave_active) continue;
 
-        if (q_uniform && k_uniform) {
-            const uint32_t ss_q = q_ss[0], at_q = q_att[0];
-            const bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == k_first;
-            const bool back = (ss_q >> 16) == (k_first >> 16) && ((at_q >> k_mod_first) & 1u);
-            if (same_span) {
-                total += (uint32_t)n * (uint32_t)tk;
-            } else if (back) {
-                // pairs with k <= q:  sum_q clamp(q - k0 + 1, 0, tk)
-                uint32_t part = 0;
+        for (int kc = 0; kc < tk; kc += kWave) {
+            // run starts among this chunk's keys: a key whose fields differ from its
+            // predecessor's (the first key of the chunk always starts one)
+            const int n_keys = min(kWave, tk - kc);
+            const uint64_t wk = lane < n_keys ? bits[k0 + kc + lane] : 0;
+            const uint32_t ss_k = word_ss(wk), mod_k = word_mod(wk);
+            const uint32_t ss_p = __shfl_up(ss_k, 1), mod_p = __shfl_up(mod_k, 1);
+            const bool starts = lane < n_keys && (lane == 0 || ss_k != ss_p || mod_k != mod_p);
+            uint64_t m = __ballot(starts);
+            while (m) {
+                const int a = __ffsll((unsigned long long)m) - 1;
+                m &= m - 1;
+                const int b = m ? __ffsll((unsigned long long)m) - 1 : n_keys;   // the run is keys a..b-1
+                const uint32_t ss_r = __shfl(ss_k, a), mod_r = __shfl(mod_k, a);
+                const int64_t first = k0 + kc + a;
+                const int64_t len = b - a;
                 for (int r = lane; r < n; r += kWave) {
-                    int64_t v = q_pos[0] + r - k0 + 1;
-                    part += (uint32_t)max((int64_t)0, min(v, (int64_t)tk));
+                    const uint32_t ss_q = q_ss[r];
+                    const bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_r;
+                    const bool back = (ss_q >> 16) == (ss_r >> 16) && ((q_att[r] >> mod_r) & 1u);
+                    // keys of the run at or before the row's position
+                    const int64_t upto = max((int64_t)0, min(q_pos[r] - first + 1, len));
+                    part += (uint32_t)(same_span ? len : (back ? upto : 0));
                 }
-                total += wave_sum(part);
             }
-        } else {
-            uint32_t part = 0;
-            for (int64_t k = k0 + lane; k < k0 + tk; k += kWave) {
-                const uint64_t wk = bits[k];
-                const uint32_t ss_k = word_ss(wk), mod_k = word_mod(wk);
-                for (int r = 0; r < n; ++r)
-                    part += visible(q_ss[r], q_att[r], q_pos[r], ss_k, mod_k, k) ? 1u : 0u;
-            }
-            total += wave_sum(part);
         }
     }
+    const uint32_t total = wave_sum(part);
     if (wave_active && lane == 0) {
         const uint32_t full = (uint32_t)rows * (uint32_t)tk;
         if (cnt) cnt[i * nk + j] = total;
