@@ -87,6 +87,24 @@ def test_encode_and_tile_map_with_attend_sets(idx):
             check_tile_map(lay, tile[0], tile[1], use_c=False)
 
 
+def test_tile_map_many_short_runs():
+    """Hundreds of 1-3 token spans of alternating modality: nearly every key
+    starts a new run of equal mask fields."""
+    rng = np.random.default_rng(17)
+    spans, deny, pos = [], [], 1
+    while pos + 8 < 1024:
+        n = int(rng.integers(1, 4))
+        spans.append((pos, n, 1 + len(spans) % 3))
+        deny.append(int(rng.integers(0, 2)) << int(rng.integers(0, 4)))
+        pos += n + int(rng.integers(0, 3))
+    lay = wl.Layout(1024, spans, [0, 500, 1024] if not any(s <= 500 < s + n for s, n, _ in spans) else [0, 1024],
+                    deny=deny)
+    assert len(spans) > 250
+    assert np.array_equal(to_np_u64(gpu_bits(lay)), oracle_bits(lay))
+    for tile in ((64, 64), (128, 32), (16, 128)):
+        check_tile_map(lay, tile[0], tile[1], use_c=False)
+
+
 def test_tile_map_block_causal():
     for blk in (96, 128, 50):
         lay = wl.layout_block_causal(1024 if blk != 50 else 1000 + 24, blk)
