@@ -222,10 +222,13 @@ int mmattn_bwd(const void* q_loc, const void* k, const void* v, const uint64_t* 
 /* Measurement aid (not part of the method): while a pair of HIP events is set
  * for a stage, every later mmattn_fwd / mmattn_bwd call records ev_start just
  * before and ev_stop just after that stage's main kernel on the call's stream,
- * so a harness can time one kernel inside a multi-launch call.  Pass nulls to
- * clear.  stage: MMATTN_STAGE_*.  The only process-wide state in the library;
+ * so a harness can time one kernel inside a multi-launch call (FWD and DQ
+ * include the aggregation launch when lists are split; DKV_REDUCE is the
+ * partial-sum launch after the dK/dV kernel, recorded only when it runs).  Pass
+ * nulls to clear.  stage: MMATTN_STAGE_*.  The only process-wide state in the library;
  * not thread-safe.  Returns MMATTN_ERR_SHAPE for an unknown stage. */
-enum { MMATTN_STAGE_FWD = 0, MMATTN_STAGE_DKV = 1, MMATTN_STAGE_DQ = 2, MMATTN_STAGE_COUNT = 3 };
+enum { MMATTN_STAGE_FWD = 0, MMATTN_STAGE_DKV = 1, MMATTN_STAGE_DQ = 2, MMATTN_STAGE_DKV_REDUCE = 3,
+       MMATTN_STAGE_COUNT = 4 };
 int mmattn_stage_events(int stage, void* ev_start, void* ev_stop);
 
 /* Measurement aid (not part of the method): enqueue a kernel that only issues

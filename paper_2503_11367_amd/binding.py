@@ -242,7 +242,7 @@ def bwd(q_loc, k, v, bits, blocks, block: int, o_loc, lse, do_loc, scale: Option
     return dq, dk, dv
 
 
-STAGE_FWD, STAGE_DKV, STAGE_DQ = 0, 1, 2
+STAGE_FWD, STAGE_DKV, STAGE_DQ, STAGE_DKV_REDUCE = 0, 1, 2, 3
 
 
 def mfma_ceiling(iters: int, random_operands: bool, sink: torch.Tensor, stream=None) -> float:

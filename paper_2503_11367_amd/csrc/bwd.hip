@@ -1051,12 +1051,14 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
                        (const ushort_t*)a.v, (const ushort_t*)doh, a.bits, clean, a.block, n_loc,
                        L.n_pad, a.S, a.Hq, a.Hkv, a.scale, scale_log2, ld, pb, L.ch, err,
                        (ushort_t*)dk, (ushort_t*)dv, acc_k, acc_v);
+    stage_end(MMATTN_STAGE_DKV, st);
     if (L.ch.cmax > 1) {
         const int64_t n_elems = a.S * a.Hkv * D;
+        stage_begin(MMATTN_STAGE_DKV_REDUCE, st);
         hipLaunchKernelGGL(dkv_reduce_kernel, dim3((unsigned)((n_elems / 4 + 255) / 256)), dim3(256), 0,
                            st, L.ch.cmax, n_elems, err, acc_k, acc_v, (ushort_t*)dk, (ushort_t*)dv);
+        stage_end(MMATTN_STAGE_DKV_REDUCE, st);
     }
-    stage_end(MMATTN_STAGE_DKV, st);
     const bool pair = rep % 2 == 0;
     stage_begin(MMATTN_STAGE_DQ, st);
     float* dq_part = (float*)(base + L.dq_part);
