@@ -940,11 +940,11 @@ struct BwdLayout {
 static KvChunking kv_chunking(int32_t nk_b, int32_t Hq, int32_t Hkv) {
     const int64_t units = (int64_t)nk_b * Hkv;
     const int32_t rep = Hq / Hkv;
-    int32_t cmax = 1;                  // smallest divisor of rep that yields >= 2048 workgroups, else rep
+    int32_t cmax = 1;                  // smallest divisor of rep that yields >= 1024 workgroups, else rep
     for (int32_t c = 1; c <= rep; ++c) {
         if (rep % c) continue;
         cmax = c;
-        if (units * c >= 2048) break;
+        if (units * c >= 1024) break;
     }
     return KvChunking{cmax, rep / cmax};
 }
