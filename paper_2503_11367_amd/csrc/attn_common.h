@@ -160,6 +160,8 @@ constexpr float kLn2 = 0.6931471805599453f;
 //   klist[nq][nk], kcount[nq]  active k-tiles of each q-tile, ascending;
 //                            entry = k-tile index | (PARTIAL ? kPartialFlag : 0)
 //   qorder[nq]               q-tiles by kcount descending (longest first)
+//   csz[1]                   slice length the list builder suggests for cutting the
+//                            lists into slices (see list_split), from the actual lengths
 constexpr uint32_t kPartialFlag = 0x80000000u;
 
 struct TilePlan {
@@ -169,23 +171,29 @@ struct TilePlan {
     uint32_t* klist;
     int32_t* qorder;
     int32_t* ticket;     // zeroed counter used by the list builder (one per plan)
+    int32_t* csz;
+    int32_t groups;      // workgroups per q-tile (head groups) of the launch the plan is built for
 };
 
-// slices of a q-tile's active k-tile list (forward): cmax slices of csz list entries;
-// cmax == 1 means the list is not split
+// slices of a q-tile's active k-tile list: the launch provides cmax slices per q-tile,
+// so a slice has at least csz list entries; cmax == 1 means the lists are not split
 struct FwdSplit {
     int32_t cmax, csz;
 };
 // Intra-GPU balancing (paper section 3.2.2) for the query-outer kernels: when a share
 // has too few (q-tile, head group) work items to fill the chip, every q-tile's active
-// k-tile list is cut into slices of `csz` tiles that run as separate workgroups and
-// write partial results, aggregated by one more launch.
+// k-tile list is cut into slices that run as separate workgroups and write partial
+// results, aggregated by one more launch.  The host fixes how many slices a q-tile may
+// have (grid size, partial buffers): two to four times (short / long sequences; unused
+// slices are workgroups that exit at once, about 4 us per thousand) what lists of full
+// length would need for about 1024 workgroups.  The slice length itself is chosen on the device from the
+// actual list lengths (slice_length below) and is never shorter than csz.
 inline FwdSplit list_split(int32_t nq, int32_t nk, int32_t Hq, int32_t Hkv) {
     const int hpw = (Hq / Hkv) % 2 == 0 ? 2 : 1;
     const int64_t items = (int64_t)nq * (Hq / hpw);
     int64_t cmax = 1;
     if (items < 512) {
-        cmax = (1024 + items - 1) / items;                    // aim at about 1024 workgroups
+        cmax = (nk >= 512 ? 4 : 2) * ((1024 + items - 1) / items);
         const int64_t most = nk / 2 > 1 ? nk / 2 : 1;         // at least two tiles per slice
         if (cmax > most) cmax = most;
         if (cmax > 64) cmax = 64;
@@ -194,6 +202,27 @@ inline FwdSplit list_split(int32_t nq, int32_t nk, int32_t Hq, int32_t Hkv) {
     sp.csz = (int32_t)((nk + cmax - 1) / cmax);
     sp.cmax = (nk + sp.csz - 1) / sp.csz;                     // no empty trailing slices
     return sp;
+}
+// Slice length from the lists themselves (total entries, longest list, non-empty
+// lists; `groups` workgroups walk every list).
+//   Lists of about equal length: a quarter of one CU's share of all entries, i.e. about
+//   1024 equal slices, which the 256 CUs finish in whole rounds.
+//   Uneven lists: the slices that finish last cost about one slice of time, while every
+//   slice costs a fixed amount of bandwidth for its partial result (worth about 1/32 of
+//   a tile's time across the chip); c + W/(32 c) is smallest at c = sqrt(W/32).
+// At least 8 tiles, at most the whole list.
+__host__ __device__ inline int32_t slice_length(int64_t total, int32_t longest, int32_t lists,
+                                                int32_t groups, int32_t nk) {
+    const int64_t work = total * groups;
+    int64_t c;
+    if ((int64_t)longest * lists * 4 <= total * 5) {          // longest <= 1.25 x mean
+        c = (work + 1023) / 1024;
+    } else {
+        c = (int64_t)__builtin_sqrtf((float)work / 32.0f) + 1;
+    }
+    if (c < 8) c = 8;
+    if (c > nk) c = nk;
+    return (int32_t)c;
 }
 
 // transposed plan for key-outer kernels: for each k-tile the active q-tiles

@@ -680,10 +680,11 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     const int g = h0 / rep;
     const int qt = plan.qorder[tile_rank];
     const int kc_total = plan.kcount[qt];
-    const int nchunk = max(1, (kc_total + split.csz - 1) / split.csz);
+    const int csz = max(*plan.csz, split.csz);
+    const int nchunk = max(1, (kc_total + csz - 1) / csz);
     if (chunk >= nchunk) return;          // workgroup-uniform
-    const int n_active = max(0, min(kc_total - chunk * split.csz, split.csz));
-    const uint32_t* klist = plan.klist + (int64_t)qt * plan.nk + chunk * split.csz;
+    const int n_active = max(0, min(kc_total - chunk * csz, csz));
+    const uint32_t* klist = plan.klist + (int64_t)qt * plan.nk + chunk * csz;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -913,7 +914,8 @@ dq_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int64_t n_pad, i
     const int h = (int)(rh % Hq);
     if (row >= n_loc) return;
     const int kc_total = plan.kcount[row / kDqBM];
-    const int nchunk = max(1, (kc_total + split.csz - 1) / split.csz);
+    const int csz = max(*plan.csz, split.csz);
+    const int nchunk = max(1, (kc_total + csz - 1) / csz);
     if (nchunk == 1) return;              // written by dq_kernel itself
     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int c = 0; c < nchunk; ++c)
@@ -1018,6 +1020,8 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     pa.klist = (uint32_t*)(base + L.klist);
     pa.qorder = (int32_t*)(base + L.qorder);
     pa.ticket = err + 1;
+    pa.csz = err + kFlagInts;
+    pa.groups = a.Hq / (a.Hq / a.Hkv % 2 == 0 ? 2 : 1);
     TilePlanT pb;
     pb.nq = L.nq_b; pb.nk = L.nk_b; pb.tq = kKvBM; pb.tk = kKvBN;
     pb.cls = (uint8_t*)(base + L.cls_b);

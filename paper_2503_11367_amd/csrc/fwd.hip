@@ -90,12 +90,14 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     }
     const int g = h0 / rep;
     const int qt = plan.qorder[tile_rank];
-    // this workgroup's slice of the active list: split.csz entries from chunk * csz on
+    // this workgroup's slice of the active list: csz entries from chunk * csz on; the
+    // length is the list builder's suggestion, but never below what the grid provides for
     const int kc_total = plan.kcount[qt];
-    const int nchunk = max(1, (kc_total + split.csz - 1) / split.csz);
+    const int csz = max(*plan.csz, split.csz);
+    const int nchunk = max(1, (kc_total + csz - 1) / csz);
     if (chunk >= nchunk) return;          // workgroup-uniform
-    const int n_active = max(0, min(kc_total - chunk * split.csz, split.csz));
-    const uint32_t* klist = plan.klist + (int64_t)qt * plan.nk + chunk * split.csz;
+    const int n_active = max(0, min(kc_total - chunk * csz, csz));
+    const uint32_t* klist = plan.klist + (int64_t)qt * plan.nk + chunk * csz;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -486,7 +488,8 @@ fwd_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int32_t Hq, int
     const int h = (int)(rh % Hq);
     if (row >= n_loc) return;
     const int kc_total = plan.kcount[row / kFwdBM];
-    const int nchunk = max(1, (kc_total + split.csz - 1) / split.csz);
+    const int csz = max(*plan.csz, split.csz);
+    const int nchunk = max(1, (kc_total + csz - 1) / csz);
     if (nchunk == 1) return;              // written by the attention kernel itself
     const int64_t rows = (int64_t)plan.nq * kFwdBM;
     float m = -INFINITY;
@@ -587,6 +590,8 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
     plan.klist = (uint32_t*)(base + L.klist);
     plan.qorder = (int32_t*)(base + L.qorder);
     plan.ticket = err + 1;
+    plan.csz = err + kFlagInts;
+    plan.groups = a.Hq / a.Hkv * a.kv_count / (a.Hq / a.Hkv % 2 == 0 ? 2 : 1);
 
     if (!a.plan_ready) {
         int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);

@@ -46,7 +46,7 @@ __global__ void __launch_bounds__(64)
 compact_kernel(const uint8_t* __restrict__ cls, int32_t n_lines, int32_t n_items,
                int64_t line_stride, int64_t item_stride, int32_t* __restrict__ count,
                uint32_t* __restrict__ list, int32_t* __restrict__ order,
-               int32_t* __restrict__ ticket) {
+               int32_t* __restrict__ ticket, int32_t* __restrict__ csz_out, int32_t groups) {
     const int line = blockIdx.x;
     const int lane = threadIdx.x;
     int base = 0;
@@ -74,6 +74,22 @@ compact_kernel(const uint8_t* __restrict__ cls, int32_t n_lines, int32_t n_items
     // the counts go through LDS in chunks, so that the quadratic comparison reads
     // (all lanes the same address: a broadcast) never go back to memory
     __shared__ int32_t cnt_s[kCompactChunk];
+    if (csz_out) {                             // suggested slice length for cutting the lists
+        int64_t total = 0;
+        int longest = 0, lists = 0;
+        for (int a = lane; a < n_lines; a += kWave) {
+            const int c = __hip_atomic_load(&count[a], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            total += c;
+            longest = max(longest, c);
+            lists += c > 0 ? 1 : 0;
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            total += __shfl_xor(total, off);
+            longest = max(longest, __shfl_xor(longest, off));
+            lists += __shfl_xor(lists, off);
+        }
+        if (lane == 0) *csz_out = slice_length(total, longest, lists, groups, n_items);
+    }
     for (int a0 = 0; a0 < n_lines; a0 += kWave) {
         const int a = a0 + lane;
         const int ca = a < n_lines
@@ -115,14 +131,14 @@ int launch_zero_kv(void* dk, void* dv, size_t bytes_each, hipStream_t st) {
 
 int launch_compact_rows(const TilePlan& p, hipStream_t st) {
     hipLaunchKernelGGL(compact_kernel, dim3(p.nq), dim3(64), 0, st, p.cls, p.nq, p.nk,
-                       (int64_t)p.nk, (int64_t)1, p.kcount, p.klist, p.qorder, p.ticket);
+                       (int64_t)p.nk, (int64_t)1, p.kcount, p.klist, p.qorder, p.ticket, p.csz, p.groups);
     MM_LAUNCH_CHECK();
     return MMATTN_OK;
 }
 
 int launch_compact_cols(const TilePlanT& p, hipStream_t st) {
     hipLaunchKernelGGL(compact_kernel, dim3(p.nk), dim3(64), 0, st, p.cls, p.nk, p.nq,
-                       (int64_t)1, (int64_t)p.nk, p.qcount, p.qlist, p.korder, p.ticket);
+                       (int64_t)1, (int64_t)p.nk, p.qcount, p.qlist, p.korder, p.ticket, (int32_t*)nullptr, 1);
     MM_LAUNCH_CHECK();
     return MMATTN_OK;
 }
