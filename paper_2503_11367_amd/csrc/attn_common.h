@@ -170,7 +170,6 @@ struct TilePlan {
     int32_t* kcount;
     uint32_t* klist;
     int32_t* qorder;
-    int32_t* ticket;     // zeroed counter used by the list builder (one per plan)
     int32_t* csz;
     int32_t groups;      // workgroups per q-tile (head groups) of the launch the plan is built for
 };
@@ -232,11 +231,10 @@ struct TilePlanT {
     int32_t* qcount;     // [nk]
     uint32_t* qlist;     // [nk][nq]
     int32_t* korder;     // [nk] by qcount descending
-    int32_t* ticket;
 };
 
-// int32 words cleared by launch_validate_blocks at `err`: the error flag, then one
-// ticket per tile plan of the call
+// int32 words cleared by launch_validate_blocks at `err`: the error flag and spare words;
+// the word after them holds the slice length chosen by the list builder
 constexpr int kFlagInts = 4;
 int launch_compact_rows(const TilePlan& p, hipStream_t st);
 int launch_compact_cols(const TilePlanT& p, hipStream_t st);

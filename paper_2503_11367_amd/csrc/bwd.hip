@@ -1019,7 +1019,6 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     pa.kcount = (int32_t*)(base + L.kcount);
     pa.klist = (uint32_t*)(base + L.klist);
     pa.qorder = (int32_t*)(base + L.qorder);
-    pa.ticket = err + 1;
     pa.csz = err + kFlagInts;
     pa.groups = a.Hq / (a.Hq / a.Hkv % 2 == 0 ? 2 : 1);
     TilePlanT pb;
@@ -1028,7 +1027,6 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     pb.qcount = (int32_t*)(base + L.qcount);
     pb.qlist = (uint32_t*)(base + L.qlist);
     pb.korder = (int32_t*)(base + L.korder);
-    pb.ticket = err + 2;
 
     int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
     if (rc) return rc;

@@ -589,7 +589,6 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
     plan.kcount = (int32_t*)(base + L.kcount);
     plan.klist = (uint32_t*)(base + L.klist);
     plan.qorder = (int32_t*)(base + L.qorder);
-    plan.ticket = err + 1;
     plan.csz = err + kFlagInts;
     plan.groups = a.Hq / a.Hkv * a.kv_count / (a.Hq / a.Hkv % 2 == 0 ? 2 : 1);
 

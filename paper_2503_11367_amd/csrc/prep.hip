@@ -1,6 +1,5 @@
-// Preparation kernels for the attention passes: block-list sanitising,
-// permuted transposes of operand tensors, and compaction of the tile classes
-// into per-tile work lists (so that fully masked tiles are never visited --
+// Preparation kernels for the attention passes: block-list sanitising and
+// compaction of the tile classes into per-tile work lists (so that fully masked tiles are never visited --
 // the block skipping of paper section 3.2.1) ordered longest first (the
 // intra-GPU balance concern of section 3.2.2: long query blocks start early so
 // that the tail of the launch is short).
@@ -9,8 +8,8 @@
 namespace mm {
 
 // ---- block list ------------------------------------------------------------
-// One workgroup: clears the error flag and the plan tickets that follow it (the
-// flag block is kFlagInts int32 wide), then copies the block list, replacing
+// One workgroup: clears the error flag (the flag block is kFlagInts int32 wide),
+// then copies the block list, replacing
 // out-of-range entries by 0 and raising the flag.
 __global__ void __launch_bounds__(256)
 validate_blocks_kernel(const int32_t* __restrict__ blocks, int32_t n_blocks, int64_t n_seq_blocks,
@@ -38,15 +37,11 @@ int launch_validate_blocks(const int32_t* blocks, int32_t n_blocks, int64_t n_se
 
 // ---- work lists ---------------------------------------------------------------
 // One wavefront per line (a q-tile's row of classes, or a k-tile's column) compacts
-// the line's non-empty tiles.  The wavefront that finishes last (a ticket counter,
-// zeroed by validate_blocks_kernel) then ranks the lines: order[rank] = line, by
-// (count descending, line ascending), so that heavy lines are scheduled first.
-constexpr int kCompactChunk = 2048;
+// the line's non-empty tiles.
 __global__ void __launch_bounds__(64)
 compact_kernel(const uint8_t* __restrict__ cls, int32_t n_lines, int32_t n_items,
                int64_t line_stride, int64_t item_stride, int32_t* __restrict__ count,
-               uint32_t* __restrict__ list, int32_t* __restrict__ order,
-               int32_t* __restrict__ ticket, int32_t* __restrict__ csz_out, int32_t groups) {
+               uint32_t* __restrict__ list) {
     const int line = blockIdx.x;
     const int lane = threadIdx.x;
     int base = 0;
@@ -63,51 +58,71 @@ compact_kernel(const uint8_t* __restrict__ cls, int32_t n_lines, int32_t n_items
         }
         base += __popcll(m);
     }
-    int last = 0;
-    if (lane == 0) {
-        __hip_atomic_store(&count[line], base, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();                   // the count is visible before the ticket is taken
-        last = atomicAdd(ticket, 1) == n_lines - 1;
+    if (lane == 0) count[line] = base;
+}
+
+// Ranks the lines: order[rank] = line, by (count descending, line ascending), so that
+// heavy lines are scheduled first.  One thread per line; every thread counts the lines
+// that precede its own, reading the counts through LDS in chunks (all lanes the same
+// address: a broadcast).  Workgroup 0 also derives the slice length for cutting the
+// lists (csz_out, may be null) from the total, the longest and the non-empty lists.
+constexpr int kRankThreads = 256;
+constexpr int kRankChunk = 2048;
+__global__ void __launch_bounds__(kRankThreads)
+rank_lines_kernel(const int32_t* __restrict__ count, int32_t n_lines, int32_t n_items,
+                  int32_t* __restrict__ order, int32_t* __restrict__ csz_out, int32_t groups) {
+    __shared__ int32_t cnt_s[kRankChunk];
+    const int tid = threadIdx.x;
+    const int a = blockIdx.x * kRankThreads + tid;
+    const int ca = a < n_lines ? count[a] : 0;
+    int pos = 0;
+    for (int b0 = 0; b0 < n_lines; b0 += kRankChunk) {
+        const int nb = min(kRankChunk, n_lines - b0);
+        __syncthreads();
+        for (int b = tid; b < nb; b += kRankThreads) cnt_s[b] = count[b0 + b];
+        __syncthreads();
+        for (int b = 0; b < nb; ++b) {
+            const int cb = cnt_s[b];
+            pos += (cb > ca || (cb == ca && b0 + b < a)) ? 1 : 0;
+        }
     }
-    if (!__shfl(last, 0)) return;
-    __threadfence();
-    // the counts go through LDS in chunks, so that the quadratic comparison reads
-    // (all lanes the same address: a broadcast) never go back to memory
-    __shared__ int32_t cnt_s[kCompactChunk];
-    if (csz_out) {                             // suggested slice length for cutting the lists
+    if (a < n_lines) order[pos] = a;
+
+    if (csz_out && blockIdx.x == 0) {          // workgroup-uniform
+        __shared__ int64_t tot_s[kRankThreads];
+        __shared__ int32_t max_s[kRankThreads], num_s[kRankThreads];
         int64_t total = 0;
         int longest = 0, lists = 0;
-        for (int a = lane; a < n_lines; a += kWave) {
-            const int c = __hip_atomic_load(&count[a], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int b = tid; b < n_lines; b += kRankThreads) {
+            const int c = count[b];
             total += c;
             longest = max(longest, c);
             lists += c > 0 ? 1 : 0;
         }
-        for (int off = 32; off > 0; off >>= 1) {
-            total += __shfl_xor(total, off);
-            longest = max(longest, __shfl_xor(longest, off));
-            lists += __shfl_xor(lists, off);
-        }
-        if (lane == 0) *csz_out = slice_length(total, longest, lists, groups, n_items);
-    }
-    for (int a0 = 0; a0 < n_lines; a0 += kWave) {
-        const int a = a0 + lane;
-        const int ca = a < n_lines
-                           ? __hip_atomic_load(&count[a], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-        int pos = 0;
-        for (int b0 = 0; b0 < n_lines; b0 += kCompactChunk) {
-            const int nb = min(kCompactChunk, n_lines - b0);
-            __syncthreads();                 // single-wave workgroup: orders the LDS accesses
-            for (int b = lane; b < nb; b += kWave)
-                cnt_s[b] = __hip_atomic_load(&count[b0 + b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __syncthreads();
-            for (int b = 0; b < nb; ++b) {
-                const int cb = cnt_s[b];
-                pos += (cb > ca || (cb == ca && b0 + b < a)) ? 1 : 0;
+        tot_s[tid] = total; max_s[tid] = longest; num_s[tid] = lists;
+        __syncthreads();
+        for (int off = kRankThreads / 2; off > 0; off >>= 1) {
+            if (tid < off) {
+                tot_s[tid] += tot_s[tid + off];
+                max_s[tid] = max(max_s[tid], max_s[tid + off]);
+                num_s[tid] += num_s[tid + off];
             }
+            __syncthreads();
         }
-        if (a < n_lines) order[pos] = a;
+        if (tid == 0) *csz_out = slice_length(tot_s[0], max_s[0], num_s[0], groups, n_items);
     }
+}
+
+static int launch_lists(const uint8_t* cls, int32_t n_lines, int32_t n_items, int64_t line_stride,
+                        int64_t item_stride, int32_t* count, uint32_t* list, int32_t* order,
+                        int32_t* csz_out, int32_t groups, hipStream_t st) {
+    hipLaunchKernelGGL(compact_kernel, dim3(n_lines), dim3(64), 0, st, cls, n_lines, n_items,
+                       line_stride, item_stride, count, list);
+    hipLaunchKernelGGL(rank_lines_kernel, dim3((n_lines + kRankThreads - 1) / kRankThreads),
+                       dim3(kRankThreads), 0, st, (const int32_t*)count, n_lines, n_items, order,
+                       csz_out, groups);
+    MM_LAUNCH_CHECK();
+    return MMATTN_OK;
 }
 
 // zero fill of two equally sized buffers (a kernel rather than a memset node, so
@@ -130,17 +145,13 @@ int launch_zero_kv(void* dk, void* dv, size_t bytes_each, hipStream_t st) {
 }
 
 int launch_compact_rows(const TilePlan& p, hipStream_t st) {
-    hipLaunchKernelGGL(compact_kernel, dim3(p.nq), dim3(64), 0, st, p.cls, p.nq, p.nk,
-                       (int64_t)p.nk, (int64_t)1, p.kcount, p.klist, p.qorder, p.ticket, p.csz, p.groups);
-    MM_LAUNCH_CHECK();
-    return MMATTN_OK;
+    return launch_lists(p.cls, p.nq, p.nk, (int64_t)p.nk, (int64_t)1, p.kcount, p.klist, p.qorder,
+                        p.csz, p.groups, st);
 }
 
 int launch_compact_cols(const TilePlanT& p, hipStream_t st) {
-    hipLaunchKernelGGL(compact_kernel, dim3(p.nk), dim3(64), 0, st, p.cls, p.nk, p.nq,
-                       (int64_t)1, (int64_t)p.nk, p.qcount, p.qlist, p.korder, p.ticket, (int32_t*)nullptr, 1);
-    MM_LAUNCH_CHECK();
-    return MMATTN_OK;
+    return launch_lists(p.cls, p.nk, p.nq, (int64_t)1, (int64_t)p.nk, p.qcount, p.qlist, p.korder,
+                        nullptr, 1, st);
 }
 
 }  // namespace mm

@@ -28,10 +28,12 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
     return v;
 }
 
+// kpw: k-tiles per wavefront (each wavefront walks kpw consecutive k-tiles, so that on
+// large maps the q-tile's words are staged once for 4*kpw tile pairs)
 __global__ void __launch_bounds__(kTmThreads)
 tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
                 const int32_t* __restrict__ blocks, int32_t block, int64_t n_rows,
-                int32_t tq, int32_t tk, int32_t nk,
+                int32_t tq, int32_t tk, int32_t nk, int32_t kpw,
                 uint8_t* __restrict__ cls, uint32_t* __restrict__ cnt) {
     __shared__ uint32_t q_ss[kTmQChunk];
     __shared__ uint32_t q_att[kTmQChunk];
@@ -40,15 +42,10 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int64_t i = blockIdx.y;
-    const int64_t j = (int64_t)blockIdx.x * kTmWaves + wave;
     const int64_t r0 = i * tq;
     const int64_t rows = min((int64_t)tq, n_rows - r0);      // ragged last q-tile
-    const bool wave_active = j < nk;
-    const int64_t k0 = j * tk;
-
-    uint32_t part = 0;
-    for (int64_t c0 = 0; c0 < rows; c0 += kTmQChunk) {
-        const int n = (int)min((int64_t)kTmQChunk, rows - c0);
+    // words of the q rows c0 .. c0+n-1 of the tile into LDS (all threads; two barriers)
+    auto stage_rows = [&](int64_t c0, int n) {
         __syncthreads();
         if ((int)threadIdx.x < n) {
             int64_t p = row_pos(blocks, block, r0 + c0 + threadIdx.x);
@@ -58,42 +55,55 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
             q_att[threadIdx.x] = word_att(w);
         }
         __syncthreads();
-        if (!wave_active) continue;
+    };
+    const bool single = rows <= kTmQChunk;                   // workgroup-uniform
+    if (single) stage_rows(0, (int)rows);
 
-        for (int kc = 0; kc < tk; kc += kWave) {
-            // run starts among this chunk's keys: a key whose fields differ from its
-            // predecessor's (the first key of the chunk always starts one)
-            const int n_keys = min(kWave, tk - kc);
-            const uint64_t wk = lane < n_keys ? bits[k0 + kc + lane] : 0;
-            const uint32_t ss_k = word_ss(wk), mod_k = word_mod(wk);
-            const uint32_t ss_p = __shfl_up(ss_k, 1), mod_p = __shfl_up(mod_k, 1);
-            const bool starts = lane < n_keys && (lane == 0 || ss_k != ss_p || mod_k != mod_p);
-            uint64_t m = __ballot(starts);
-            while (m) {
-                const int a = __ffsll((unsigned long long)m) - 1;
-                m &= m - 1;
-                const int b = m ? __ffsll((unsigned long long)m) - 1 : n_keys;   // the run is keys a..b-1
-                const uint32_t ss_r = __shfl(ss_k, a), mod_r = __shfl(mod_k, a);
-                const int64_t first = k0 + kc + a;
-                const int64_t len = b - a;
-                for (int r = lane; r < n; r += kWave) {
-                    const uint32_t ss_q = q_ss[r];
-                    const bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_r;
-                    const bool back = (ss_q >> 16) == (ss_r >> 16) && ((q_att[r] >> mod_r) & 1u);
-                    // keys of the run at or before the row's position
-                    const int64_t upto = max((int64_t)0, min(q_pos[r] - first + 1, len));
-                    part += (uint32_t)(same_span ? len : (back ? upto : 0));
+    for (int jj = 0; jj < kpw; ++jj) {
+        const int64_t j = ((int64_t)blockIdx.x * kTmWaves + wave) * kpw + jj;
+        const bool wave_active = j < nk;
+        const int64_t k0 = j * tk;
+        uint32_t part = 0;
+        for (int64_t c0 = 0; c0 < rows; c0 += kTmQChunk) {
+            const int n = (int)min((int64_t)kTmQChunk, rows - c0);
+            if (!single) stage_rows(c0, n);
+            if (!wave_active) continue;
+
+            for (int kc = 0; kc < tk; kc += kWave) {
+                // run starts among this chunk's keys: a key whose fields differ from its
+                // predecessor's (the first key of the chunk always starts one)
+                const int n_keys = min(kWave, tk - kc);
+                const uint64_t wk = lane < n_keys ? bits[k0 + kc + lane] : 0;
+                const uint32_t ss_k = word_ss(wk), mod_k = word_mod(wk);
+                const uint32_t ss_p = __shfl_up(ss_k, 1), mod_p = __shfl_up(mod_k, 1);
+                const bool starts = lane < n_keys && (lane == 0 || ss_k != ss_p || mod_k != mod_p);
+                uint64_t m = __ballot(starts);
+                while (m) {
+                    const int a = __ffsll((unsigned long long)m) - 1;
+                    m &= m - 1;
+                    const int b = m ? __ffsll((unsigned long long)m) - 1 : n_keys;   // the run is keys a..b-1
+                    const uint32_t ss_r = __shfl(ss_k, a), mod_r = __shfl(mod_k, a);
+                    const int64_t first = k0 + kc + a;
+                    const int64_t len = b - a;
+                    for (int r = lane; r < n; r += kWave) {
+                        const uint32_t ss_q = q_ss[r];
+                        const bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_r;
+                        const bool back = (ss_q >> 16) == (ss_r >> 16) && ((q_att[r] >> mod_r) & 1u);
+                        // keys of the run at or before the row's position
+                        const int64_t upto = max((int64_t)0, min(q_pos[r] - first + 1, len));
+                        part += (uint32_t)(same_span ? len : (back ? upto : 0));
+                    }
                 }
             }
         }
-    }
-    const uint32_t total = wave_sum(part);
-    if (wave_active && lane == 0) {
-        const uint32_t full = (uint32_t)rows * (uint32_t)tk;
-        if (cnt) cnt[i * nk + j] = total;
-        if (cls)
-            cls[i * nk + j] = total == 0 ? MMATTN_TILE_EMPTY
-                              : (total == full ? MMATTN_TILE_FULL : MMATTN_TILE_PARTIAL);
+        const uint32_t total = wave_sum(part);
+        if (wave_active && lane == 0) {
+            const uint32_t full = (uint32_t)rows * (uint32_t)tk;
+            if (cnt) cnt[i * nk + j] = total;
+            if (cls)
+                cls[i * nk + j] = total == 0 ? MMATTN_TILE_EMPTY
+                                  : (total == full ? MMATTN_TILE_FULL : MMATTN_TILE_PARTIAL);
+        }
     }
 }
 
@@ -118,9 +128,14 @@ int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, 
     const int64_t nq = (n_rows + tq - 1) / tq;
     const int32_t nk = (int32_t)(S / tk);
     if (nq == 0) return MMATTN_OK;
-    dim3 grid((unsigned)((nk + kTmWaves - 1) / kTmWaves), (unsigned)nq);
+    // k-tiles per wavefront: one while the map has few tile pairs, up to 8 once there are
+    // enough pairs for a thousand workgroups anyway
+    const int64_t kpw64 = nq * nk / (kTmWaves * 1024);
+    const int32_t kpw = (int32_t)std::max<int64_t>(1, std::min<int64_t>(8, kpw64));
+    const int32_t per_wg = kTmWaves * kpw;
+    dim3 grid((unsigned)((nk + per_wg - 1) / per_wg), (unsigned)nq);
     hipLaunchKernelGGL(tile_map_kernel, grid, dim3(kTmThreads), 0, st, d_bits, S, d_blocks, block,
-                       n_rows, tq, tk, nk, d_cls, d_cnt);
+                       n_rows, tq, tk, nk, kpw, d_cls, d_cnt);
     MM_LAUNCH_CHECK();
     if (d_rowpairs) {
         hipLaunchKernelGGL(row_pairs_kernel, dim3((unsigned)nq), dim3(256), 0, st, d_cnt, nk,
