@@ -7,10 +7,12 @@
 //   phase 1  every thread ranks its blocks by counting the blocks that precede
 //            them in the visiting order (a total order, so ranks are a
 //            permutation); the workloads are staged in LDS when they fit;
-//   phase 2  wavefront 0 runs the greedy loop: lane l keeps the loads of ranks
-//            l, l+64, ... in registers (SLOTS of them, a template parameter
-//            chosen from P) and its own local minimum; a wave-level
-//            lexicographic min picks the receiving rank;
+//   phase 2  wavefront 0 runs the greedy loop.  Up to 64 ranks (SLOTS == 1): the
+//            lanes hold the ranks sorted by (load, rank), the block goes to lane
+//            0's rank and one ballot re-inserts its grown key.  More ranks: lane
+//            l keeps the loads of ranks l, l+64, ... in registers (SLOTS of
+//            them, a template parameter chosen from P) and its own local
+//            minimum; a wave-level lexicographic min picks the receiving rank;
 //   phase 3  per-rank CSR lists in ascending block index by counting, for each
 //            block, the earlier blocks of the same rank.
 #include "common.h"
@@ -58,14 +60,20 @@ __device__ __forceinline__ MinKey wave_min(MinKey k) {
     return r;
 }
 
+// the value held by the next higher lane (wavefront shift left by one; lane 63 keeps
+// its own, which the caller never uses)
+__device__ __forceinline__ uint32_t lane_above(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x130 /* wave_shl:1 */, 0xf, 0xf, false);
+}
+
 template <int SLOTS>
 __global__ void __launch_bounds__(kBalThreads)
 balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
                int32_t* __restrict__ rank_of_block, uint64_t* __restrict__ load,
                int32_t* __restrict__ rank_off, int32_t* __restrict__ rank_blocks) {
-    __shared__ uint16_t rob[MMATTN_MAX_BLOCKS];
+    __shared__ __attribute__((aligned(16))) uint16_t rob[MMATTN_MAX_BLOCKS];
     __shared__ int32_t count[MMATTN_MAX_RANKS + 1];
-    __shared__ uint64_t w_lds[kBalLdsW];
+    __shared__ __attribute__((aligned(16))) uint64_t w_lds[kBalLdsW];
     const int tid = threadIdx.x;
 
     // phase 1: visiting order, kept in rank_blocks until phase 3 overwrites it
@@ -75,13 +83,23 @@ balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
         for (int b = tid; b < nB; b += kBalThreads) w_lds[b] = W[b];
         __syncthreads();
     }
+    const uint64_t* Wp = staged ? w_lds : W;           // phase 2 reads the workloads through this
     for (int b = tid; b < nB; b += kBalThreads) {
         int pos = 0;
         if (staged) {
             const uint64_t wb = w_lds[b];
-            for (int c = 0; c < nB; ++c) {
-                const uint64_t wc = w_lds[c];
-                pos += (wc > wb || (wc == wb && c < b)) ? 1 : 0;
+            typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
+            const u64x2* w2 = (const u64x2*)w_lds;     // two workloads per LDS read
+            const int pairs = nB >> 1;
+#pragma unroll 4
+            for (int c2 = 0; c2 < pairs; ++c2) {
+                const u64x2 wc = w2[c2];
+                pos += (wc.x > wb || (wc.x == wb && 2 * c2 < b)) ? 1 : 0;
+                pos += (wc.y > wb || (wc.y == wb && 2 * c2 + 1 < b)) ? 1 : 0;
+            }
+            if (nB & 1) {
+                const uint64_t wc = w_lds[nB - 1];
+                pos += (wc > wb || (wc == wb && nB - 1 < b)) ? 1 : 0;
             }
         } else {
             const uint64_t wb = W[b];
@@ -96,7 +114,41 @@ balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
     __syncthreads();
 
     // phase 2: greedy assignment by wavefront 0
-    if (tid < kWave) {
+    if (SLOTS == 1 && tid < kWave) {
+        // At most one rank per lane: the lanes hold the ranks SORTED by (load, rank), lane 0
+        // the least loaded.  A block goes to lane 0's rank; its new key is re-inserted at
+        // the position given by how many other keys are smaller (one ballot), the keys
+        // before that position move down one lane.  All per-block decisions are scalar.
+        const int lane = tid;
+        uint32_t lo = lane < P ? 0u : 0xFFFFFFFFu, hi = lo;          // load; lanes >= P: +inf
+        uint32_t rk = lane < P ? (uint32_t)lane : 0xFFFFFFFFu;
+        for (int t0 = 0; t0 < nB; t0 += kWave) {
+            const int t = t0 + lane;
+            const int32_t my_b = t < nB ? order[t] : 0;
+            const uint64_t my_w = t < nB ? Wp[my_b] : 0;
+            const int n = min(kWave, nB - t0);
+            for (int u = 0; u < n; ++u) {
+                const int32_t b = __builtin_amdgcn_readlane(my_b, u);
+                const uint64_t w = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(my_w >> 32), u) << 32) |
+                                   (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)my_w, u);
+                const uint32_t g = (uint32_t)__builtin_amdgcn_readlane((int)rk, 0);
+                const uint64_t grown = (((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, 0) << 32) |
+                                        (uint32_t)__builtin_amdgcn_readlane((int)lo, 0)) + w;
+                const uint64_t mine = ((uint64_t)hi << 32) | lo;
+                const bool less = lane > 0 && (mine < grown || (mine == grown && rk < g));
+                const int at = __popcll(__ballot(less));              // new lane of rank g
+                // lanes below `at` take their upper neighbour's key, lane `at` the grown one
+                const uint32_t lo_up = lane_above(lo), hi_up = lane_above(hi), rk_up = lane_above(rk);
+                if (lane < at) { lo = lo_up; hi = hi_up; rk = rk_up; }
+                else if (lane == at) { lo = (uint32_t)grown; hi = (uint32_t)(grown >> 32); rk = g; }
+                if (lane == 0) {
+                    rank_of_block[b] = (int32_t)g;
+                    rob[b] = (uint16_t)g;
+                }
+            }
+        }
+        if (lane < P) load[rk] = ((uint64_t)hi << 32) | lo;
+    } else if (tid < kWave) {
         const int lane = tid;
         uint64_t mine[SLOTS];
 #pragma unroll
@@ -107,15 +159,14 @@ balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
         for (int t0 = 0; t0 < nB; t0 += kWave) {
             const int t = t0 + lane;
             const int32_t my_b = t < nB ? order[t] : 0;
-            const uint64_t my_w = t < nB ? W[my_b] : 0;
+            const uint64_t my_w = t < nB ? Wp[my_b] : 0;
             const int n = min(kWave, nB - t0);
             for (int u = 0; u < n; ++u) {
                 const int32_t b = __builtin_amdgcn_readlane(my_b, u);
                 const uint32_t wlo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)my_w, u);
                 const uint32_t whi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(my_w >> 32), u);
                 const uint64_t w = ((uint64_t)whi << 32) | wlo;
-                // with one rank there is nothing to choose
-                const uint32_t g = P == 1 ? 0u : wave_min(local).rank;
+                const uint32_t g = wave_min(local).rank;
                 if ((int)(g & (kWave - 1)) == lane) {
                     const int slot = g / kWave;
 #pragma unroll
@@ -155,7 +206,16 @@ balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
     for (int b = tid; b < nB; b += kBalThreads) {
         const uint16_t g = rob[b];
         int before = 0;
-        for (int c = 0; c < b; ++c) before += rob[c] == g ? 1 : 0;
+        typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+        const u16x8* rob8 = (const u16x8*)rob;         // eight ranks per LDS read
+        const int octets = b >> 3;
+#pragma unroll 2
+        for (int c8 = 0; c8 < octets; ++c8) {
+            const u16x8 r = rob8[c8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) before += r[u] == g ? 1 : 0;
+        }
+        for (int c = octets << 3; c < b; ++c) before += rob[c] == g ? 1 : 0;
         rank_blocks[count[g] + before] = b;
     }
 }

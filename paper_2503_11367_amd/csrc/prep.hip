@@ -71,7 +71,7 @@ constexpr int kRankChunk = 2048;
 __global__ void __launch_bounds__(kRankThreads)
 rank_lines_kernel(const int32_t* __restrict__ count, int32_t n_lines, int32_t n_items,
                   int32_t* __restrict__ order, int32_t* __restrict__ csz_out, int32_t groups) {
-    __shared__ int32_t cnt_s[kRankChunk];
+    __shared__ __attribute__((aligned(16))) int32_t cnt_s[kRankChunk];
     const int tid = threadIdx.x;
     const int a = blockIdx.x * kRankThreads + tid;
     const int ca = a < n_lines ? count[a] : 0;
@@ -79,11 +79,15 @@ rank_lines_kernel(const int32_t* __restrict__ count, int32_t n_lines, int32_t n_
     for (int b0 = 0; b0 < n_lines; b0 += kRankChunk) {
         const int nb = min(kRankChunk, n_lines - b0);
         __syncthreads();
-        for (int b = tid; b < nb; b += kRankThreads) cnt_s[b] = count[b0 + b];
+        for (int b = tid; b < ((nb + 3) & ~3); b += kRankThreads) cnt_s[b] = b < nb ? count[b0 + b] : -1;
         __syncthreads();
-        for (int b = 0; b < nb; ++b) {
-            const int cb = cnt_s[b];
-            pos += (cb > ca || (cb == ca && b0 + b < a)) ? 1 : 0;
+        // four counts per LDS read; the tail of the last quad is padded with -1 (never ahead)
+        for (int b = 0; b < nb; b += 4) {
+            const int4 cb = *(const int4*)&cnt_s[b];
+            pos += (cb.x > ca || (cb.x == ca && b0 + b < a)) ? 1 : 0;
+            pos += (cb.y > ca || (cb.y == ca && b0 + b + 1 < a)) ? 1 : 0;
+            pos += (cb.z > ca || (cb.z == ca && b0 + b + 2 < a)) ? 1 : 0;
+            pos += (cb.w > ca || (cb.w == ca && b0 + b + 3 < a)) ? 1 : 0;
         }
     }
     if (a < n_lines) order[pos] = a;
