@@ -114,7 +114,17 @@ balance_kernel(const uint64_t* __restrict__ W, int32_t nB, int32_t P,
     __syncthreads();
 
     // phase 2: greedy assignment by wavefront 0
-    if (SLOTS == 1 && tid < kWave) {
+    if (SLOTS == 1 && P == 1 && tid < kWave) {
+        // a single rank receives every block
+        uint64_t sum = 0;
+        for (int b = tid; b < nB; b += kWave) {
+            rank_of_block[b] = 0;
+            rob[b] = 0;
+            sum += Wp[b];
+        }
+        for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+        if (tid == 0) load[0] = sum;
+    } else if (SLOTS == 1 && tid < kWave) {
         // At most one rank per lane: the lanes hold the ranks SORTED by (load, rank), lane 0
         // the least loaded.  A block goes to lane 0's rank; its new key is re-inserted at
         // the position given by how many other keys are smaller (one ballot), the keys
