@@ -186,7 +186,8 @@ int mmattn_fwd_heads(const void* q_loc, const void* k, const void* v, const uint
  * windows overlap the attention of the earlier ones.
  *   k_src, v_src      device [S,Hkv,D], read on copy_stream once everything
  *                     enqueued on `stream` before this call has completed
- *   k_stage, v_stage  device [S,Hkv,D], overwritten with k_src, v_src
+ *   k_stage, v_stage  device [S,Hkv,D], overwritten with k_src, v_src (may be the
+ *                     same buffers as k_src, v_src: then nothing is copied)
  *   copy_stream       a HIP stream other than `stream`, default priority
  *   ws                mmattn_workspace_size(MMATTN_OP_FWD_HEADS, ...) bytes
  * When the call returns, all work has been enqueued; `stream` has been made to

@@ -186,10 +186,12 @@ int mmattn_fwd_staged(const void* q_loc, const void* k_src, const void* v_src, v
         ok(hipStreamWaitEvent(cs, ready, 0));
     for (int i = 0; i < n_stage && rc == MMATTN_OK; ++i) {
         const size_t off = (size_t)i * width;
-        ok(hipMemcpy2DAsync((char*)k_stage + off, pitch, (const char*)k_src + off, pitch, width,
-                            (size_t)S, hipMemcpyDeviceToDevice, cs));
-        ok(hipMemcpy2DAsync((char*)v_stage + off, pitch, (const char*)v_src + off, pitch, width,
-                            (size_t)S, hipMemcpyDeviceToDevice, cs));
+        if (k_src != k_stage)                   // already in place: nothing to move
+            ok(hipMemcpy2DAsync((char*)k_stage + off, pitch, (const char*)k_src + off, pitch, width,
+                                (size_t)S, hipMemcpyDeviceToDevice, cs));
+        if (v_src != v_stage)
+            ok(hipMemcpy2DAsync((char*)v_stage + off, pitch, (const char*)v_src + off, pitch, width,
+                                (size_t)S, hipMemcpyDeviceToDevice, cs));
         if (ok(hipEventCreateWithFlags(&arrived[i], hipEventDisableTiming)))
             ok(hipEventRecord(arrived[i], cs));
     }

@@ -76,6 +76,21 @@ def test_staged_entry_point(Hq, Hkv, D, hps):
         ks.fill_(float("nan")); vs.fill_(float("nan"))
 
 
+def test_staged_in_place():
+    """k_stage / v_stage may be the source buffers themselves: no copies, same result."""
+    lay = wl.layout_random(151, S=512, n_samples=1, max_spans=3)
+    blocks = [1, 6, 3]
+    t = make_tensors(411, len(blocks) * 64, lay.S, 8, 4, 128)
+    bits = gpu_bits(lay)
+    bl = torch.tensor(blocks, dtype=torch.int32, device=DEV)
+    k0, v0 = t["k"].clone(), t["v"].clone()
+    o, lse = mb.fwd_staged(t["q"], t["k"], t["v"], t["k"], t["v"], bits, bl, 64, 2, torch.cuda.Stream())
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle_fwd(lay, blocks, 64, t, 8, 4)
+    check(o, lse, o_ref, lse_ref)
+    assert torch.equal(t["k"], k0) and torch.equal(t["v"], v0)
+
+
 def test_window_touches_only_its_heads():
     """Heads outside the window are neither read (NaN there is harmless) nor
     written (sentinel survives); windows in any order, plan reused."""
