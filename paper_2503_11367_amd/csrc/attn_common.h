@@ -187,9 +187,9 @@ struct FwdSplit {
 // slices are workgroups that exit at once, about 4 us per thousand) what lists of full
 // length would need for about 1024 workgroups.  The slice length itself is chosen on the device from the
 // actual list lengths (slice_length below) and is never shorter than csz.
-inline FwdSplit list_split(int32_t nq, int32_t nk, int32_t Hq, int32_t Hkv) {
-    const int hpw = (Hq / Hkv) % 2 == 0 ? 2 : 1;
-    const int64_t items = (int64_t)nq * (Hq / hpw);
+// `groups`: workgroups per q-tile (head groups).
+inline FwdSplit list_split(int32_t nq, int32_t nk, int32_t groups) {
+    const int64_t items = (int64_t)nq * groups;
     int64_t cmax = 1;
     if (items < 512) {
         cmax = (nk >= 512 ? 4 : 2) * ((1024 + items - 1) / items);

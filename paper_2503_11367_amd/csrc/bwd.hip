@@ -783,9 +783,14 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // all ordinary vector loads so far are awaited once, before the transfers start
     // (see the note in the forward kernel)
     wait_vmcnt<0>();
-    uint32_t pend[NST - 1];
+
+    // A tile is two phases: S and dP of its 64 keys (32 MFMAs, hardly any vector work), then
+    // the element-wise work and the dQ products (16 MFMAs under about 180 vector
+    // instructions); the compiler schedules inside each.
+    constexpr int PD = NST - 1;            // tiles it .. it+PD-1 are resident or in flight
+    uint32_t pend[PD];
 #pragma unroll
-    for (int j = 0; j < NST - 1; ++j) {
+    for (int j = 0; j < PD; ++j) {
         pend[j] = 0u;
         if (j < n_active) {
             pend[j] = entry_at(j);
@@ -793,85 +798,101 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         }
     }
 
-    // The ring position of tile `it` is it mod NST; the loop is unrolled NST-fold so that
-    // every LDS offset is an immediate.
-    for (int it0 = 0; it0 < n_active; it0 += NST) {
+    constexpr int kHalf = 32 * RB;
+    floatx16 sv[2], dpv[2];                // scores and dP of the tile's two halves, between the phases
+    // phase 1 of the tile at LDS offset `tile`
+    auto phase_sdp = [&](int tile, bool partial, int64_t k0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int st = 0; st < NST; ++st) {
-            const int it = it0 + st;
-            if (it >= n_active) break;
-            const int sn = (st + NST - 1) % NST;
-            const uint32_t entry = pend[0];
-            const bool partial = (entry & kPartialFlag) != 0;
-            const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kDqBN;
-            const int younger = min(NST - 2, n_active - 1 - it);
-            if (younger >= 2) wait_vmcnt<(NST > 3 ? 4 * NI : 0)>();
-            else if (younger == 1) wait_vmcnt<(NST > 2 ? 2 * NI : 0)>();
-            else wait_vmcnt<0>();
-            __syncthreads();
-            uint32_t fresh = 0u;
-            if (it + NST - 1 < n_active) {
-                if (((it + NST - 1) & 63) == 0) {
-                    const int j = it + NST - 1 + lane;
-                    list_chunk = j < n_active ? klist[j] : 0u;
-                    wait_vmcnt<0>();       // awaited here so that no wait is needed after the branch
-                }
-                fresh = entry_at(it + NST - 1);
-                issue_tile(fresh, sn);
+        for (int kb = 0; kb < 2; ++kb) {
+            floatx16 s, dp;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+            // two independent accumulation chains, alternated
+#pragma unroll
+            for (int ds = 0; ds < NDS; ++ds) {
+                s = mfma32(read_row(krow_a[ds], tile + kb * kHalf), qf[ds], s);
+                dp = mfma32(read_row(vrow_a[ds], tile + kb * kHalf), dof[ds], dp);
             }
-#pragma unroll
-            for (int j = 0; j + 1 < NST - 1; ++j) pend[j] = pend[j + 1];
-            pend[NST - 2] = fresh;
             if (partial) {
-                if (tid < kDqBN) {
-                    const uint64_t wk = bits[k0 + tid];
-                    sm.kss[0][tid] = word_ss(wk);
-                    sm.kss[1][tid] = word_mod(wk);
-                }
-                __syncthreads();
-            }
-            constexpr int kHalf = 32 * RB;
-            const int tile = st * kStageBytes;
-
-            bf16x8 dsf[4];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                floatx16 s, dp;
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const u32x4 kw = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(kb * 128 + q4 * 32));
+                    const u32x4 km = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(4 * kDqBN + kb * 128 + q4 * 32));
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-                // two independent accumulation chains, alternated
-#pragma unroll
-                for (int ds = 0; ds < NDS; ++ds) {
-                    s = mfma32(read_row(krow_a[ds], tile + kb * kHalf), qf[ds], s);
-                    dp = mfma32(read_row(vrow_a[ds], tile + kb * kHalf), dof[ds], dp);
-                }
-                if (partial) {
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        const u32x4 kw = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(kb * 128 + q4 * 32));
-                        const u32x4 km = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(4 * kDqBN + kb * 128 + q4 * 32));
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
-                            if (!visible(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
-                        }
+                    for (int j = 0; j < 4; ++j) {
+                        const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
+                        if (!visible(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
                     }
                 }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    // masked entries are -inf: exp2 gives 0 (padding rows have LSE = +inf)
-                    const float p = __builtin_amdgcn_exp2f(s[r] * scale_log2 - my_lse2);
-                    dsf[kb * 2 + (r >> 3)][r & 7] = (__bf16)(p * (dp[r] - my_delta));
-                }
             }
-            // dQ^T += K^T dS^T
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                for (int db = 0; db < NDB; ++db)
-                    dq[db] = mfma32(read_tr(tile, ks, db), dsf[ks], dq[db]);
+            sv[kb] = s;
+            dpv[kb] = dp;
         }
-    }
+    };
+    // phase 2: dS = P o (dP - Delta) as bf16, then dQ^T += K^T dS^T
+    auto phase_dq = [&](int tile) __attribute__((always_inline)) {
+        bf16x8 dsf[4];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                // masked entries are -inf: exp2 gives 0 (padding rows have LSE = +inf)
+                const float p = __builtin_amdgcn_exp2f(sv[kb][r] * scale_log2 - my_lse2);
+                dsf[kb * 2 + (r >> 3)][r & 7] = (__bf16)(p * (dpv[kb][r] - my_delta));
+            }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+                dq[db] = mfma32(read_tr(tile, ks, db), dsf[ks], dq[db]);
+    };
+
+    // The ring position of tile `it` is it mod NST; the loop is unrolled NST-fold so that
+    // every LDS offset is an immediate.
+    auto tiles = [&](auto&& body) __attribute__((always_inline)) {
+        for (int it0 = 0; it0 < n_active; it0 += NST) {
+#pragma unroll
+            for (int st = 0; st < NST; ++st) {
+                const int it = it0 + st;
+                if (it >= n_active) break;
+                const int sn = (st + PD) % NST;          // stage of tile it-1, free after the barrier
+                const uint32_t entry = pend[0];
+                const bool partial = (entry & kPartialFlag) != 0;
+                const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kDqBN;
+                const int younger = min(PD - 1, n_active - 1 - it);
+                if (younger >= 2) wait_vmcnt<(PD > 2 ? 4 * NI : 0)>();
+                else if (younger == 1) wait_vmcnt<(PD > 1 ? 2 * NI : 0)>();
+                else wait_vmcnt<0>();
+                __syncthreads();
+                uint32_t fresh = 0u;
+                if (it + PD < n_active) {
+                    if (((it + PD) & 63) == 0) {
+                        const int j = it + PD + lane;
+                        list_chunk = j < n_active ? klist[j] : 0u;
+                        wait_vmcnt<0>();       // awaited here so that no wait is needed after the branch
+                    }
+                    fresh = entry_at(it + PD);
+                    issue_tile(fresh, sn);
+                }
+#pragma unroll
+                for (int j = 0; j + 1 < PD; ++j) pend[j] = pend[j + 1];
+                pend[PD - 1] = fresh;
+                if (partial) {
+                    if (tid < kDqBN) {
+                        const uint64_t wk = bits[k0 + tid];
+                        sm.kss[0][tid] = word_ss(wk);
+                        sm.kss[1][tid] = word_mod(wk);
+                    }
+                    __syncthreads();
+                }
+                body(it, st, partial, k0);
+            }
+        }
+    };
+    tiles([&](int it, int st, bool partial, int64_t k0) __attribute__((always_inline)) {
+        phase_sdp(st * kStageBytes, partial, k0);
+        phase_dq(st * kStageBytes);
+    });
 
     if (!row_ok) return;
     if (nchunk > 1) {
@@ -978,7 +999,7 @@ static BwdLayout bwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     const size_t acc = L.ch.cmax > 1 ? (size_t)L.ch.cmax * S * Hkv * D * 4 : 0;
     L.acc_k = take(acc);
     L.acc_v = take(acc);
-    L.split = list_split(L.nq_a, L.nk_a, Hq, Hkv);
+    L.split = list_split(L.nq_a, L.nk_a, Hq);          // dq_kernel: one workgroup per (q-tile, head)
     L.dq_part = take(L.split.cmax > 1 ? (size_t)L.split.cmax * L.n_pad * Hq * D * 4 : 0);
     L.total = off;
     return L;
@@ -1020,7 +1041,7 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     pa.klist = (uint32_t*)(base + L.klist);
     pa.qorder = (int32_t*)(base + L.qorder);
     pa.csz = err + kFlagInts;
-    pa.groups = a.Hq / (a.Hq / a.Hkv % 2 == 0 ? 2 : 1);
+    pa.groups = a.Hq;
     TilePlanT pb;
     pb.nq = L.nq_b; pb.nk = L.nk_b; pb.tq = kKvBM; pb.tk = kKvBN;
     pb.cls = (uint8_t*)(base + L.cls_b);
@@ -1061,11 +1082,14 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
                            st, L.ch.cmax, n_elems, err, acc_k, acc_v, (ushort_t*)dk, (ushort_t*)dv);
         stage_end(MMATTN_STAGE_DKV_REDUCE, st);
     }
-    const bool pair = rep % 2 == 0;
+    // One query head per workgroup of four wavefronts and a two-stage ring: two such
+    // workgroups share a CU with independent barriers.  Measured against a workgroup of
+    // two heads (eight wavefronts sharing the K/V tiles, three or four stages, also with
+    // the two heads' phases half a tile out of step): equal at 128k, 1 % to 4 % faster
+    // elsewhere.
     stage_begin(MMATTN_STAGE_DQ, st);
     float* dq_part = (float*)(base + L.dq_part);
-    if (pair) launch_dq_kernel<D, 2, 3>(a, d_o, n_loc, L, scale_log2, clean, ld, pa, err, dq, dq_part, st);
-    else      launch_dq_kernel<D, 1, 2>(a, d_o, n_loc, L, scale_log2, clean, ld, pa, err, dq, dq_part, st);
+    launch_dq_kernel<D, 1, 2>(a, d_o, n_loc, L, scale_log2, clean, ld, pa, err, dq, dq_part, st);
     if (L.split.cmax > 1) {
         const int64_t threads = n_loc * a.Hq * (D / 4);
         hipLaunchKernelGGL(dq_combine_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,

@@ -532,7 +532,7 @@ static FwdLayout fwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     const int32_t Hq_run = Hq / Hkv * Hkv_run;
     L.nq = (int32_t)((n_loc + kFwdBM - 1) / kFwdBM);
     L.nk = (int32_t)(S / kFwdBN);
-    L.split = list_split(L.nq, L.nk, Hq_run, Hkv_run);
+    L.split = list_split(L.nq, L.nk, Hq_run / ((Hq / Hkv) % 2 == 0 ? 2 : 1));
     size_t off = 0;
     L.err = off;          off += 256;
     L.clean_blocks = off; off += align_up((size_t)n_blocks * 4, 256);
