@@ -19,7 +19,8 @@
 //                  the key-outer pass: split the work of a block, write partial
 //                  results, aggregate in one more launch); the partials are fp32 and
 //                  summed in a fixed order by dkv_reduce_kernel;
-//   dq_kernel      query-outer, same shape as the forward kernel.
+//   dq_kernel      query-outer: a workgroup of four wavefronts owns 128 query rows of one
+//                  head and walks the active 64-key tiles (two-stage K/V ring).
 // All contractions are 32x32x16 bf16 MFMAs.  Tiles go global -> LDS directly
 // (no registers) into rotation-swizzled layouts; a tile that is needed both as
 // row fragments and transposed is stored once (SwzTile MODE 0) and read with
