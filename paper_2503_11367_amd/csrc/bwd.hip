@@ -748,7 +748,11 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // fragment addresses (LDS byte addresses at ring stage 0): K and V rows share the lane
     // pattern (same tile layout) but live in different rings; K is also read transposed
     constexpr int PER = 16 * KT::RPS, NV = PER / 8;
-    uint32_t krow_a[NDS], vrow_a[NDS], ktr_a[NDB][NV];
+    // The V ring follows the K ring in LDS; with a short ring every V offset still fits
+    // the 16-bit offset field, so the K row addresses serve both.
+    constexpr int kVOff = NST * kStageBytes;
+    static_assert(2 * NST * kStageBytes <= 65536, "V ring out of reach of the offset field");
+    uint32_t krow_a[NDS], ktr_a[NDB][NV];
     {
         RowFragAddr<KT, D> fr;
         TrFragAddr<KT, D> ft;
@@ -757,7 +761,6 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds) {
             krow_a[ds] = lds_addr_of(sm.k[0]) + (uint32_t)fr.off[ds];
-            vrow_a[ds] = lds_addr_of(sm.v[0]) + (uint32_t)fr.off[ds];
         }
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
@@ -803,18 +806,34 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     floatx16 sv[2], dpv[2];                // scores and dP of the tile's two halves, between the phases
     // phase 1 of the tile at LDS offset `tile`
     auto phase_sdp = [&](int tile, bool partial, int64_t k0) __attribute__((always_inline)) {
+        // Two independent accumulation chains, alternated; their K and V row fragments are
+        // requested two pairs of MFMAs ahead (the compiler on its own requests them one
+        // ahead and waits before almost every MFMA), across the two halves of the tile.
+        constexpr int NP = 2 * NDS;        // MFMA pairs of the tile
+        bf16x8 kfr[2], vfr[2];
+        auto fetch = [&](int i) __attribute__((always_inline)) {
+            const int off = tile + (i / NDS) * kHalf;
+            kfr[i & 1] = read_row(krow_a[i % NDS], off);
+            vfr[i & 1] = read_row(krow_a[i % NDS], kVOff + off);
+        };
+        fetch(0);
+        fetch(1);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            floatx16 s, dp;
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-            // two independent accumulation chains, alternated
+            for (int r = 0; r < 16; ++r) { sv[kb][r] = 0.f; dpv[kb][r] = 0.f; }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ds = 0; ds < NDS; ++ds) {
-                s = mfma32(read_row(krow_a[ds], tile + kb * kHalf), qf[ds], s);
-                dp = mfma32(read_row(vrow_a[ds], tile + kb * kHalf), dof[ds], dp);
-            }
-            if (partial) {
+        for (int i = 0; i < NP; ++i) {
+            const int kb = i / NDS, ds = i % NDS;
+            sv[kb] = mfma32(kfr[i & 1], qf[ds], sv[kb]);
+            dpv[kb] = mfma32(vfr[i & 1], dof[ds], dpv[kb]);
+            if (i + 2 < NP) fetch(i + 2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (partial) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
                     const u32x4 kw = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(kb * 128 + q4 * 32));
@@ -822,12 +841,9 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
-                        if (!visible(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
+                        if (!visible(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) sv[kb][q4 * 4 + j] = -INFINITY;
                     }
                 }
-            }
-            sv[kb] = s;
-            dpv[kb] = dp;
         }
     };
     // phase 2: dS = P o (dP - Delta) as bf16, then dQ^T += K^T dS^T
@@ -841,11 +857,18 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
                 const float p = __builtin_amdgcn_exp2f(sv[kb][r] * scale_log2 - my_lse2);
                 dsf[kb * 2 + (r >> 3)][r & 7] = (__bf16)(p * (dpv[kb][r] - my_delta));
             }
+        // K^T fragments requested two MFMAs ahead
+        constexpr int NM = 4 * NDB;
+        bf16x8 tf[2];
+        tf[0] = read_tr(tile, 0, 0);
+        tf[1] = read_tr(tile, 1 / NDB, 1 % NDB);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-                dq[db] = mfma32(read_tr(tile, ks, db), dsf[ks], dq[db]);
+        for (int m = 0; m < NM; ++m) {
+            dq[m % NDB] = mfma32(tf[m & 1], dsf[m / NDB], dq[m % NDB]);
+            if (m + 2 < NM) tf[m & 1] = read_tr(tile, (m + 2) / NDB, (m + 2) % NDB);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     // The ring position of tile `it` is it mod NST; the loop is unrolled NST-fold so that
