@@ -413,12 +413,16 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
                     const bf16x2 pb2 = {(__bf16)ev[2 * k], (__bf16)ev[2 * k + 1]};
                     pw[k] = __builtin_bit_cast(uint32_t, pb2);
                     asm volatile("" : "+v"(pw[k]));
-                    if (!KR && (k & 3) == 3) {                  // eight probabilities done: publish them
-                        const u32x4 o4 = {pw[k - 3], pw[k - 2], pw[k - 1], pw[k]};
-                        *(u32x4 __attribute__((address_space(3)))*)(uintptr_t)(
-                            pb + (uint32_t)(p_imm + (k >> 2) * 1024)) = o4;
-                    }
                 }
+            // V role: publish the unit's probabilities for the partner wave, in the unit's last
+            // two slots (the partner reads them after the next barrier; LDS operations complete
+            // in order, so a store in the middle of the unit delays the fragment reads queued
+            // behind it, which the coming MFMAs wait for: 2.5 % of the kernel's time)
+            if (!KR && t >= NS - 2) {
+                const int k4 = t - (NS - 2);
+                const u32x4 o4 = {pw[4 * k4], pw[4 * k4 + 1], pw[4 * k4 + 2], pw[4 * k4 + 3]};
+                *(u32x4 __attribute__((address_space(3)))*)(uintptr_t)(pb + (uint32_t)(p_imm + k4 * 1024)) = o4;
+            }
 #pragma unroll
             for (int e = 0; e < 16; ++e)
                 if (slot_of(e) == t) {
