@@ -32,6 +32,8 @@ namespace mm {
 
 // ---------------------------------------------------------------- prep -------
 // One thread per 8 elements; D/8 consecutive lanes reduce one (row, head).
+//   ldk[Hq][2][n_pad] = -LSE/scale, then -Delta (padding rows: -inf, 0): the key-outer pass
+//                      starts its S and dP accumulators from these
 //   ld[Hq][2][n_pad] = LSE in base-2 units, then Delta = rowsum(dO o O), per head; rows
 //                      n_loc .. n_pad-1 are padding: LSE = +inf (probability 0), Delta = 0;
 //                      followed by [3][n_pad] uint32: every local row's sample/span field,
@@ -46,8 +48,8 @@ __global__ void __launch_bounds__(256)
 bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
                 const ushort_t* __restrict__ dO, const float* __restrict__ lse,
                 const uint64_t* __restrict__ bits, const int32_t* __restrict__ blocks, int32_t block,
-                int64_t n_loc, int64_t n_pad, int32_t Hq, float* __restrict__ ld,
-                ushort_t* __restrict__ qh, ushort_t* __restrict__ doh) {
+                int64_t n_loc, int64_t n_pad, int32_t Hq, float inv_scale, float* __restrict__ ld,
+                float* __restrict__ ldk, ushort_t* __restrict__ qh, ushort_t* __restrict__ doh) {
     constexpr int TPR = D / 8;
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t rh = gid / TPR;                       // row*Hq + h over padded rows
@@ -75,8 +77,14 @@ bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
         *(u32x4*)(doh + e) = dv;
         if (c == 0) {
             float* out = ld + (int64_t)h * 2 * n_pad + row;
-            out[0] = ok ? lse[(int64_t)h * n_loc + row] * kLog2e : INFINITY;
+            const float l = ok ? lse[(int64_t)h * n_loc + row] : INFINITY;
+            out[0] = l * kLog2e;
             out[n_pad] = ok ? acc : 0.f;
+            // the same as accumulator start values for the key-outer pass: S - LSE/scale and
+            // dP - Delta come straight out of the matrix instructions
+            float* outk = ldk + (int64_t)h * 2 * n_pad + row;
+            outk[0] = -l * inv_scale;
+            outk[n_pad] = ok ? -acc : 0.f;
             if (h == 0) {
                 uint32_t* info = (uint32_t*)(ld + (int64_t)Hq * 2 * n_pad) + row;
                 uint32_t ss = 0u, ca = 0u;
@@ -154,7 +162,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
            const ushort_t* __restrict__ V, const ushort_t* __restrict__ dOh,
            const uint64_t* __restrict__ bits, const int32_t* __restrict__ blocks, int32_t block,
            int64_t n_loc, int64_t n_pad, int64_t S, int32_t Hq, int32_t Hkv, float scale,
-           float scale_log2, const float* __restrict__ ld_g,
+           float scale_log2, const float* __restrict__ ld_g, const float* __restrict__ ldk_g,
            TilePlanT plan, KvChunking ch, const int32_t* __restrict__ err,
            ushort_t* __restrict__ dK, ushort_t* __restrict__ dV, float* __restrict__ accK,
            float* __restrict__ accV) {
@@ -240,8 +248,8 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
         const int64_t tile = ((int64_t)hq * n_pad + r0) * D;    // 64 consecutive rows, padded with zeros
 #pragma unroll
         for (int i = 0; i < NI; ++i) dma16(Qh + tile, tr_off[i], lds_q + stage * kStage + i * 1024);
-        if (wave < 2)                                           // wave 0: lse2 rows, wave 1: delta rows
-            dma4(ld_g + ((int64_t)hq * 2 + wave) * n_pad + r0, (uint32_t)(lane * 4),
+        if (wave < 2)                                           // wave 0: -LSE/scale rows, wave 1: -Delta rows
+            dma4(ldk_g + ((int64_t)hq * 2 + wave) * n_pad + r0, (uint32_t)(lane * 4),
                  lds_ld + stage * (8 * kKvBM) + wave * (4 * kKvBM));
         else if (wave < 5)                                      // waves 2-4: the rows' mask inputs
             dma4(info_g + (int64_t)(wave - 2) * n_pad + r0, (uint32_t)(lane * 4),
@@ -330,13 +338,27 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
 #define MM_SLOT_END() __builtin_amdgcn_sched_barrier(0)
     floatx16 xa, xb;                       // S (V role) / dP (K role) of the current and the next unit, alternating
     bf16x8 rf[NKF];                        // leading row fragments of the next first product
-    floatx4 rc[4];                         // row constants of the current unit
+    floatx4 cin[4];                        // start values of the next first product: the row constants of ITS rows
     u32x4 pin[2];                          // K role: P of the current unit
 
     // first product without overlap (start-up only)
-    auto first_plain = [&](floatx16& x, const uint32_t (&a)[NDS], int imm) __attribute__((always_inline)) {
+    // the accumulator of a first product starts from its rows' constants (-LSE/scale for S,
+    // -Delta for dP, staged with the Q tile): 16 element rows = four 16-byte reads
+    auto start_values = [&](uint32_t base, int imm, floatx4 (&c)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) x[r] = 0.f;
+        for (int q4 = 0; q4 < 4; ++q4)
+            c[q4] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(base + (uint32_t)(imm + q4 * 32));
+    };
+    auto as_acc = [&](const floatx4 (&c)[4]) __attribute__((always_inline)) -> floatx16 {
+        floatx16 x;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) x[r] = c[r >> 2][r & 3];
+        return x;
+    };
+    auto first_plain = [&](floatx16& x, const uint32_t (&a)[NDS], int imm, uint32_t rcb, int rc_imm) __attribute__((always_inline)) {
+        floatx4 c0[4];
+        start_values(rcb, rc_imm, c0);
+        x = as_acc(c0);
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds) x = mfma32(read_row(a[ds], imm), res[ds], x);
     };
@@ -360,16 +382,16 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     //   x_cur  -> P or dS of this unit (bf16), second product from the transpose
     //             fragments at a2 + imm2, row groups ks0 and ks0+1
     //   rf[]   <- fragments 0..NKF-1 of the first product after that: a1n_lo[..] + imm1n
-    //   rc[]   holds the row constants of this unit's first 8 element rows on entry; the
-    //             others are read early in the unit (rcb + rc_imm), the next unit's first
-    //             ones at its end (rcb_n + rc_imm_n)
+    //   cin[]  holds the start values of x_next on entry (the row constants of the next
+    //             unit's rows); after the first slot it is refilled from rcb + rc_imm with
+    //             those of the unit after next
     //   hook() runs after the second slot (scalar work hidden behind the matrix pipe)
     //   V role: this unit's P is stored at pb + p_imm;  K role: it is read from there (the
     //             first half is in pin[0] on entry) and pin[0] <- the next unit's, at
     //             pb + p_imm_n (-1 when that P is not published yet)
     auto unit = [&](auto KR_, floatx16& x_next, const floatx16& x_cur, const uint32_t* a1_hi, int off1,
                     int imm1, const uint32_t* a1n_lo, int imm1n, const uint32_t (&a2)[NDB][NV], int imm2,
-                    int ks0, uint32_t rcb, int rc_imm, uint32_t rcb_n, int rc_imm_n, uint32_t pb,
+                    int ks0, uint32_t rcb, int rc_imm, uint32_t pb,
                     int p_imm, int p_imm_n, auto&& hook) __attribute__((always_inline)) {
         constexpr bool KR = decltype(KR_)::value;
         bf16x8 tf[NKF], pf0, pf1;
@@ -388,10 +410,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             // ---- matrix instruction and the request that refills its operand ----
             if (t < NDS) {
                 if (t == 0) {
-                    floatx16 z;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) z[r] = 0.f;
-                    x_next = mfma32(rf[0], res[0], z);
+                    x_next = mfma32(rf[0], res[0], as_acc(cin));
                 } else {
                     x_next = mfma32(rf[t % NKF], res[t], x_next);
                 }
@@ -426,23 +445,25 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
 #pragma unroll
             for (int e = 0; e < 16; ++e)
                 if (slot_of(e) == t) {
-                    const float c = rc[e >> 2][e & 3];
                     if (!KR) {
-                        // masked entries are -inf: exp2 gives 0 (padding rows have LSE = +inf)
-                        ev[e] = __builtin_amdgcn_exp2f(x_cur[e] * scale_log2 - c);
+                        // x_cur is S - LSE/scale; masked entries are -inf: exp2 gives 0 (padding
+                        // rows have LSE = +inf)
+                        ev[e] = __builtin_amdgcn_exp2f(x_cur[e] * scale_log2);
                     } else {
+                        // x_cur is dP - Delta
                         const uint32_t w = pin[e >> 3][(e & 7) >> 1];
                         const float pv = __builtin_bit_cast(float, (e & 1) ? (w & 0xffff0000u) : (w << 16));
-                        ev[e] = pv * (x_cur[e] - c);
+                        ev[e] = pv * x_cur[e];
                     }
                     asm volatile("" : "+v"(ev[e]));
                 }
-            // row constants: four rows per read, requested a few slots before their use
-            if (t == (slot_of(8) > 4 ? slot_of(8) - 4 : 0)) rc[2] = read_rc(rcb, rc_imm, 2);
-            if (t == (slot_of(12) > 5 ? slot_of(12) - 4 : 1)) rc[3] = read_rc(rcb, rc_imm, 3);
+            // start values of the first product formed in the NEXT unit: four rows per read,
+            // spread over the unit (cin[] was consumed by the first slot's MFMA)
+            if (t == 1) cin[0] = read_rc(rcb, rc_imm, 0);
+            if (t == 2) cin[1] = read_rc(rcb, rc_imm, 1);
             if (t == SLV + 1) {
-                rc[0] = read_rc(rcb_n, rc_imm_n, 0);
-                rc[1] = read_rc(rcb_n, rc_imm_n, 1);
+                cin[2] = read_rc(rcb, rc_imm, 2);
+                cin[3] = read_rc(rcb, rc_imm, 3);
             }
             // K role: P of this unit's last 8 element rows, then of the next unit's first 8
             if (KR && t == (slot_of(8) > 4 ? slot_of(8) - 4 : 0)) pin[1] = read_p(p_imm + 1024);
@@ -506,21 +527,20 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
                 const int qs0 = u, qs1 = (u + 1) % kKvQst;
                 const bool partial = top(i, [] {});
                 if (i == 0 && n_steps > 0) {
-                    first_plain(xa, row_addr, 0);
+                    first_plain(xa, row_addr, 0, rc_addr, 0);
 #pragma unroll
                     for (int j = 0; j < NKF; ++j) rf[j] = read_row(row_addr[j], kUnit);
-                    rc[0] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(rc_addr);
-                    rc[1] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(rc_addr + 32);
+                    start_values(rc_addr, 128, cin);
                 }
                 if (i < n_steps) {
                     if (partial) mask_unit(xa, qs0 * (12 * kKvBM));
                     unit(std::false_type{}, xb, xa, &row_addr[NKF], 0, qs0 * kStage + kUnit, &row_addr[0],
-                         qs1 * kStage, dtr, 0, 0, rc_addr, qs0 * kLdStage, rc_addr, qs0 * kLdStage + 128,
+                         qs1 * kStage, dtr, 0, 0, rc_addr, qs1 * kLdStage,
                          p_addr, (u & 1) * 16384, -1, [&] { issue(i); });
                     if (partial) mask_unit(xb, qs0 * (12 * kKvBM) + 128);
                     unit(std::false_type{}, xa, xb, &row_addr[NKF], 0, qs1 * kStage, &row_addr[0],
-                         qs1 * kStage + kUnit, dtr, 0, 2, rc_addr, qs0 * kLdStage + 128, rc_addr,
-                         qs1 * kLdStage, p_addr, (u & 1) * 16384 + 2048, -1, [] {});
+                         qs1 * kStage + kUnit, dtr, 0, 2, rc_addr, qs1 * kLdStage + 128,
+                         p_addr, (u & 1) * 16384 + 2048, -1, [] {});
                 } else {
                     issue(i);
                 }
@@ -535,8 +555,8 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     } else {
         // ---- K role: step i-1 (units 2i-2, 2i-1) and the first product of step i.  All
         // ring positions are run-time here: drow[] is the dO tile of step i (the one of
-        // step i-1 lies dprev bytes from it), qtr[] the Q tile of step i-1, rcp / rcc
-        // the row constants of steps i-1 / i, pp the P buffer of step i-1.
+        // step i-1 lies dprev bytes from it), qtr[] the Q tile of step i-1, rcc
+        // the row constants of step i, pp the P buffer of step i-1.
         uint32_t drow[NDS], qtr[NDB][NV];
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds) drow[ds] = row_addr[ds];
@@ -545,24 +565,23 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
 #pragma unroll
             for (int v = 0; v < NV; ++v) qtr[db][v] = tr_addr[db][v] + (uint32_t)((kKvQst - 1) * kStage);
         int dprev = 0, qpos = kKvQst - 1;
-        uint32_t rcp = rc_addr + (uint32_t)((kKvQst - 1) * kLdStage), rcc = rc_addr;
+        uint32_t rcc = rc_addr;
         uint32_t pp = p_addr + 16384u;
         for (int i = 0; i <= n_steps; ++i) {
             top(i, [&] {
                 if (i >= 1) pin[0] = *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(pp);
             });
             if (i == 0 && n_steps > 0) {
-                first_plain(xa, drow, 0);
+                first_plain(xa, drow, 0, rc_addr, 0);
 #pragma unroll
                 for (int j = 0; j < NKF; ++j) rf[j] = read_row(drow[j], kUnit);
-                rc[0] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(rc_addr);
-                rc[1] = *(const floatx4 __attribute__((address_space(3)))*)(uintptr_t)(rc_addr + 32);
+                start_values(rc_addr, 128, cin);
             }
             if (i >= 1) {
-                unit(std::true_type{}, xb, xa, &drow[NKF], dprev, kUnit, &drow[0], 0, qtr, 0, 0, rcp, 0,
-                     rcp, 128, pp, 0, 2048, [&] { issue(i); });
-                unit(std::true_type{}, xa, xb, &drow[NKF], 0, 0, &drow[0], kUnit, qtr, 0, 2, rcp, 128,
-                     rcc, 0, pp, 2048, -1, [] {});
+                unit(std::true_type{}, xb, xa, &drow[NKF], dprev, kUnit, &drow[0], 0, qtr, 0, 0, rcc, 0,
+                     pp, 0, 2048, [&] { issue(i); });
+                unit(std::true_type{}, xa, xb, &drow[NKF], 0, 0, &drow[0], kUnit, qtr, 0, 2, rcc, 128,
+                     pp, 2048, -1, [] {});
             } else {
                 issue(i);
             }
@@ -578,7 +597,6 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int v = 0; v < NV; ++v) qtr[db][v] += (uint32_t)(qdelta * kStage);
-            rcp = rcc;
             rcc = rc_addr + (uint32_t)(((i + 1) & (kKvQst - 1)) * kLdStage);
             pp = p_addr + (uint32_t)((i & 1) * 16384);
         }
@@ -977,7 +995,7 @@ dq_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int64_t n_pad, i
 
 // ---------------------------------------------------------------- host -------
 struct BwdLayout {
-    size_t err, clean_blocks, ld, qh, doh, cls_a, kcount, klist, qorder, cls_b, qcount, qlist,
+    size_t err, clean_blocks, ld, ldk, qh, doh, cls_a, kcount, klist, qorder, cls_b, qcount, qlist,
         korder, acc_k, acc_v, dq_part, total;
     int32_t nq_a, nk_a, nq_b, nk_b;
     int64_t n_pad;
@@ -1014,6 +1032,7 @@ static BwdLayout bwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     L.err = take(256);
     L.clean_blocks = take((size_t)n_blocks * 4);
     L.ld = take(((size_t)Hq * 2 + 3) * L.n_pad * 4);
+    L.ldk = take((size_t)Hq * 2 * L.n_pad * 4);
     L.qh = take((size_t)Hq * L.n_pad * D * 2);
     L.doh = take((size_t)Hq * L.n_pad * D * 2);
     L.cls_a = take((size_t)L.nq_a * L.nk_a);
@@ -1058,6 +1077,7 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     int32_t* err = (int32_t*)(base + L.err);
     int32_t* clean = (int32_t*)(base + L.clean_blocks);
     float* ld = (float*)(base + L.ld);
+    float* ldk = (float*)(base + L.ldk);
     ushort_t* qh = (ushort_t*)(base + L.qh);
     ushort_t* doh = (ushort_t*)(base + L.doh);
     float* acc_k = (float*)(base + L.acc_k);
@@ -1093,14 +1113,14 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
         const int64_t threads = L.n_pad * a.Hq * (D / 8);
         hipLaunchKernelGGL(bwd_prep_kernel<D>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
                            st, (const ushort_t*)a.q, (const ushort_t*)o, (const ushort_t*)d_o, lse,
-                           a.bits, clean, a.block, n_loc, L.n_pad, a.Hq, ld, qh, doh);
+                           a.bits, clean, a.block, n_loc, L.n_pad, a.Hq, 1.0f / a.scale, ld, ldk, qh, doh);
     }
     const int rep = a.Hq / a.Hkv;
     stage_begin(MMATTN_STAGE_DKV, st);
     hipLaunchKernelGGL(dkv_kernel<D>, dim3((unsigned)((int64_t)L.nk_b * a.Hkv * L.ch.cmax)),
                        dim3(kKvThreads), 0, st, (const ushort_t*)qh, (const ushort_t*)a.k,
                        (const ushort_t*)a.v, (const ushort_t*)doh, a.bits, clean, a.block, n_loc,
-                       L.n_pad, a.S, a.Hq, a.Hkv, a.scale, scale_log2, ld, pb, L.ch, err,
+                       L.n_pad, a.S, a.Hq, a.Hkv, a.scale, scale_log2, ld, ldk, pb, L.ch, err,
                        (ushort_t*)dk, (ushort_t*)dv, acc_k, acc_v);
     stage_end(MMATTN_STAGE_DKV, st);
     if (L.ch.cmax > 1) {
