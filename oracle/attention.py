@@ -59,7 +59,8 @@ def probabilities(Qh, Kg, vis, scale):
     return P, lse
 
 
-def forward(Q_loc, K, V, rows, sample, span, causal, scale=None, chunk=512, modality=None, attend=None):
+def forward(Q_loc, K, V, rows, sample, span, causal, scale=None, chunk=512, modality=None, attend=None,
+            window=None):
     """Q_loc [n,Hq,D], K,V [S,Hkv,D] float64; rows[n] global positions.
     Returns O [n,Hq,D] and LSE [Hq,n]."""
     n, Hq, D = Q_loc.shape
@@ -71,7 +72,7 @@ def forward(Q_loc, K, V, rows, sample, span, causal, scale=None, chunk=512, moda
     k_idx = np.arange(S)
     for a in range(0, n, chunk):
         b = min(n, a + chunk)
-        vis = visible(rows[a:b], k_idx, sample, span, causal, modality, attend)
+        vis = visible(rows[a:b], k_idx, sample, span, causal, modality, attend, window)
         for h in range(Hq):
             g = h // rep
             P, lse = probabilities(Q_loc[a:b, h], K[:, g], vis, scale)
@@ -81,7 +82,7 @@ def forward(Q_loc, K, V, rows, sample, span, causal, scale=None, chunk=512, moda
 
 
 def backward(Q_loc, K, V, dO, rows, sample, span, causal, scale=None, chunk=512, modality=None,
-             attend=None):
+             attend=None, window=None):
     """Returns dQ [n,Hq,D], dK [S,Hkv,D], dV [S,Hkv,D] (this rank's partial
     sums), all float64."""
     n, Hq, D = Q_loc.shape
@@ -94,7 +95,7 @@ def backward(Q_loc, K, V, dO, rows, sample, span, causal, scale=None, chunk=512,
     k_idx = np.arange(S)
     for a in range(0, n, chunk):
         b = min(n, a + chunk)
-        vis = visible(rows[a:b], k_idx, sample, span, causal, modality, attend)
+        vis = visible(rows[a:b], k_idx, sample, span, causal, modality, attend, window)
         for h in range(Hq):
             g = h // rep
             P, _ = probabilities(Q_loc[a:b, h], K[:, g], vis, scale)

@@ -28,12 +28,22 @@ This expresses the "shared question" pattern of the paper's comparison with
 DCP (section 5.5 and its appendix): answers are nobidir spans of distinct modalities that attend
 the text modality (the question) and their own.
 
+A span may carry a look-back `window` W: among the earlier keys of the
+span's own modality its tokens see only those with q - k < W (keys of other
+modalities and the own-span term are not limited).  The "lambda" pattern of
+the same comparison (a few leading sink tokens every later token keeps
+attending, plus a sliding window) is then two nobidir spans per sample: the
+sinks with one modality, the rest with another modality and the window.  The
+paper names the pattern without giving its encoding; the window field
+(bits 44-59 of the word) is this build's extension of the bitfield.
+
 Word layout (LSB first, section 4.2: low bits = LLM and modality encoders,
 bit 63 = causal bit):
   bits 0-7   attend-set, bit m set = may attend modality m   (all set here)
   bits 8-11  own modality index
   bits 12-27 span id (0 = none)
   bits 28-43 sample id
+  bits 44-59 look-back window over keys of the own modality (0 = unlimited)
   bit 63     causal bit
 
 Pins: tests/test_oracle_mask.py -- closed-form pair totals
@@ -44,8 +54,11 @@ text tokens see every earlier token), encode/decode round trip; for the
 attend-set generalisation a mask written out by hand and the pair count
 (P1 count minus the denied backward pairs, counted by a separate loop); for
 nobidir spans a shared-question mask written out by hand and its closed-form
-pair count; tests/test_oracle_attention.py checks that every answer's rows
-equal plain causal attention over [question, that answer].
+pair count; for windows a lambda mask written out by hand, its closed-form
+pair count, the mask built from the pattern's description, and window >=
+length = no window; tests/test_oracle_attention.py checks that every
+answer's rows equal plain causal attention over [question, that answer] and
+that the lambda pattern equals the library routine with a band mask.
 """
 import numpy as np
 
@@ -83,20 +96,31 @@ def token_fields(S, spans, sample_off, noncausal=None, deny=None, nobidir=None):
     return sample, span, causal, modality, attend
 
 
-def visible(q_idx, k_idx, sample, span, causal, modality=None, attend=None):
+def token_windows(S, spans, window):
+    """Per-token look-back window (0 = unlimited) from per-span windows."""
+    w = np.zeros(S, dtype=np.int64)
+    for (start, n, _mod), wj in zip(spans, window):
+        w[start:start + n] = int(wj)
+    return w
+
+
+def visible(q_idx, k_idx, sample, span, causal, modality=None, attend=None, window=None):
     """Boolean matrix vis[q,k] for global token index arrays q_idx, k_idx.
-    Without modality/attend every attend-set is taken as all ones."""
+    Without modality/attend every attend-set is taken as all ones; without
+    window no token's look-back is limited."""
     q = np.asarray(q_idx)[:, None]
     k = np.asarray(k_idx)[None, :]
     same_sample = sample[q] == sample[k]
     back = (causal[q] == 1) & (k <= q)
     if attend is not None:
         back &= ((attend[q] >> modality[k]) & 1) == 1
+    if window is not None:
+        back &= (window[q] == 0) | (modality[q] != modality[k]) | (q - k < window[q])
     same_span = (span[q] != 0) & (span[q] == span[k])
     return same_sample & (back | same_span)
 
 
-def encode(sample, span, causal, modality, attend=None):
+def encode(sample, span, causal, modality, attend=None, window=None):
     """Per-token 64-bit word from the fields, as uint64."""
     if attend is None:
         w = np.full(sample.shape, ATTEND_ALL, dtype=np.uint64)
@@ -105,6 +129,8 @@ def encode(sample, span, causal, modality, attend=None):
     w |= modality.astype(np.uint64) << np.uint64(8)
     w |= span.astype(np.uint64) << np.uint64(12)
     w |= sample.astype(np.uint64) << np.uint64(28)
+    if window is not None:
+        w |= window.astype(np.uint64) << np.uint64(44)
     w |= causal.astype(np.uint64) << np.uint64(CAUSAL_BIT)
     return w
 
@@ -118,3 +144,9 @@ def decode(bits):
     sample = ((b >> np.uint64(28)) & np.uint64(0xFFFF)).astype(np.int64)
     causal = ((b >> np.uint64(CAUSAL_BIT)) & np.uint64(1)).astype(np.int64)
     return sample, span, causal, modality, attend
+
+
+def decode_window(bits):
+    """The look-back window field of each word."""
+    b = np.asarray(bits, dtype=np.uint64)
+    return ((b >> np.uint64(44)) & np.uint64(0xFFFF)).astype(np.int64)

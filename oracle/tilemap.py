@@ -27,7 +27,7 @@ from .mask import visible
 EMPTY, FULL, PARTIAL = 0, 1, 2
 
 
-def tile_map(sample, span, causal, tq, tk, modality=None, attend=None):
+def tile_map(sample, span, causal, tq, tk, modality=None, attend=None, window=None):
     S = sample.shape[0]
     assert S % tq == 0 and S % tk == 0
     nq, nk = S // tq, S // tk
@@ -35,7 +35,7 @@ def tile_map(sample, span, causal, tq, tk, modality=None, attend=None):
     k_idx = np.arange(S)
     for i in range(nq):
         q_idx = np.arange(i * tq, (i + 1) * tq)
-        vis = visible(q_idx, k_idx, sample, span, causal, modality, attend)          # [tq, S]
+        vis = visible(q_idx, k_idx, sample, span, causal, modality, attend, window)          # [tq, S]
         cnt[i] = vis.reshape(tq, nk, tk).sum(axis=(0, 2))
     cls = np.full((nq, nk), PARTIAL, dtype=np.uint8)
     cls[cnt == 0] = EMPTY
@@ -61,12 +61,12 @@ def _load_c():
             raise RuntimeError("oracle/libtilemap_ref.so not built; run __graft_entry__.build()")
         _lib = ctypes.CDLL(path)
         _lib.tilemap_ref.restype = ctypes.c_int
-        _lib.tilemap_ref.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int64, ctypes.c_int32,
+        _lib.tilemap_ref.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int64, ctypes.c_int32,
                                                               ctypes.c_int32] + [ctypes.c_void_p] * 3
     return _lib
 
 
-def tile_map_c(sample, span, causal, tq, tk, modality=None, attend=None):
+def tile_map_c(sample, span, causal, tq, tk, modality=None, attend=None, window=None):
     """Same result as tile_map, computed by the plain-C double loop."""
     lib = _load_c()
     S = sample.shape[0]
@@ -77,11 +77,12 @@ def tile_map_c(sample, span, causal, tq, tk, modality=None, attend=None):
     ca = np.ascontiguousarray(causal, dtype=np.int64)
     mo = np.ascontiguousarray(np.zeros(S) if modality is None else modality, dtype=np.int64)
     at = np.ascontiguousarray(np.full(S, 0xFF) if attend is None else attend, dtype=np.int64)
+    wi = np.ascontiguousarray(np.zeros(S) if window is None else window, dtype=np.int64)
     cls = np.zeros((nq, nk), dtype=np.uint8)
     cnt = np.zeros((nq, nk), dtype=np.uint32)
     W = np.zeros(nq, dtype=np.uint64)
     rc = lib.tilemap_ref(sa.ctypes.data, sp.ctypes.data, ca.ctypes.data, mo.ctypes.data, at.ctypes.data,
-                         S, tq, tk,
+                         wi.ctypes.data, S, tq, tk,
                          cls.ctypes.data, cnt.ctypes.data, W.ctypes.data)
     assert rc == 0
     return cls, cnt, W

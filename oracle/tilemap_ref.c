@@ -5,7 +5,8 @@
  * tests/test_oracle_tilemap.py.
  *
  *   vis(q,k) = sample[q]==sample[k] &&
- *              ((causal[q] && k<=q && bit modality[k] of attend[q]) ||
+ *              ((causal[q] && k<=q && bit modality[k] of attend[q] &&
+ *                (window[q]==0 || modality[q]!=modality[k] || q-k<window[q])) ||
  *               (span[q]!=0 && span[q]==span[k]))
  *   cnt[i][j] = number of visible pairs in q-tile i x k-tile j
  *   cls = 0 EMPTY (cnt==0), 1 FULL (cnt==tq*tk), 2 PARTIAL
@@ -14,7 +15,8 @@
 #include <stdint.h>
 
 int tilemap_ref(const int64_t* sample, const int64_t* span, const int64_t* causal,
-                const int64_t* modality, const int64_t* attend, int64_t S, int32_t tq, int32_t tk,
+                const int64_t* modality, const int64_t* attend, const int64_t* window,
+                int64_t S, int32_t tq, int32_t tk,
                 uint8_t* cls, uint32_t* cnt, uint64_t* W)
 {
     if (S % tq || S % tk) return -1;
@@ -28,6 +30,7 @@ int tilemap_ref(const int64_t* sample, const int64_t* span, const int64_t* causa
                 for (int64_t k = j * tk; k < (j + 1) * tk; ++k) {
                     int same_sample = sample[q] == sample[k];
                     int back = causal[q] && k <= q && ((attend[q] >> modality[k]) & 1);
+                    if (window[q] != 0 && modality[q] == modality[k] && q - k >= window[q]) back = 0;
                     int same_span = span[q] != 0 && span[q] == span[k];
                     c += (uint32_t)(same_sample && (back || same_span));
                 }

@@ -30,6 +30,7 @@ class Layout:
     noncausal: List[int] = field(default_factory=list)   # per-span flag (0 = causal bit set)
     deny: List[int] = field(default_factory=list)        # per-span mask of modalities NOT attended
     nobidir: List[int] = field(default_factory=list)     # per-span flag (1 = no bidirectional term)
+    window: List[int] = field(default_factory=list)      # per-span look-back window over the own modality (0 = none)
 
     def __post_init__(self):
         if not self.noncausal:
@@ -38,12 +39,18 @@ class Layout:
             self.deny = [0] * len(self.spans)
         if not self.nobidir:
             self.nobidir = [0] * len(self.spans)
+        if not self.window:
+            self.window = [0] * len(self.spans)
 
     def span_flags(self) -> List[int]:
         """Per-span flag words of the C ABI: bit 0 non-causal, bit 1 no
-        bidirectional term, bits 8-15 deny mask."""
-        return [int(n) | (int(u) << 1) | (int(d) << 8)
-                for n, u, d in zip(self.noncausal, self.nobidir, self.deny)]
+        bidirectional term, bits 8-15 deny mask, bits 16-31 look-back window
+        (as a signed 32-bit value, the type of the flags field)."""
+        out = []
+        for n, u, d, w in zip(self.noncausal, self.nobidir, self.deny, self.window):
+            f = int(n) | (int(u) << 1) | (int(d) << 8) | (int(w) << 16)
+            out.append(f - (1 << 32) if f >= (1 << 31) else f)
+        return out
 
 
 @dataclass
@@ -207,6 +214,21 @@ def layout_shared_question(n_question: int, answer_lens: List[int], n_tail: int 
         pos += n
     S = pos + n_tail
     return Layout(S, spans, [0, S], deny=deny, nobidir=[1] * len(spans))
+
+
+def layout_lambda(sample_lens: List[int], n_sink: int, window: int) -> Layout:
+    """Attention sinks plus a sliding window (the "lambda" pattern of the
+    paper's comparison with DCP), per packed sample: the first n_sink tokens
+    are a span of modality 1, the rest a span of modality 2 with the look-back
+    window; neither has the bidirectional term.  A token then sees its
+    sample's sinks and the last `window` tokens up to itself."""
+    spans, win, off = [], [], [0]
+    for L in sample_lens:
+        assert L > n_sink >= 1
+        spans += [(off[-1], n_sink, 1), (off[-1] + n_sink, L - n_sink, 2)]
+        win += [0, window]
+        off.append(off[-1] + L)
+    return Layout(off[-1], spans, off, nobidir=[1] * len(spans), window=win)
 
 
 def layout_block_causal(S: int, block: int) -> Layout:

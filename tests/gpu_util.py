@@ -13,12 +13,18 @@ def fields(lay):
     return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny, lay.nobidir)
 
 
+def windows(lay):
+    """Per-token look-back windows, or None when the layout has none (the
+    oracle's functions take it as the keyword `window`)."""
+    return om.token_windows(lay.S, lay.spans, lay.window) if any(lay.window) else None
+
+
 def gpu_bits(lay):
     return mb.mask_encode(lay.spans, lay.sample_off, lay.S, device=DEV, flags=lay.span_flags())
 
 
 def oracle_bits(lay):
-    return om.encode(*fields(lay))
+    return om.encode(*fields(lay), window=windows(lay))
 
 
 def to_np_u64(t):

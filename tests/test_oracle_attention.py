@@ -52,6 +52,23 @@ def test_shared_question_equals_causal_sdpa_per_answer():
         pos += n
 
 
+def test_lambda_equals_sdpa_with_the_band_mask():
+    """Sinks plus sliding window: the library routine with the boolean mask
+    written from the pattern's description (no mask predicate involved)."""
+    L, n_sink, W = 90, 3, 12
+    lay = wl.layout_lambda([L], n_sink, W)
+    f, rows, Q, K, V, _ = setup(lay, 4, 2, 16, 5)
+    win = om.token_windows(lay.S, lay.spans, lay.window)
+    O, _ = oa.forward(Q, K, V, rows, f[0], f[1], f[2], modality=f[3], attend=f[4], window=win, chunk=32)
+    pos = np.arange(L)
+    band = (pos[None, :] <= pos[:, None]) & ((pos[None, :] < n_sink) | (pos[:, None] - pos[None, :] < W))
+    q = torch.from_numpy(Q).permute(1, 0, 2)[None]
+    k = torch.from_numpy(K).permute(1, 0, 2)[None].repeat_interleave(2, dim=1)
+    v = torch.from_numpy(V).permute(1, 0, 2)[None].repeat_interleave(2, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=torch.from_numpy(band))
+    assert np.allclose(O, ref[0].permute(1, 0, 2).numpy(), atol=1e-12)
+
+
 def test_single_span_equals_full_sdpa():
     lay = wl.Layout(64, [(0, 64, wl.IMAGE)], [0, 64])
     f, rows, Q, K, V, _ = setup(lay, 2, 2, 8, 1)

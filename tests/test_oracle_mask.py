@@ -13,11 +13,15 @@ def fields(lay):
     return om.token_fields(lay.S, lay.spans, lay.sample_off, lay.noncausal, lay.deny, lay.nobidir)
 
 
+def windows(lay):
+    return om.token_windows(lay.S, lay.spans, lay.window) if any(lay.window) else None
+
+
 def dense(lay):
     sample, span, causal, modality, attend = fields(lay)
     idx = np.arange(lay.S)
-    if any(lay.deny) or any(lay.nobidir):
-        return om.visible(idx, idx, sample, span, causal, modality, attend)
+    if any(lay.deny) or any(lay.nobidir) or any(lay.window):
+        return om.visible(idx, idx, sample, span, causal, modality, attend, windows(lay))
     return om.visible(idx, idx, sample, span, causal)
 
 
@@ -135,6 +139,90 @@ def test_shared_question_pair_count(nq, answers):
     lay = wl.layout_shared_question(nq, answers)
     want = nq * (nq + 1) // 2 + sum(n * nq + n * (n + 1) // 2 for n in answers)
     assert int(dense(lay).sum()) == want
+
+
+def test_lambda_rows_by_hand():
+    """7 tokens, 2 sinks, window 3: every token sees the sinks before it and the
+    last three tokens up to itself."""
+    lay = wl.layout_lambda([7], 2, 3)
+    expect = np.array([
+        [1, 0, 0, 0, 0, 0, 0],
+        [1, 1, 0, 0, 0, 0, 0],
+        [1, 1, 1, 0, 0, 0, 0],
+        [1, 1, 1, 1, 0, 0, 0],
+        [1, 1, 1, 1, 1, 0, 0],
+        [1, 1, 0, 1, 1, 1, 0],
+        [1, 1, 0, 0, 1, 1, 1]], dtype=bool)
+    assert np.array_equal(dense(lay), expect)
+    assert windows(lay).tolist() == [0, 0, 3, 3, 3, 3, 3]
+
+
+def lambda_pairs(sample_lens, n_sink, window):
+    """per sample: s(s+1)/2 among the sinks, then body token i (0-based) sees the
+    s sinks and min(i+1, W) body tokens."""
+    tot = 0
+    for L in sample_lens:
+        tot += n_sink * (n_sink + 1) // 2
+        tot += sum(n_sink + min(i + 1, window) for i in range(L - n_sink))
+    return tot
+
+
+@pytest.mark.parametrize("lens,n_sink,window", [([40], 4, 8), ([33, 70, 25], 3, 16), ([64, 64], 1, 1),
+                                                 ([50], 5, 200)])
+def test_lambda_pair_count_and_shape(lens, n_sink, window):
+    lay = wl.layout_lambda(lens, n_sink, window)
+    v = dense(lay)
+    assert int(v.sum()) == lambda_pairs(lens, n_sink, window)
+    # the same mask from its description: sinks or the band, inside a sample, never ahead
+    pos = np.arange(lay.S)
+    start = np.repeat(lay.sample_off[:-1], np.diff(lay.sample_off))
+    q, k = pos[:, None], pos[None, :]
+    want = (start[:, None] == start[None, :]) & (k <= q) & ((k - start[None, :] < n_sink) | (q - k < window))
+    assert np.array_equal(v, want)
+
+
+def test_window_not_shorter_than_the_sample_is_no_window():
+    a = wl.layout_lambda([48, 30], 2, 48)
+    b = wl.layout_lambda([48, 30], 2, 0)
+    assert np.array_equal(dense(a), dense(b))
+    pos = np.arange(78)
+    smp = (pos >= 48).astype(int)
+    assert np.array_equal(dense(b), (smp[:, None] == smp[None, :]) & (pos[None, :] <= pos[:, None]))
+
+
+def test_window_limits_only_the_own_modality_and_not_the_own_span():
+    """image span [2:6] with window 2 (bidirectional) after two text tokens: its
+    tokens still see the whole span and all earlier text; a second image span
+    [8:10] with window 2 loses the first span's tokens, which are more than one
+    position back, but keeps the text."""
+    lay = wl.Layout(10, [(2, 4, wl.IMAGE), (8, 2, wl.IMAGE)], [0, 10], window=[2, 2])
+    v = dense(lay)
+    assert v[3].tolist() == [True, True, True, True, True, True, False, False, False, False]
+    assert v[8].tolist() == [True, True, False, False, False, False, True, True, True, True]
+    assert v[9].tolist() == [True, True, False, False, False, False, True, True, True, True]
+    assert v[7].tolist() == [True] * 8 + [False] * 2          # text is not limited
+
+
+def test_tile_map_with_windows():
+    lay = wl.layout_lambda([300, 212], 7, 40)
+    f = fields(lay)
+    w = windows(lay)
+    a = ot.tile_map(f[0], f[1], f[2], 64, 32, f[3], f[4], w)
+    b = ot.tile_map_c(f[0], f[1], f[2], 64, 32, f[3], f[4], w)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    assert int(a[2].sum()) == lambda_pairs([300, 212], 7, 40)
+    # far below the band and to the right of the sinks' columns the tiles are empty
+    assert a[0][4, 1] == ot.EMPTY and a[0][4, 0] == ot.PARTIAL
+
+
+def test_window_field_round_trip():
+    lay = wl.layout_lambda([100, 60], 4, 65535)
+    bits = om.encode(*fields(lay), window=windows(lay))
+    assert np.array_equal(om.decode_window(bits), windows(lay))
+    for x, y in zip(om.decode(bits), fields(lay)):
+        assert np.array_equal(x, y)
+    assert lay.span_flags() == [2, 2 | (65535 << 16) - (1 << 32), 2, 2 | (65535 << 16) - (1 << 32)]
 
 
 def test_block_causal_is_block_lower_triangle():
