@@ -22,9 +22,11 @@
  *
  * Mask word (LSB first): bits 0-7 attend-set (bit m = may attend modality m),
  * bits 8-11 own modality, bits 12-27 span id (0 = not in a bidirectional
- * span), bits 28-43 sample id, bit 63 causal bit.  Visibility of key k to
+ * span), bits 28-43 sample id, bits 44-59 look-back window W over keys of the
+ * own modality (0 = unlimited), bit 63 causal bit.  Visibility of key k to
  * query q:
- *   sample(q)==sample(k) && ( (causal(q) && k<=q && attend(q)[modality(k)]) ||
+ *   sample(q)==sample(k) && ( (causal(q) && k<=q && attend(q)[modality(k)] &&
+ *                              (W(q)==0 || modality(k)!=modality(q) || q-k<W(q))) ||
  *                             (span(q)!=0 && span(q)==span(k)) )
  * Text tokens attend every modality; a span's attend-set is all ones minus its
  * deny mask, so with no deny masks the backward term is plain causal
@@ -83,11 +85,19 @@ enum { MMATTN_TILE_EMPTY = 0, MMATTN_TILE_FULL = 1, MMATTN_TILE_PARTIAL = 2 };
  * earlier tokens of the modalities they attend (an answer of section 5.5's
  * shared-question pattern: attends text and its own modality); such a span
  * must keep the causal bit and must attend its own modality, so that every
- * token sees at least itself (else MMATTN_ERR_LAYOUT). */
+ * token sees at least itself (else MMATTN_ERR_LAYOUT).  flags bits 16-31: a
+ * look-back window W in tokens (0 = none): among the earlier keys of the
+ * span's own modality its tokens see only those less than W positions back;
+ * other modalities and the own-span term are not limited.  Attention sinks
+ * plus a sliding window (section 5.5's "lambda" pattern) are two NOBIDIR spans
+ * per sample: the sinks with one modality, the rest with another and the
+ * window.  The paper does not say how its bitfield holds this pattern; the
+ * window field is an extension of the section 4.2 word. */
 typedef struct { int64_t start, len; int32_t modality, flags; } mmattn_span;
 #define MMATTN_SPAN_NONCAUSAL 1
 #define MMATTN_SPAN_NOBIDIR   2
 #define MMATTN_SPAN_DENY_SHIFT 8   /* flags bits 8-15: modalities the span's tokens do NOT attend */
+#define MMATTN_SPAN_WINDOW_SHIFT 16 /* flags bits 16-31: look-back window over the own modality, tokens */
 #define MMATTN_MAX_SPANS   65535
 #define MMATTN_MAX_SAMPLES 65535
 #define MMATTN_MAX_BLOCKS  16384   /* nB accepted by mmattn_balance */

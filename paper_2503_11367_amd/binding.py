@@ -23,6 +23,8 @@ OP_ENCODE, OP_TILE_MAP, OP_BALANCE, OP_FWD, OP_BWD, OP_FWD_HEADS = range(6)
 TILE_EMPTY, TILE_FULL, TILE_PARTIAL = 0, 1, 2
 SPAN_NONCAUSAL = 1
 SPAN_NOBIDIR = 2
+SPAN_DENY_SHIFT = 8       # flags bits 8-15: modalities the span's tokens do not attend
+SPAN_WINDOW_SHIFT = 16    # flags bits 16-31: look-back window over the own modality, tokens
 BF16 = 0
 
 
@@ -107,8 +109,10 @@ def _workspace(nbytes: int, device) -> torch.Tensor:
 def mask_encode(spans: Sequence[Tuple[int, int, int]], sample_off: Sequence[int], S: int,
                 device="cuda", flags: Optional[Sequence[int]] = None, stream=None,
                 bits: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """mmattn_mask_encode.  spans: (start, len, modality); returns int64[S]
-    holding the 64-bit words."""
+    """mmattn_mask_encode.  spans: (start, len, modality); flags: per-span flag
+    words of the C ABI (SPAN_* bits, deny mask, look-back window; a window above
+    32767 makes the 32-bit word negative); returns int64[S] holding the 64-bit
+    words."""
     n = len(spans)
     arr = (Span * max(n, 1))()
     for i, (st, ln, mod) in enumerate(spans):

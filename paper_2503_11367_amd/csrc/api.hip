@@ -88,7 +88,9 @@ int mmattn_mask_encode(const mmattn_span* spans, int32_t n_spans, const int64_t*
         const mmattn_span& sp = spans[j];
         if (sp.len <= 0 || sp.start < prev_end || sp.start + sp.len > S) return MMATTN_ERR_LAYOUT;
         if (sp.modality < 1 || sp.modality > 7) return MMATTN_ERR_LAYOUT;     // one attend bit each
-        if (sp.flags & ~(MMATTN_SPAN_NONCAUSAL | MMATTN_SPAN_NOBIDIR | (0xFF << MMATTN_SPAN_DENY_SHIFT)))
+        if ((uint32_t)sp.flags & ~(uint32_t)(MMATTN_SPAN_NONCAUSAL | MMATTN_SPAN_NOBIDIR |
+                                             (0xFFu << MMATTN_SPAN_DENY_SHIFT) |
+                                             (0xFFFFu << MMATTN_SPAN_WINDOW_SHIFT)))
             return MMATTN_ERR_LAYOUT;
         // without the bidirectional term a token sees itself only through the
         // backward-looking term: causal bit set and own modality attended
@@ -111,7 +113,7 @@ int mmattn_tile_map(const uint64_t* d_bits, int64_t S, int32_t tq, int32_t tk, u
     if (S <= 0 || tq <= 0 || tk <= 0 || S % tq != 0 || S % tk != 0) return MMATTN_ERR_SHAPE;
     if ((int64_t)tq * tk > ((int64_t)1 << 31)) return MMATTN_ERR_SHAPE;
     if (S / tq > 65535 || S / tk > ((int64_t)1 << 24)) return MMATTN_ERR_UNSUPPORTED;
-    return launch_tile_map(d_bits, S, nullptr, 1, S, tq, tk, d_cls, d_cnt, d_rowpairs,
+    return launch_tile_map(d_bits, S, nullptr, 1, S, tq, tk, d_cls, d_cnt, d_rowpairs, nullptr,
                            (hipStream_t)stream);
 }
 

@@ -180,6 +180,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     constexpr int PER = 16 * QT::RPS, NV = PER / 8;    // transpose-read address period
     __shared__ KvSmem<D> sm;
     if (*err) return;
+    const bool windows = err[kWindowFlag] != 0;      // some query row has a look-back window
 
     // ---- work decode: chunk index slowest, then k-tile rank (longest first), KV
     // heads pinned to XCDs ------------------------------------------------------
@@ -364,7 +365,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     };
     // PARTIAL steps: rows 8*q4 + 4*hh + 0..3 (+32 per unit) of the step's mask inputs, 16 bytes per read
     const uint32_t info_addr = lds_info + hh * 16;
-    auto mask_unit = [&](floatx16& x, int imm) __attribute__((always_inline)) {
+    auto mask_with = [&](auto with_windows, floatx16& x, int imm) __attribute__((always_inline)) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const u32x4 ss = *(lds_u4)(uintptr_t)(info_addr + (uint32_t)(imm + q4 * 32));
@@ -372,8 +373,13 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             const u32x4 ps = *(lds_u4)(uintptr_t)(info_addr + (uint32_t)(imm + q4 * 32 + 8 * kKvBM));
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (!visible(ss[j], ca[j], (int64_t)ps[j], k_ss, k_mod, key)) x[q4 * 4 + j] = -INFINITY;
+                if (!visible<decltype(with_windows)::value>(ss[j], ca[j], (int64_t)ps[j], k_ss, k_mod, key))
+                    x[q4 * 4 + j] = -INFINITY;
         }
+    };
+    auto mask_unit = [&](floatx16& x, int imm) __attribute__((always_inline)) {
+        if (windows) mask_with(std::true_type{}, x, imm);      // workgroup-uniform
+        else mask_with(std::false_type{}, x, imm);
     };
     // One unit: NS slots, each one MFMA, one fragment request and a share of the
     // element-wise work (see the forward kernel).  KR: std::true_type for the K role.
@@ -854,6 +860,11 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             __builtin_amdgcn_sched_barrier(0);
         }
         if (partial) {
+            // the query-side fields are per-lane constants; passed through an empty asm so that
+            // what the predicate derives from them is computed here and not kept in registers
+            // across the whole loop
+            uint32_t qs = q_ss, qa = q_causal, qp = (uint32_t)q_pos;
+            asm volatile("" : "+v"(qs), "+v"(qa), "+v"(qp));
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -863,7 +874,9 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
-                        if (!visible(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) sv[kb][q4 * 4 + j] = -INFINITY;
+                        if (!visible<true>(qs, qa, (int64_t)qp, kw[j], km[j], k0 + kl)) sv[kb][q4 * 4 + j] = -INFINITY;
+                        // one element at a time: no register is free for a second one's temporaries
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
         }
@@ -1099,11 +1112,13 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
 
     int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
     if (rc) return rc;
-    rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kDqBM, kDqBN, pa.cls, nullptr, nullptr, st);
+    rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kDqBM, kDqBN, pa.cls, nullptr, nullptr,
+                         err + kWindowFlag, st);
     if (rc) return rc;
     rc = launch_compact_rows(pa, st);
     if (rc) return rc;
-    rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kKvBM, kKvBN, pb.cls, nullptr, nullptr, st);
+    rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kKvBM, kKvBN, pb.cls, nullptr, nullptr,
+                         nullptr, st);
     if (rc) return rc;
     rc = launch_compact_cols(pb, st);
     if (rc) return rc;

@@ -23,25 +23,50 @@ constexpr int kWave = 64;
 // Mask word fields (paper section 4.2 layout as fixed in mmattn.h).
 constexpr int kSpanShift = 12;
 constexpr int kSampleShift = 28;
+constexpr int kWindowShift = 44;
 constexpr int kCausalBit = 63;
 
 // Compact views used by the kernels.  `ss`: low 16 bits span id, next 16 bits
-// sample id; equal `ss` words mean same sample AND same span.  Query side `att`:
-// the attend-set (bits 0-7 of the word) if the causal bit is set, else 0.  Key
-// side `mod`: the token's own modality (bits 8-11).
+// sample id; equal `ss` words mean same sample AND same span.  Key side `mod`:
+// the token's own modality (bits 8-11 of the word); values above 7 have no attend
+// bit and count as 8.  Query side `att`: 0 without the causal bit, else the
+// attend-set (bits 0-7; bits 8-11 stay zero, so modality 8 is never attended), the
+// own modality (bits 12-15) and the look-back window (bits 16-31).
 __host__ __device__ inline uint32_t word_ss(uint64_t w) { return (uint32_t)(w >> kSpanShift); }
-__host__ __device__ inline uint32_t word_att(uint64_t w) {
-    return (w >> kCausalBit) ? (uint32_t)(w & 0xFFu) : 0u;
+__host__ __device__ inline uint32_t word_mod(uint64_t w) {
+    const uint32_t m = (uint32_t)(w >> 8) & 0xFu;
+    return m < 8u ? m : 8u;
 }
-__host__ __device__ inline uint32_t word_mod(uint64_t w) { return (uint32_t)(w >> 8) & 0xFu; }
+__host__ __device__ inline uint32_t word_att(uint64_t w) {
+    if (!(w >> kCausalBit)) return 0u;
+    return (uint32_t)(w & 0xFFu) | (word_mod(w) << 12) | ((uint32_t)(w >> kWindowShift) << 16);
+}
+__host__ __device__ inline uint32_t att_window(uint32_t att) { return att >> 16; }
+__host__ __device__ inline uint32_t att_modality(uint32_t att) { return (att >> 12) & 0xFu; }
 
-// vis(q,k) = same_sample && ((causal(q) && k<=q && attend(q)[modality(k)]) ||
+// vis(q,k) = same_sample && ((causal(q) && k<=q && attend(q)[modality(k)] &&
+//                             (window(q)==0 || modality(k)!=modality(q) || q-k<window(q))) ||
 //                            (span(q)!=0 && span(q)==span(k)))
+// WINDOWS = false leaves the window term out: for launches none of whose query rows has
+// a window (the usual case), where the query-side fields change per element and the
+// extra comparisons would be wasted.
+template <bool WINDOWS>
 __device__ __forceinline__ bool visible(uint32_t ss_q, uint32_t att_q, int64_t q,
                                         uint32_t ss_k, uint32_t mod_k, int64_t k) {
-    bool same_sample = (ss_q >> 16) == (ss_k >> 16);
-    bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_k;
-    return same_span || (same_sample && ((att_q >> mod_k) & 1u) && k <= q);
+    const bool same_sample = (ss_q >> 16) == (ss_k >> 16);
+    const bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_k;
+    const bool attends = (att_q >> mod_k) & 1u;
+    // positions are below 2^31, so 32-bit arithmetic serves
+    if constexpr (!WINDOWS) {
+        return same_span || (same_sample && attends && (int32_t)k <= (int32_t)q);
+    } else {
+        // k <= q  <=>  the 32-bit difference is below 2^31.  Farthest visible look-back:
+        // window - 1 for keys of the own modality (no window: 0 - 1 wraps to the maximum),
+        // unlimited otherwise
+        const uint32_t back = (uint32_t)q - (uint32_t)k;
+        const uint32_t reach = mod_k == att_modality(att_q) ? att_window(att_q) - 1u : 0x7FFFFFFFu;
+        return same_span || (same_sample && attends && back <= min(reach, 0x7FFFFFFFu));
+    }
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -59,9 +84,10 @@ int launch_mfma_ceiling(int32_t iters, int32_t random_operands, float* sink, dou
                         hipStream_t st);
 int launch_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* sample_off,
                   int32_t n_samples, int64_t S, uint64_t* d_bits, void* ws, hipStream_t st);
+// d_window_flag (may be null): set to 1 if any of the rows has a look-back window
 int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
                     int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls, uint32_t* d_cnt,
-                    uint64_t* d_rowpairs, hipStream_t st);
+                    uint64_t* d_rowpairs, int32_t* d_window_flag, hipStream_t st);
 int launch_balance(const uint64_t* d_W, int32_t nB, int32_t P, int32_t* d_rank_of_block,
                    uint64_t* d_load, int32_t* d_rank_off, int32_t* d_rank_blocks, hipStream_t st);
 

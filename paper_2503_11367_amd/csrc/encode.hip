@@ -36,6 +36,7 @@ __device__ __forceinline__ void encode_token(const DevSpan* spans, int32_t n_spa
         if (spans[a].flags & MMATTN_SPAN_NONCAUSAL) causal = 0;
         // attend-set: all modalities minus the span's deny mask (flags bits 8-15)
         w &= ~(uint64_t)((spans[a].flags >> MMATTN_SPAN_DENY_SHIFT) & 0xFF);
+        w |= (uint64_t)((uint32_t)spans[a].flags >> MMATTN_SPAN_WINDOW_SHIFT) << kWindowShift;
     }
     bits[t] = w | (causal << kCausalBit);
 }

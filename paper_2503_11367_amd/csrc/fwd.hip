@@ -45,9 +45,10 @@ struct FwdSmem {
     uint32_t kss[2][2][kFwdBN];                           // sample/span field and modality of a PARTIAL tile's keys, by tile parity
 };
 
-// HPW query heads per workgroup (4 wavefronts each), NST LDS stages.
+// HPW query heads per workgroup (4 wavefronts each), NST LDS stages; one workgroup per
+// CU at D = 128 (LDS), so HPW wavefronts per SIMD.
 template <int D, int HPW, int NST>
-__global__ void __launch_bounds__(256 * HPW, 2)
+__global__ void __launch_bounds__(256 * HPW, HPW)
 fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
            const ushort_t* __restrict__ V, const uint64_t* __restrict__ bits,
            const int32_t* __restrict__ blocks, int32_t block, int64_t n_loc, int64_t S,
@@ -225,6 +226,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     };
     // key words of rows 8*q4 + 4*hh + 0..3 (+32 per half tile), 16 bytes per read
     const uint32_t kss_a = lds_addr_of(sm.kss) + hh * 16;
+    // (the query-side parts of the predicate, window included, are per-lane constants here)
     auto mask_scores = [&](uint32_t entry, int parity, int kb, floatx16& s) __attribute__((always_inline)) {
         if (entry & kPartialFlag) {            // workgroup-uniform
             const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
@@ -236,8 +238,10 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
-                    if (!visible(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
+                    if (!visible<true>(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
                 }
+                // four elements at a time: the comparison results live in scalar registers
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
@@ -596,7 +600,7 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
         int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
         if (rc) return rc;
         rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kFwdBM, kFwdBN, plan.cls, nullptr,
-                             nullptr, st);
+                             nullptr, nullptr, st);
         if (rc) return rc;
         rc = launch_compact_rows(plan, st);
         if (rc) return rc;

@@ -8,8 +8,9 @@
 // stretches of keys with the same sample/span/modality fields: a text run, a
 // modality span); for one query row and one run the number of visible keys has
 // a closed form -- the whole run if it is the row's own span, the keys up to
-// the row's position if the row looks back at that modality in its sample,
-// else none -- so every lane takes a few rows and walks the runs.  Exact for
+// the row's position (and inside its look-back window, if it has one for that
+// modality) if the row looks back at that modality in its sample, else none --
+// so every lane takes a few rows and walks the runs.  Exact for
 // any layout; a tile whose keys all differ degenerates to one run per key.
 //
 // The same kernel serves the attention kernels' private maps: there the q rows
@@ -34,7 +35,7 @@ __global__ void __launch_bounds__(kTmThreads)
 tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
                 const int32_t* __restrict__ blocks, int32_t block, int64_t n_rows,
                 int32_t tq, int32_t tk, int32_t nk, int32_t kpw,
-                uint8_t* __restrict__ cls, uint32_t* __restrict__ cnt) {
+                uint8_t* __restrict__ cls, uint32_t* __restrict__ cnt, int32_t* __restrict__ window_flag) {
     __shared__ uint32_t q_ss[kTmQChunk];
     __shared__ uint32_t q_att[kTmQChunk];
     __shared__ int64_t q_pos[kTmQChunk];
@@ -53,6 +54,8 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
             q_pos[threadIdx.x] = p;
             q_ss[threadIdx.x] = word_ss(w);
             q_att[threadIdx.x] = word_att(w);
+            // every writer stores the same value; the attention kernels read it after this launch
+            if (window_flag && blockIdx.x == 0 && att_window(word_att(w)) != 0) *window_flag = 1;
         }
         __syncthreads();
     };
@@ -86,12 +89,16 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
                     const int64_t first = k0 + kc + a;
                     const int64_t len = b - a;
                     for (int r = lane; r < n; r += kWave) {
-                        const uint32_t ss_q = q_ss[r];
+                        const uint32_t ss_q = q_ss[r], att = q_att[r];
                         const bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_r;
-                        const bool back = (ss_q >> 16) == (ss_r >> 16) && ((q_att[r] >> mod_r) & 1u);
-                        // keys of the run at or before the row's position
+                        const bool back = (ss_q >> 16) == (ss_r >> 16) && ((att >> mod_r) & 1u);
+                        // keys of the run at or before the row's position ...
                         const int64_t upto = max((int64_t)0, min(q_pos[r] - first + 1, len));
-                        part += (uint32_t)(same_span ? len : (back ? upto : 0));
+                        // ... minus those a look-back window over the row's own modality cuts off
+                        const uint32_t win = att_window(att);
+                        const bool windowed = win != 0 && mod_r == att_modality(att);
+                        const int64_t cut = windowed ? max((int64_t)0, min(q_pos[r] - win + 1 - first, len)) : 0;
+                        part += (uint32_t)(same_span ? len : (back ? upto - cut : 0));
                     }
                 }
             }
@@ -124,7 +131,7 @@ row_pairs_kernel(const uint32_t* __restrict__ cnt, int32_t nk, uint64_t* __restr
 
 int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
                     int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls, uint32_t* d_cnt,
-                    uint64_t* d_rowpairs, hipStream_t st) {
+                    uint64_t* d_rowpairs, int32_t* d_window_flag, hipStream_t st) {
     const int64_t nq = (n_rows + tq - 1) / tq;
     const int32_t nk = (int32_t)(S / tk);
     if (nq == 0) return MMATTN_OK;
@@ -135,7 +142,7 @@ int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, 
     const int32_t per_wg = kTmWaves * kpw;
     dim3 grid((unsigned)((nk + per_wg - 1) / per_wg), (unsigned)nq);
     hipLaunchKernelGGL(tile_map_kernel, grid, dim3(kTmThreads), 0, st, d_bits, S, d_blocks, block,
-                       n_rows, tq, tk, nk, kpw, d_cls, d_cnt);
+                       n_rows, tq, tk, nk, kpw, d_cls, d_cnt, d_window_flag);
     MM_LAUNCH_CHECK();
     if (d_rowpairs) {
         hipLaunchKernelGGL(row_pairs_kernel, dim3((unsigned)nq), dim3(256), 0, st, d_cnt, nk,

@@ -57,6 +57,9 @@ def test_encode_validation():
     assert encode_rc([(8, 8, 1, 2 | 1)], [0, 64], 64) == -5                 # no bidirectional term, no causal bit
     assert encode_rc([(8, 8, 1, 2 | (2 << 8))], [0, 64], 64) == -5          # ... or own modality denied
     assert encode_rc([(8, 8, 1, 0)], [0, 64], 64, ws=0) == -4
+    # a look-back window (flags bits 16-31, here the largest) passes the layout checks
+    assert encode_rc([(8, 8, 1, 2 | (0xFFFF << 16) - (1 << 32))], [0, 64], 64, ws=0) == -4
+    assert encode_rc([(8, 8, 1, 4 | (100 << 16))], [0, 64], 64, ws=0) == -5
     assert encode_rc([(8, 8, 1, 0)], [0, 64], 64, ws_bytes=8) == -4
     assert encode_rc([(8, 8, 1, 0)], [0, 64], 64, ws=FAKE + 8) == -4        # misaligned
 

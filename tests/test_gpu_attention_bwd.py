@@ -12,7 +12,7 @@ from oracle import tilemap as ot
 from paper_2503_11367_amd import binding as mb
 from paper_2503_11367_amd import workloads as wl
 
-from gpu_util import (DEV, bf16_to_f64, f64, fields, gpu_bits, make_tensors, max_abs, rel_l2)
+from gpu_util import (DEV, bf16_to_f64, f64, fields, gpu_bits, make_tensors, max_abs, rel_l2, windows)
 
 pytestmark = pytest.mark.gpu
 
@@ -35,14 +35,15 @@ def run_case(lay, blocks, block, Hq, Hkv, D, seed):
     o, lse, dq, dk, dv = gpu_fwd_bwd(lay, blocks, block, t)
     rows = oa.rows_of_blocks(blocks, block)
     Q, K, V, dO = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"]), f64(t["do_bits"])
-    dq_ref, dk_ref, dv_ref = oa.backward(Q, K, V, dO, rows, f[0], f[1], f[2], modality=f[3], attend=f[4])
+    dq_ref, dk_ref, dv_ref = oa.backward(Q, K, V, dO, rows, f[0], f[1], f[2], modality=f[3], attend=f[4],
+                                         window=windows(lay))
     for name, got, ref in (("dq", dq, dq_ref), ("dk", dk, dk_ref), ("dv", dv, dv_ref)):
         g = bf16_to_f64(got)
         assert np.isfinite(g).all(), name
         assert rel_l2(g, ref) < TOL, (name, rel_l2(g, ref))
     # keys that no row of the share sees get exactly zero
     from oracle import mask as om
-    seen = om.visible(rows, np.arange(lay.S), f[0], f[1], f[2], f[3], f[4]).any(axis=0)
+    seen = om.visible(rows, np.arange(lay.S), f[0], f[1], f[2], f[3], f[4], windows(lay)).any(axis=0)
     assert (bf16_to_f64(dk)[~seen] == 0).all() and (bf16_to_f64(dv)[~seen] == 0).all()
 
 
@@ -53,6 +54,16 @@ def test_attend_sets(seed):
     assert any(lay.deny)
     blocks = list(range(lay.S // 64)) if seed != 1 else list(range(1, lay.S // 64, 2))
     run_case(lay, blocks, 64, Hq=2 + 2 * (seed % 2), Hkv=2, D=[128, 64, 128][seed], seed=60 + seed)
+
+
+def test_lambda_and_windowed_spans():
+    """Attention sinks plus a sliding window (section 5.5's lambda pattern) and
+    windows on bidirectional image spans."""
+    run_case(wl.layout_lambda([2048], 4, 300), list(range(16)), 128, Hq=4, Hkv=2, D=128, seed=94)
+    run_case(wl.layout_lambda([700, 324, 1024], 16, 256), [15, 3, 8, 9], 128, Hq=2, Hkv=1, D=64, seed=95)
+    lay = wl.layout_random(71, S=1024, n_samples=2, max_spans=6)
+    lay.window = [37 * (j + 1) for j in range(len(lay.spans))]
+    run_case(lay, list(range(8)), 128, Hq=2, Hkv=1, D=128, seed=97)
 
 
 def test_shared_question_and_block_causal():

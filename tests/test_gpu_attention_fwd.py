@@ -14,7 +14,7 @@ from oracle import tilemap as ot
 from paper_2503_11367_amd import binding as mb
 from paper_2503_11367_amd import workloads as wl
 
-from gpu_util import (DEV, bf16_to_f64, f64, fields, gpu_bits, make_tensors, max_abs, rel_l2)
+from gpu_util import (DEV, bf16_to_f64, f64, fields, gpu_bits, make_tensors, max_abs, rel_l2, windows)
 
 pytestmark = pytest.mark.gpu
 
@@ -42,7 +42,8 @@ def run_case(lay, blocks, block, Hq, Hkv, D, seed, heads=None, rows_sample=None)
     lse_ref = np.zeros_like(lse_gpu)
     for j, h in enumerate(hs):
         g = h // rep
-        oo, ll = oa.forward(Q[sel][:, h:h + 1], K[:, g:g + 1], V[:, g:g + 1], rows[sel], f[0], f[1], f[2], modality=f[3], attend=f[4])
+        oo, ll = oa.forward(Q[sel][:, h:h + 1], K[:, g:g + 1], V[:, g:g + 1], rows[sel], f[0], f[1], f[2],
+                            modality=f[3], attend=f[4], window=windows(lay))
         o_ref[:, j] = oo[:, 0]
         lse_ref[j] = ll[0]
     assert np.isfinite(o_gpu).all()
@@ -60,6 +61,18 @@ def test_shared_question_and_block_causal():
              Hq=4, Hkv=2, D=128, seed=81)
     run_case(wl.layout_shared_question(64, [128] * 7, n_tail=64), [7, 2, 12, 5], 64, Hq=2, Hkv=1, D=64, seed=82)
     run_case(wl.layout_block_causal(1024, 96), list(range(8)), 128, Hq=2, Hkv=2, D=128, seed=83)
+
+
+def test_lambda_and_windowed_spans():
+    """Attention sinks plus a sliding window (section 5.5's lambda pattern),
+    packed and not, window not a tile multiple; and windows on bidirectional
+    image spans (the own span stays whole)."""
+    run_case(wl.layout_lambda([2048], 4, 300), list(range(16)), 128, Hq=4, Hkv=2, D=128, seed=84)
+    run_case(wl.layout_lambda([700, 324, 1024], 16, 256), [15, 3, 8, 9], 128, Hq=2, Hkv=1, D=64, seed=85)
+    run_case(wl.layout_lambda([1024], 64, 1), list(range(0, 16, 3)), 64, Hq=2, Hkv=2, D=128, seed=86)
+    lay = wl.layout_random(71, S=1024, n_samples=2, max_spans=6)
+    lay.window = [37 * (j + 1) for j in range(len(lay.spans))]
+    run_case(lay, list(range(8)), 128, Hq=2, Hkv=1, D=128, seed=87)
 
 
 def test_tiny_every_rank_share():

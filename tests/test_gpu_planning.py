@@ -9,7 +9,7 @@ from oracle import tilemap as ot
 from paper_2503_11367_amd import binding as mb
 from paper_2503_11367_amd import workloads as wl
 
-from gpu_util import DEV, fields, gpu_bits, oracle_bits, to_np_u64
+from gpu_util import DEV, fields, gpu_bits, oracle_bits, to_np_u64, windows
 
 pytestmark = pytest.mark.gpu
 
@@ -62,7 +62,7 @@ def check_tile_map(lay, tq, tk, use_c):
     f = fields(lay)
     bits = torch.from_numpy(oracle_bits(lay).view(np.int64)).to(DEV)      # oracle-encoded input
     cls, cnt, rp = mb.tile_map(bits, tq, tk)
-    ref = (ot.tile_map_c if use_c else ot.tile_map)(f[0], f[1], f[2], tq, tk, f[3], f[4])
+    ref = (ot.tile_map_c if use_c else ot.tile_map)(f[0], f[1], f[2], tq, tk, f[3], f[4], windows(lay))
     assert np.array_equal(cls.cpu().numpy(), ref[0])
     assert np.array_equal(cnt.cpu().numpy().view(np.uint32), ref[1])
     assert np.array_equal(rp.cpu().numpy().view(np.uint64), ref[2])
@@ -103,6 +103,39 @@ def test_tile_map_many_short_runs():
     assert np.array_equal(to_np_u64(gpu_bits(lay)), oracle_bits(lay))
     for tile in ((64, 64), (128, 32), (16, 128)):
         check_tile_map(lay, tile[0], tile[1], use_c=False)
+
+
+def layouts_window():
+    """Look-back windows: attention sinks plus a sliding window (the lambda
+    pattern of section 5.5) in one sample and packed, window shorter and longer
+    than a tile, the largest window, and windows on ordinary image spans."""
+    out = [wl.layout_lambda([1024], 4, 100), wl.layout_lambda([700, 324, 1024], 16, 256),
+           wl.layout_lambda([2048], 64, 1), wl.layout_lambda([4096], 1, 65535),
+           wl.layout_lambda([3000, 1096], 130, 777)]
+    lay = wl.layout_random(71, S=1024, n_samples=2, max_spans=6)
+    lay.window = [37 * (j + 1) for j in range(len(lay.spans))]
+    out.append(lay)
+    return out
+
+
+@pytest.mark.parametrize("idx", range(6))
+def test_encode_and_tile_map_with_windows(idx):
+    lay = layouts_window()[idx]
+    assert any(lay.window)
+    assert np.array_equal(to_np_u64(gpu_bits(lay)), oracle_bits(lay))
+    for tile in ((64, 64), (128, 64), (64, 128), (16, 256)):
+        check_tile_map(lay, tile[0], tile[1], use_c=lay.S > 2048)
+
+
+def test_lambda_tile_map_is_a_band():
+    """8192 tokens, 64 sinks, window 1024: below the band only the sinks' column
+    of tiles is left, so a q-tile has at most 1 + 1024/64 + 1 active k-tiles."""
+    lay = wl.layout_lambda([8192], 64, 1024)
+    check_tile_map(lay, 128, 64, use_c=True)
+    bits = gpu_bits(lay)
+    cls, _, _ = mb.tile_map(bits, 128, 64)
+    active = (cls.cpu().numpy() != 0).sum(axis=1)
+    assert active.max() <= 1 + 1024 // 64 + 2 and active[-1] == 1 + 1024 // 64 + 2
 
 
 def test_tile_map_block_causal():
