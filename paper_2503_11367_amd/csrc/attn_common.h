@@ -231,7 +231,18 @@ struct TilePlanT {
     int32_t* qcount;     // [nk]
     uint32_t* qlist;     // [nk][nq]
     int32_t* korder;     // [nk] by qcount descending
+    // list slices (intra-GPU balancing, paper section 3.2.2, for the key-outer pass): a
+    // k-tile whose list is much longer than a CU's share of all the work is cut into
+    // slices of `slicing[kSliceLen]` entries that run as separate workgroups and write
+    // partial sums.  Chosen on the device (by the list builder) from the lists themselves.
+    int32_t n_extra;     // host: most slices beyond the first, over all k-tiles (grid, table size)
+    int32_t hc, hpc;     // host: workgroups per (k-tile, KV head, slice) and query heads of each
+    int32_t groups;      // host: workgroups that walk every list (KV heads x hc)
+    int32_t* slicing;    // [kSliceInts]: slice length, sliced k-tiles, extra slices in use
+    int32_t* pbase;      // [nk] first partial-sum slot of the k-tile, -1: written directly
+    int32_t* extra;      // [n_extra][2] (k-tile, slice index >= 1) by k-tile, then slice
 };
+constexpr int kSliceLen = 0, kSlicedTiles = 1, kExtraUsed = 2, kSliceInts = 4;
 
 // int32 words cleared by launch_validate_blocks at `err`: the error flag, the flag "some
 // query row of the share has a look-back window" (set by the tile map) and spare words;

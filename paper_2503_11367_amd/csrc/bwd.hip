@@ -164,8 +164,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
            int64_t n_loc, int64_t n_pad, int64_t S, int32_t Hq, int32_t Hkv, float scale,
            float scale_log2, const float* __restrict__ ld_g, const float* __restrict__ ldk_g,
            TilePlanT plan, KvChunking ch, const int32_t* __restrict__ err,
-           ushort_t* __restrict__ dK, ushort_t* __restrict__ dV, float* __restrict__ accK,
-           float* __restrict__ accV) {
+           ushort_t* __restrict__ dK, ushort_t* __restrict__ dV, float* __restrict__ pool) {
     constexpr int NDS = D / 16, NDB = D / 32;
     constexpr int RB = D * 2;
     using QT = SwzTile<D, 0>;
@@ -182,12 +181,13 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     if (*err) return;
     const bool windows = err[kWindowFlag] != 0;      // some query row has a look-back window
 
-    // ---- work decode: chunk index slowest, then k-tile rank (longest first), KV
-    // heads pinned to XCDs ------------------------------------------------------
+    // ---- work decode: chunk index slowest, then work item (longest first: the first
+    // slices of the sliced lists, the other slices, the unsliced lists; then the unused
+    // slice entries, which exit), KV heads pinned to XCDs ---------------------------
     const int rep = Hq / Hkv;
     int chunk, tile_rank, g;
     {
-        const int units = plan.nk * Hkv;
+        const int units = (plan.nk + plan.n_extra) * Hkv;
         const int bid = blockIdx.x;
         chunk = bid / units;
         const int u = bid - chunk * units;
@@ -200,12 +200,28 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             g = u - tile_rank * Hkv;
         }
     }
-    const int kt = plan.korder[tile_rank];
-    const int n_q = plan.qcount[kt];
-    const bool shared_unit = ch.cmax > 1;              // several workgroups per unit: fp32 partials, summed later
+    int kt, slice = 0;
+    {
+        const int sliced = plan.slicing[kSlicedTiles], used = plan.slicing[kExtraUsed];
+        if (tile_rank < sliced) {
+            kt = plan.korder[tile_rank];
+        } else if (tile_rank < sliced + used) {
+            kt = plan.extra[2 * (tile_rank - sliced)];
+            slice = plan.extra[2 * (tile_rank - sliced) + 1];
+        } else if (tile_rank < plan.nk + used) {
+            kt = plan.korder[tile_rank - used];
+        } else {
+            return;                                    // workgroup-uniform
+        }
+    }
+    const int slice_len = plan.slicing[kSliceLen];
+    const int first = slice * slice_len;               // this workgroup's part of the k-tile's list
+    const int n_q = max(0, min(slice_len, plan.qcount[kt] - first));
+    const int slot0 = plan.pbase[kt];
+    const bool shared_unit = slot0 >= 0;               // several workgroups per unit: fp32 partials, summed later
     const int n_steps = n_q * ch.hpc;                  // 0 (no query sees these keys): writes zeros
     const int head0 = g * rep + chunk * ch.hpc;        // first query head of this workgroup
-    const uint32_t* qlist = plan.qlist + (int64_t)kt * plan.nq;
+    const uint32_t* qlist = plan.qlist + (int64_t)kt * plan.nq + first;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -613,8 +629,10 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     const int64_t obase = (key * Hkv + g) * (int64_t)D + 4 * hh;
     const float osc = k_role ? scale : 1.0f;
     if (shared_unit) {
-        // this workgroup's partial sums, fp32, in its own slice [chunk][S][Hkv][D]
-        float* dst = (k_role ? accK : accV) + (int64_t)chunk * S * Hkv * D + obase;
+        // this workgroup's partial sums, fp32, in its own slot: dK [128][Hkv][D], then dV
+        const int64_t tile_elems = (int64_t)kKvBN * Hkv * D;
+        float* dst = pool + ((int64_t)(slot0 + slice * ch.cmax + chunk) * 2 + (k_role ? 0 : 1)) * tile_elems +
+                     ((int64_t)(kblk * 32 + li) * Hkv + g) * D + 4 * hh;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -638,25 +656,47 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     }
 }
 
-// sum the per-workgroup fp32 partials of every (k-tile, KV head) unit in a fixed
-// order and write bf16; 4 elements per thread
+// sum the fp32 partials of every k-tile that several workgroups worked on (slices of
+// its list, chunks of a KV group's query heads) in a fixed order and write bf16.
+// grid (k-tile, part of the tile); kRedIt x 4 elements per thread
+constexpr int kRedIt = 1;
+constexpr int kRedPerWg = 256 * 4 * kRedIt;
 __global__ void __launch_bounds__(256)
-dkv_reduce_kernel(int32_t cmax, int64_t n_elems, const int32_t* __restrict__ err,
-                  const float* __restrict__ accK, const float* __restrict__ accV,
-                  ushort_t* __restrict__ dK, ushort_t* __restrict__ dV) {
+dkv_reduce_kernel(TilePlanT plan, int32_t Hkv, int32_t D, const int32_t* __restrict__ err,
+                  const float* __restrict__ pool, ushort_t* __restrict__ dK, ushort_t* __restrict__ dV) {
     if (*err) return;
-    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (e >= n_elems) return;
-    floatx4 a = *(const floatx4*)(accK + e), b = *(const floatx4*)(accV + e);
-    for (int c = 1; c < cmax; ++c) {
-        a += *(const floatx4*)(accK + c * n_elems + e);
-        b += *(const floatx4*)(accV + c * n_elems + e);
-    }
-    bf16x4 oa, ob;
+    const int kt = blockIdx.x;
+    const int slot0 = plan.pbase[kt];
+    if (slot0 < 0) return;                             // written directly by its one workgroup
+    const int c = plan.slicing[kSliceLen];
+    const int slots = max(1, (plan.qcount[kt] + c - 1) / c) * plan.hc;
+    const int64_t tile_elems = (int64_t)kKvBN * Hkv * D;
+    const float* src = pool + (int64_t)slot0 * 2 * tile_elems;
+    // tile_elems = 128 * Hkv * D is a multiple of kRedPerWg (D >= 64), so no bounds test
+    floatx4 a[kRedIt], b[kRedIt];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) { oa[u] = (__bf16)a[u]; ob[u] = (__bf16)b[u]; }
-    *(u32x2*)(dK + e) = __builtin_bit_cast(u32x2, oa);
-    *(u32x2*)(dV + e) = __builtin_bit_cast(u32x2, ob);
+    for (int it = 0; it < kRedIt; ++it) {
+        const int64_t e = (int64_t)blockIdx.y * kRedPerWg + (it * 256 + threadIdx.x) * 4;
+        a[it] = *(const floatx4*)(src + e) + *(const floatx4*)(src + 2 * tile_elems + e);
+        b[it] = *(const floatx4*)(src + tile_elems + e) + *(const floatx4*)(src + 3 * tile_elems + e);
+    }
+    for (int s = 2; s < slots; ++s)
+#pragma unroll
+        for (int it = 0; it < kRedIt; ++it) {
+            const int64_t e = (int64_t)blockIdx.y * kRedPerWg + (it * 256 + threadIdx.x) * 4;
+            a[it] += *(const floatx4*)(src + (int64_t)s * 2 * tile_elems + e);
+            b[it] += *(const floatx4*)(src + ((int64_t)s * 2 + 1) * tile_elems + e);
+        }
+#pragma unroll
+    for (int it = 0; it < kRedIt; ++it) {
+        const int64_t e = (int64_t)blockIdx.y * kRedPerWg + (it * 256 + threadIdx.x) * 4;
+        bf16x4 oa, ob;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { oa[u] = (__bf16)a[it][u]; ob[u] = (__bf16)b[it][u]; }
+        const int64_t o = (int64_t)kt * tile_elems + e;
+        *(u32x2*)(dK + o) = __builtin_bit_cast(u32x2, oa);
+        *(u32x2*)(dV + o) = __builtin_bit_cast(u32x2, ob);
+    }
 }
 
 // ---------------------------------------------------------------- dQ ---------
@@ -1009,8 +1049,8 @@ dq_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int64_t n_pad, i
 // ---------------------------------------------------------------- host -------
 struct BwdLayout {
     size_t err, clean_blocks, ld, ldk, qh, doh, cls_a, kcount, klist, qorder, cls_b, qcount, qlist,
-        korder, acc_k, acc_v, dq_part, total;
-    int32_t nq_a, nk_a, nq_b, nk_b;
+        korder, slicing, pbase, extra, pool, dq_part, total;
+    int32_t nq_a, nk_a, nq_b, nk_b, n_extra;
     int64_t n_pad;
     KvChunking ch;
     FwdSplit split;                   // list slices of the query-outer (dQ) pass
@@ -1056,9 +1096,17 @@ static BwdLayout bwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     L.qcount = take((size_t)L.nk_b * 4);
     L.qlist = take((size_t)L.nq_b * L.nk_b * 4);
     L.korder = take((size_t)L.nk_b * 4);
-    const size_t acc = L.ch.cmax > 1 ? (size_t)L.ch.cmax * S * Hkv * D * 4 : 0;
-    L.acc_k = take(acc);
-    L.acc_v = take(acc);
+    // list slices of the key-outer pass: none for short lists; else as many extra slices as
+    // bring the launch to about 2048 workgroups, at most 256
+    L.n_extra = L.nq_b >= 16 ? std::min(256, 2048 / (Hkv * L.ch.cmax)) : 0;
+    L.slicing = take(kSliceInts * 4);
+    L.pbase = take((size_t)L.nk_b * 4);
+    L.extra = take((size_t)std::max(L.n_extra, 1) * 8);
+    // partial-sum slots: every k-tile's workgroups when the heads are chunked, else the sliced
+    // k-tiles' first slices (at most one per extra slice); plus the extra slices
+    const size_t slots = (L.ch.cmax > 1 ? (size_t)L.nk_b * L.ch.cmax : (size_t)std::min(L.nk_b, L.n_extra)) +
+                         (size_t)L.n_extra * L.ch.cmax;
+    L.pool = take(slots * 2 * kKvBN * Hkv * D * 4);
     L.split = list_split(L.nq_a, L.nk_a, Hq);          // dq_kernel: one workgroup per (q-tile, head)
     L.dq_part = take(L.split.cmax > 1 ? (size_t)L.split.cmax * L.n_pad * Hq * D * 4 : 0);
     L.total = off;
@@ -1093,8 +1141,7 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     float* ldk = (float*)(base + L.ldk);
     ushort_t* qh = (ushort_t*)(base + L.qh);
     ushort_t* doh = (ushort_t*)(base + L.doh);
-    float* acc_k = (float*)(base + L.acc_k);
-    float* acc_v = (float*)(base + L.acc_v);
+    float* pool = (float*)(base + L.pool);
     TilePlan pa;
     pa.nq = L.nq_a; pa.nk = L.nk_a; pa.tq = kDqBM; pa.tk = kDqBN;
     pa.cls = (uint8_t*)(base + L.cls_a);
@@ -1109,6 +1156,10 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     pb.qcount = (int32_t*)(base + L.qcount);
     pb.qlist = (uint32_t*)(base + L.qlist);
     pb.korder = (int32_t*)(base + L.korder);
+    pb.n_extra = L.n_extra; pb.hc = L.ch.cmax; pb.hpc = L.ch.hpc; pb.groups = a.Hkv * L.ch.cmax;
+    pb.slicing = (int32_t*)(base + L.slicing);
+    pb.pbase = (int32_t*)(base + L.pbase);
+    pb.extra = (int32_t*)(base + L.extra);
 
     int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
     if (rc) return rc;
@@ -1132,17 +1183,17 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     }
     const int rep = a.Hq / a.Hkv;
     stage_begin(MMATTN_STAGE_DKV, st);
-    hipLaunchKernelGGL(dkv_kernel<D>, dim3((unsigned)((int64_t)L.nk_b * a.Hkv * L.ch.cmax)),
+    hipLaunchKernelGGL(dkv_kernel<D>, dim3((unsigned)((int64_t)(L.nk_b + L.n_extra) * a.Hkv * L.ch.cmax)),
                        dim3(kKvThreads), 0, st, (const ushort_t*)qh, (const ushort_t*)a.k,
                        (const ushort_t*)a.v, (const ushort_t*)doh, a.bits, clean, a.block, n_loc,
                        L.n_pad, a.S, a.Hq, a.Hkv, a.scale, scale_log2, ld, ldk, pb, L.ch, err,
-                       (ushort_t*)dk, (ushort_t*)dv, acc_k, acc_v);
+                       (ushort_t*)dk, (ushort_t*)dv, pool);
     stage_end(MMATTN_STAGE_DKV, st);
-    if (L.ch.cmax > 1) {
-        const int64_t n_elems = a.S * a.Hkv * D;
+    if (L.ch.cmax > 1 || L.n_extra > 0) {
+        const int64_t tile_elems = (int64_t)kKvBN * a.Hkv * D;
         stage_begin(MMATTN_STAGE_DKV_REDUCE, st);
-        hipLaunchKernelGGL(dkv_reduce_kernel, dim3((unsigned)((n_elems / 4 + 255) / 256)), dim3(256), 0,
-                           st, L.ch.cmax, n_elems, err, acc_k, acc_v, (ushort_t*)dk, (ushort_t*)dv);
+        hipLaunchKernelGGL(dkv_reduce_kernel, dim3((unsigned)L.nk_b, (unsigned)(tile_elems / kRedPerWg)),
+                           dim3(256), 0, st, pb, a.Hkv, D, err, (const float*)pool, (ushort_t*)dk, (ushort_t*)dv);
         stage_end(MMATTN_STAGE_DKV_REDUCE, st);
     }
     // One query head per workgroup of four wavefronts and a two-stage ring: two such

@@ -61,16 +61,142 @@ compact_kernel(const uint8_t* __restrict__ cls, int32_t n_lines, int32_t n_items
     if (lane == 0) count[line] = base;
 }
 
+// Slices of the key-outer lists.  One workgroup.
+//   Slice length: the whole list (no slicing) unless the longest list's steps exceed half
+//   of one CU's share of all steps; then a quarter of that share, at least 8 entries,
+//   doubled until the slices beyond each list's first fit the table (`budget` entries).
+//   pbase[kt]: first partial-sum slot of k-tile kt (slots per k-tile: slices x hc), or -1
+//   when a single workgroup owns the k-tile's result and writes it directly.
+//   extra[]: (k-tile, slice) of every slice beyond a list's first, by k-tile index; the
+//   number of entries in use is slicing[kExtraUsed].
+// Called by all threads of one workgroup of kSliceThreads.
+constexpr int kSliceThreads = 256;
+struct ColSlicing {
+    int32_t hpc, hc, groups, budget;
+    int32_t *slicing, *pbase, *extra;      // slicing == nullptr: no slicing wanted (row lists)
+};
+__device__ void slice_cols(const int32_t* __restrict__ count, int32_t nk, int32_t nq, const ColSlicing cs) {
+    const int32_t hpc = cs.hpc, hc = cs.hc, groups = cs.groups, budget = cs.budget;
+    int32_t* __restrict__ slicing = cs.slicing;
+    int32_t* __restrict__ pbase = cs.pbase;
+    int32_t* __restrict__ extra = cs.extra;
+    constexpr int kWaves = kSliceThreads / kWave;
+    __shared__ int64_t tot_s[kWaves];
+    __shared__ int32_t max_s[kWaves], scan_s[kWaves];
+    __shared__ int32_t csz_s, base_s, sliced_s;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    // workgroup sum and maximum: shuffles inside a wavefront, then one LDS exchange
+    auto sum_and_max = [&](int64_t v, int32_t m, int64_t& total, int32_t& longest) {
+        for (int off = kWave / 2; off > 0; off >>= 1) {
+            v += __shfl_xor(v, off);
+            m = max(m, __shfl_xor(m, off));
+        }
+        __syncthreads();                               // earlier readers of tot_s / max_s are done
+        if (lane == 0) { tot_s[wave] = v; max_s[wave] = m; }
+        __syncthreads();
+        total = 0; longest = 0;
+        for (int w = 0; w < kWaves; ++w) { total += tot_s[w]; longest = max(longest, max_s[w]); }
+    };
+    // exclusive prefix sum over the workgroup's threads, continued from base_s
+    auto scan_step = [&](int32_t v) -> int32_t {
+        int32_t inc = v;                               // inclusive scan inside the wavefront
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int32_t up = __shfl_up(inc, off);
+            if (lane >= off) inc += up;
+        }
+        __syncthreads();                               // earlier readers of scan_s / base_s are done
+        if (lane == kWave - 1) scan_s[wave] = inc;
+        __syncthreads();
+        int32_t before = base_s + inc - v, all = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            if (w < wave) before += scan_s[w];
+            all += scan_s[w];
+        }
+        __syncthreads();
+        if (tid == 0) base_s += all;
+        __syncthreads();
+        return before;
+    };
+
+    int64_t v = 0, total;
+    int32_t m = 0, longest;
+    for (int b = tid; b < nk; b += kSliceThreads) { v += count[b]; m = max(m, count[b]); }
+    sum_and_max(v, m, total, longest);
+    if (tid == 0) {
+        const int64_t share = total * hpc * groups / 256;          // steps per CU
+        int64_t c = max(nq, 1);
+        if (budget > 0 && (int64_t)longest * hpc * 2 > share) c = max((int64_t)8, share / (4 * hpc));
+        csz_s = (int32_t)min(c, (int64_t)max(nq, 1));
+    }
+    __syncthreads();
+    if (csz_s >= longest) {
+        // nothing is sliced (the usual case): every k-tile has hc workgroups, closed forms
+        for (int b = tid; b < nk; b += kSliceThreads) pbase[b] = hc > 1 ? b * hc : -1;
+        if (tid == 0) {
+            slicing[kSliceLen] = csz_s;
+            slicing[kSlicedTiles] = 0;
+            slicing[kExtraUsed] = 0;
+        }
+        return;                                                    // workgroup-uniform
+    }
+    for (int round = 0; round < 32; ++round) {                     // workgroup-uniform loop
+        const int32_t c = csz_s;
+        int64_t need = 0, need_all;
+        int32_t unused;
+        for (int b = tid; b < nk; b += kSliceThreads) need += max(0, (count[b] + c - 1) / c - 1);
+        sum_and_max(need, 0, need_all, unused);
+        if (need_all <= budget) break;
+        if (tid == 0) csz_s = (int32_t)min((int64_t)c * 2, (int64_t)max(nq, 1));
+        __syncthreads();
+    }
+    const int32_t c = csz_s;
+    // partial-sum slots, k-tiles in index order
+    if (tid == 0) base_s = 0;
+    __syncthreads();
+    for (int b0 = 0; b0 < nk; b0 += kSliceThreads) {
+        const int b = b0 + tid;
+        const int32_t pieces = b < nk ? max(1, (count[b] + c - 1) / c) * hc : 0;
+        const int32_t slots = pieces > 1 ? pieces : 0;
+        const int32_t before = scan_step(slots);
+        if (b < nk) pbase[b] = slots ? before : -1;
+    }
+    // slices beyond the first
+    if (tid == 0) { base_s = 0; sliced_s = 0; }
+    __syncthreads();
+    int32_t sliced = 0;
+    for (int r0 = 0; r0 < nk; r0 += kSliceThreads) {
+        const int kt = r0 + tid;
+        const int32_t more = kt < nk ? max(0, (count[kt] + c - 1) / c - 1) : 0;
+        const int32_t before = scan_step(more);
+        for (int32_t s = 0; s < more; ++s)
+            if (before + s < budget) {                             // always true after the loop above
+                extra[2 * (before + s)] = kt;
+                extra[2 * (before + s) + 1] = s + 1;
+            }
+        sliced += more > 0 ? 1 : 0;
+    }
+    atomicAdd(&sliced_s, sliced);
+    __syncthreads();
+    const int32_t used = min(base_s, budget);                      // entries past `used` are never read
+    if (tid == 0) {
+        slicing[kSliceLen] = c;
+        slicing[kSlicedTiles] = sliced_s;
+        slicing[kExtraUsed] = used;
+    }
+}
+
 // Ranks the lines: order[rank] = line, by (count descending, line ascending), so that
 // heavy lines are scheduled first.  One thread per line; every thread counts the lines
 // that precede its own, reading the counts through LDS in chunks (all lanes the same
 // address: a broadcast).  Workgroup 0 also derives the slice length for cutting the
 // lists (csz_out, may be null) from the total, the longest and the non-empty lists.
 constexpr int kRankThreads = 256;
+static_assert(kRankThreads == kSliceThreads, "slice_cols runs in the ranking kernel's first workgroup");
 constexpr int kRankChunk = 2048;
 __global__ void __launch_bounds__(kRankThreads)
 rank_lines_kernel(const int32_t* __restrict__ count, int32_t n_lines, int32_t n_items,
-                  int32_t* __restrict__ order, int32_t* __restrict__ csz_out, int32_t groups) {
+                  int32_t* __restrict__ order, int32_t* __restrict__ csz_out, int32_t groups,
+                  const ColSlicing cs) {
     __shared__ __attribute__((aligned(16))) int32_t cnt_s[kRankChunk];
     const int tid = threadIdx.x;
     const int a = blockIdx.x * kRankThreads + tid;
@@ -115,16 +241,17 @@ rank_lines_kernel(const int32_t* __restrict__ count, int32_t n_lines, int32_t n_
         }
         if (tid == 0) *csz_out = slice_length(tot_s[0], max_s[0], num_s[0], groups, n_items);
     }
+    if (cs.slicing && blockIdx.x == 0) slice_cols(count, n_lines, n_items, cs);    // workgroup-uniform
 }
 
 static int launch_lists(const uint8_t* cls, int32_t n_lines, int32_t n_items, int64_t line_stride,
                         int64_t item_stride, int32_t* count, uint32_t* list, int32_t* order,
-                        int32_t* csz_out, int32_t groups, hipStream_t st) {
+                        int32_t* csz_out, int32_t groups, const ColSlicing& cs, hipStream_t st) {
     hipLaunchKernelGGL(compact_kernel, dim3(n_lines), dim3(64), 0, st, cls, n_lines, n_items,
                        line_stride, item_stride, count, list);
     hipLaunchKernelGGL(rank_lines_kernel, dim3((n_lines + kRankThreads - 1) / kRankThreads),
                        dim3(kRankThreads), 0, st, (const int32_t*)count, n_lines, n_items, order,
-                       csz_out, groups);
+                       csz_out, groups, cs);
     MM_LAUNCH_CHECK();
     return MMATTN_OK;
 }
@@ -150,12 +277,13 @@ int launch_zero_kv(void* dk, void* dv, size_t bytes_each, hipStream_t st) {
 
 int launch_compact_rows(const TilePlan& p, hipStream_t st) {
     return launch_lists(p.cls, p.nq, p.nk, (int64_t)p.nk, (int64_t)1, p.kcount, p.klist, p.qorder,
-                        p.csz, p.groups, st);
+                        p.csz, p.groups, ColSlicing{0, 0, 0, 0, nullptr, nullptr, nullptr}, st);
 }
 
 int launch_compact_cols(const TilePlanT& p, hipStream_t st) {
     return launch_lists(p.cls, p.nk, p.nq, (int64_t)1, (int64_t)p.nk, p.qcount, p.qlist, p.korder,
-                        nullptr, 1, st);
+                        nullptr, 1, ColSlicing{p.hpc, p.hc, p.groups, p.n_extra, p.slicing, p.pbase, p.extra},
+                        st);
 }
 
 }  // namespace mm

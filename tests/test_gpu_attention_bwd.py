@@ -66,6 +66,47 @@ def test_lambda_and_windowed_spans():
     run_case(lay, list(range(8)), 128, Hq=2, Hkv=1, D=128, seed=97)
 
 
+def test_long_key_lists_cut_into_slices():
+    """Sinks that every later row attends make one k-tile's list of query tiles
+    far longer than the others: the key-outer pass cuts long lists into slices
+    (separate workgroups, partial sums added in a fixed order).  Here the sink
+    tile has 64 entries and is cut into 8 slices, the band tiles into 2."""
+    run_case(wl.layout_lambda([4096], 32, 512), list(range(32)), 128, Hq=1, Hkv=1, D=64, seed=98)
+    # a share that is not the whole sequence, two heads per group
+    run_case(wl.layout_lambda([2048, 2048], 8, 200), list(range(3, 32)), 128, Hq=2, Hkv=1, D=128, seed=99)
+
+
+def test_lambda_8k_sampled():
+    """8192 tokens, 8 / 2 heads, 32 sinks, window 256: dQ of sampled rows, the
+    column sums of dV, and dK / dV of one 64-key block inside the band, which
+    only the next 64 + 256 rows see (the oracle on exactly those rows)."""
+    S, n_sink, W, Hq, Hkv, D = 8192, 32, 256, 8, 2, 128
+    lay = wl.layout_lambda([S], n_sink, W)
+    f, win = fields(lay), windows(lay)
+    blocks = list(range(S // 128))
+    t = make_tensors(77, S, S, Hq, Hkv, D)
+    _, _, dq, dk, dv = gpu_fwd_bwd(lay, blocks, 128, t)
+    Q, K, V, dO = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"]), f64(t["do_bits"])
+    rows = np.arange(S)
+    sel = np.sort(np.random.default_rng(2).choice(S, size=24, replace=False))
+    for h in (0, 7):
+        g = h // (Hq // Hkv)
+        dq_ref, _, _ = oa.backward(Q[sel][:, h:h + 1], K[:, g:g + 1], V[:, g:g + 1], dO[sel][:, h:h + 1],
+                                   rows[sel], f[0], f[1], f[2], modality=f[3], attend=f[4], window=win)
+        assert rel_l2(bf16_to_f64(dq[torch.from_numpy(sel).to(DEV)][:, h:h + 1]), dq_ref) < TOL
+    dv_sum = dv.float().sum(dim=0).cpu().numpy().astype(np.float64)
+    ref = dO.reshape(S, Hkv, Hq // Hkv, D).sum(axis=(0, 2))
+    assert np.abs(dv_sum - ref).max() < 2e-2 * np.abs(ref).max() + 0.5
+    k0, g = 5000, 1
+    seers = np.arange(k0, k0 + 64 + W)                 # every row that sees a key of the block
+    hs = slice(g * (Hq // Hkv), (g + 1) * (Hq // Hkv))
+    _, dk_ref, dv_ref = oa.backward(Q[seers][:, hs], K[:, g:g + 1], V[:, g:g + 1], dO[seers][:, hs], seers,
+                                    f[0], f[1], f[2], modality=f[3], attend=f[4], window=win)
+    blk = slice(k0, k0 + 64)
+    assert rel_l2(bf16_to_f64(dk[blk, g:g + 1]), dk_ref[blk]) < TOL
+    assert rel_l2(bf16_to_f64(dv[blk, g:g + 1]), dv_ref[blk]) < TOL
+
+
 def test_shared_question_and_block_causal():
     """Two patterns named in section 5.5: answers that see the question and
     themselves only (spans without the bidirectional term), and blocks that are
