@@ -69,6 +69,7 @@ struct SwzTile {
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef shortx4 __attribute__((address_space(3))) * lds_s4;
 typedef const u32x4 __attribute__((address_space(3))) * lds_u4;
+typedef const uint32_t __attribute__((address_space(3))) * lds_u1;
 
 // Per-lane LDS byte offsets of MFMA operand fragments inside a SwzTile, computed
 // once.  The rotation repeats every 16 super-rows, so row offsets that are

@@ -69,6 +69,31 @@ __device__ __forceinline__ bool visible(uint32_t ss_q, uint32_t att_q, int64_t q
     }
 }
 
+// A stretch of n consecutive keys, the first at position k_first, that all carry the
+// fields (ss_k, mod_k): the keys a query sees among them are one contiguous range (the whole
+// stretch for its own span; else the keys up to its position, from the start of its
+// look-back window on, if it looks back at that modality in its sample).  Key index idx in
+// 0..n-1 is visible iff (uint32_t)(idx - lo) <= last; an empty range has lo far past n.
+struct KeyRange {
+    uint32_t lo, last;
+    __device__ __forceinline__ bool sees(uint32_t idx) const { return idx - lo <= last; }
+    __device__ __forceinline__ bool all_of(int n) const { return lo == 0u && last == (uint32_t)(n - 1); }
+};
+__device__ __forceinline__ KeyRange visible_range(uint32_t ss_q, uint32_t att_q, int32_t q, uint32_t ss_k,
+                                                  uint32_t mod_k, int32_t k_first, int32_t n) {
+    const bool same_sample = (ss_q >> 16) == (ss_k >> 16);
+    const bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_k;
+    const bool attends = (att_q >> mod_k) & 1u;
+    const int32_t rel = q - k_first;                       // index of the last key at or before the query
+    const int32_t win = (int32_t)att_window(att_q);
+    const bool windowed = win != 0 && mod_k == att_modality(att_q);
+    int32_t hi = same_sample && attends ? min(rel, n - 1) : -1;
+    int32_t lo = windowed ? max(rel - win + 1, 0) : 0;
+    if (same_span) { lo = 0; hi = n - 1; }
+    const bool empty = hi < lo;
+    return KeyRange{empty ? 0x40000000u : (uint32_t)lo, empty ? 0u : (uint32_t)(hi - lo)};
+}
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Global token position of local row r of a rank share (blocks == nullptr:

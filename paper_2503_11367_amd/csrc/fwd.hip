@@ -230,6 +230,25 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     auto mask_scores = [&](uint32_t entry, int parity, int kb, floatx16& s) __attribute__((always_inline)) {
         if (entry & kPartialFlag) {            // workgroup-uniform
             const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
+            // Usually the 32 keys of the half tile are one run of equal mask fields: then every
+            // row sees one contiguous range of them, found once per row, and an element costs a
+            // subtraction and a comparison; wavefronts whose rows see all 32 keys do nothing.
+            const uint32_t ka = lds_addr_of(sm.kss) + (uint32_t)(parity * (8 * kFwdBN) + (kb * 32 + li) * 4);
+            const uint32_t ss_k = *(lds_u1)(uintptr_t)ka, mod_k = *(lds_u1)(uintptr_t)(ka + 4 * kFwdBN);
+            const uint32_t ss0 = __builtin_amdgcn_readfirstlane(ss_k), mod0 = __builtin_amdgcn_readfirstlane(mod_k);
+            if (__all(ss_k == ss0 && mod_k == mod0)) {       // wave-uniform
+                const KeyRange r = visible_range(q_ss, q_causal, (int32_t)q_pos, ss0, mod0,
+                                                 (int32_t)k0 + kb * 32, 32);
+                if (!__all(r.all_of(32))) {
+                    const uint32_t first = 4u * hh;          // key index of this lane's element (q4, j) = (0, 0)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (!r.sees(first + (uint32_t)(8 * q4 + j))) s[q4 * 4 + j] = -INFINITY;
+                }
+                return;
+            }
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 const uint32_t a = kss_a + (uint32_t)(parity * (8 * kFwdBN) + kb * 128 + q4 * 32);

@@ -231,6 +231,20 @@ def layout_lambda(sample_lens: List[int], n_sink: int, window: int) -> Layout:
     return Layout(off[-1], spans, off, nobidir=[1] * len(spans), window=win)
 
 
+def layout_short_spans(seed: int, S: int = 1024) -> Layout:
+    """Hundreds of spans of 1-3 tokens with alternating modalities, random deny
+    masks and 0-2 text tokens between them: nearly every key starts a new run of
+    equal mask fields."""
+    rng = np.random.default_rng(seed)
+    spans, deny, pos = [], [], 1
+    while pos + 8 < S:
+        n = int(rng.integers(1, 4))
+        spans.append((pos, n, 1 + len(spans) % 3))
+        deny.append(int(rng.integers(0, 2)) << int(rng.integers(0, 4)))
+        pos += n + int(rng.integers(0, 3))
+    return Layout(S, spans, [0, S], deny=deny)
+
+
 def layout_block_causal(S: int, block: int) -> Layout:
     """Causal blockwise pattern read from its name: bidirectional inside each
     block of `block` tokens, causal across blocks (every block is a span)."""

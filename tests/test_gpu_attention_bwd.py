@@ -107,6 +107,11 @@ def test_lambda_8k_sampled():
     assert rel_l2(bf16_to_f64(dv[blk, g:g + 1]), dv_ref[blk]) < TOL
 
 
+def test_many_short_spans():
+    """Nearly every key (and row) starts a new run of mask fields."""
+    run_case(wl.layout_short_spans(18), list(range(8)), 128, Hq=2, Hkv=1, D=128, seed=93)
+
+
 def test_shared_question_and_block_causal():
     """Two patterns named in section 5.5: answers that see the question and
     themselves only (spans without the bidirectional term), and blocks that are

@@ -75,6 +75,18 @@ def test_lambda_and_windowed_spans():
     run_case(lay, list(range(8)), 128, Hq=2, Hkv=1, D=128, seed=87)
 
 
+def test_many_short_spans():
+    """Nearly every key starts a new run of mask fields, so the half tiles take
+    the element-by-element path of the masking code; the long text tail after
+    position 600 takes the one-run path."""
+    lay = wl.layout_short_spans(17)
+    lay.spans = [s for s in lay.spans if s[0] < 600]
+    lay.deny, lay.noncausal = lay.deny[:len(lay.spans)], lay.noncausal[:len(lay.spans)]
+    lay.nobidir, lay.window = lay.nobidir[:len(lay.spans)], lay.window[:len(lay.spans)]
+    run_case(lay, list(range(8)), 128, Hq=2, Hkv=1, D=128, seed=88)
+    run_case(wl.layout_short_spans(18), [1, 2, 5, 7], 128, Hq=2, Hkv=2, D=64, seed=89)
+
+
 def test_tiny_every_rank_share():
     w = wl.workload(1)
     f = fields(w.layout)
