@@ -200,6 +200,9 @@ def main():
     ap.add_argument("--path-only", action="store_true",
                     help="skip the side reports (imbalance of the other workloads, matrix-pipe "
                          "ceiling, staged forward) so that a profiler sees the timed path only")
+    ap.add_argument("--all-stage-events", action="store_true",
+                    help="bracket all four main kernels with events inside the timed region "
+                         "(default: only the dominant one; the others are timed in a second pass)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a known-size kernel "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -274,18 +277,33 @@ def main():
             a.record(); b.record()             # materialise the handles
     torch.cuda.synchronize()
 
+    # Timed region: only the dominant kernel (the key-outer backward pass, 8 of the 14
+    # contractions) is bracketed by events; every event record costs a few microseconds on
+    # the stream.  The other kernels are timed in a second, untimed pass of the same steps.
+    timed = stages if args.all_stage_events else {"dkv": stages["dkv"]}
     t0 = time.perf_counter()
     for i in range(args.steps):
-        for n, sid in stages.items():
+        for n, sid in timed.items():
             mb.stage_events(sid, evs[n][i][0].cuda_event, evs[n][i][1].cuda_event)
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for sid in stages.values():
         mb.stage_events(sid, 0, 0)
-
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = {n: float(np.mean([a.elapsed_time(b) for a, b in evs[n]])) for n in stages}
+    kern_ms = {n: float(np.mean([a.elapsed_time(b) for a, b in evs[n]])) for n in timed}
+    if not args.all_stage_events:
+        n2 = min(args.steps, 5)
+        for i in range(n2):
+            for n, sid in stages.items():
+                mb.stage_events(sid, evs[n][i][0].cuda_event, evs[n][i][1].cuda_event)
+            step()
+        torch.cuda.synchronize()
+        for sid in stages.values():
+            mb.stage_events(sid, 0, 0)
+        for n in stages:
+            if n not in kern_ms:
+                kern_ms[n] = float(np.mean([a.elapsed_time(b) for a, b in evs[n][:n2]]))
     flops_fwd = 4.0 * w.D * w.Hq * pairs
     flops_bwd = 10.0 * w.D * w.Hq * pairs
     value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
@@ -296,10 +314,12 @@ def main():
     kname = {"fwd": "fwd_kernel", "dkv": "dkv_kernel", "dq": "dq_kernel"}
     bwd_ms = kern_ms["dkv"] + kern_ms["dkv_reduce"] + kern_ms["dq"]
     dom = max(alg, key=lambda n: kern_ms[n])
+    dom_in_timed_region = dom in timed
     achieved = alg[dom] / (kern_ms[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": kname[dom], "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, kname[dom])), "avg_ms": kern_ms[dom]}
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, kname[dom])), "avg_ms": kern_ms[dom],
+                "events_in_timed_region": dom_in_timed_region}
 
     out = {
         "metric": "masked-attention effective TFLOP/s (unmasked pairs) fwd+bwd",
