@@ -252,6 +252,7 @@ constexpr int kWindowFlag = 1;
 constexpr int kFlagInts = 4;
 int launch_compact_rows(const TilePlan& p, hipStream_t st);
 int launch_compact_cols(const TilePlanT& p, hipStream_t st);
+int launch_compact_both(const TilePlan& pa, const TilePlanT& pb, hipStream_t st);
 int launch_validate_blocks(const int32_t* blocks, int32_t n_blocks, int64_t n_seq_blocks,
                            int32_t* clean, int32_t* err, hipStream_t st);
 

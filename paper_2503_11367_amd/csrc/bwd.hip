@@ -1163,15 +1163,11 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
 
     int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
     if (rc) return rc;
-    rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kDqBM, kDqBN, pa.cls, nullptr, nullptr,
-                         err + kWindowFlag, st);
+    // both plans (query-outer for dQ, key-outer for dK/dV) side by side: three launches
+    rc = launch_tile_maps(a.bits, a.S, clean, a.block, n_loc, kDqBM, kDqBN, pa.cls, kKvBM, kKvBN, pb.cls,
+                          err + kWindowFlag, st);
     if (rc) return rc;
-    rc = launch_compact_rows(pa, st);
-    if (rc) return rc;
-    rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kKvBM, kKvBN, pb.cls, nullptr, nullptr,
-                         nullptr, st);
-    if (rc) return rc;
-    rc = launch_compact_cols(pb, st);
+    rc = launch_compact_both(pa, pb, st);
     if (rc) return rc;
 
     const float scale_log2 = a.scale * kLog2e;

@@ -113,6 +113,9 @@ int launch_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* samp
 int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
                     int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls, uint32_t* d_cnt,
                     uint64_t* d_rowpairs, int32_t* d_window_flag, hipStream_t st);
+int launch_tile_maps(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
+                     int64_t n_rows, int32_t tq_a, int32_t tk_a, uint8_t* d_cls_a, int32_t tq_b,
+                     int32_t tk_b, uint8_t* d_cls_b, int32_t* d_window_flag, hipStream_t st);
 int launch_balance(const uint64_t* d_W, int32_t nB, int32_t P, int32_t* d_rank_of_block,
                    uint64_t* d_load, int32_t* d_rank_off, int32_t* d_rank_blocks, hipStream_t st);
 

@@ -37,12 +37,27 @@ int launch_validate_blocks(const int32_t* blocks, int32_t n_blocks, int64_t n_se
 
 // ---- work lists ---------------------------------------------------------------
 // One wavefront per line (a q-tile's row of classes, or a k-tile's column) compacts
-// the line's non-empty tiles.
+// the line's non-empty tiles.  One launch serves up to two sets of lines (the second
+// set's lines follow the first's in the grid).
+struct CompactJob {
+    const uint8_t* cls;
+    int32_t n_lines, n_items;
+    int64_t line_stride, item_stride;
+    int32_t* count;
+    uint32_t* list;
+};
+struct CompactJobs { CompactJob j[2]; };
+
 __global__ void __launch_bounds__(64)
-compact_kernel(const uint8_t* __restrict__ cls, int32_t n_lines, int32_t n_items,
-               int64_t line_stride, int64_t item_stride, int32_t* __restrict__ count,
-               uint32_t* __restrict__ list) {
-    const int line = blockIdx.x;
+compact_kernel(const CompactJobs jobs) {
+    const bool second = (int)blockIdx.x >= jobs.j[0].n_lines;     // workgroup-uniform
+    const CompactJob& J = jobs.j[second ? 1 : 0];
+    const uint8_t* __restrict__ cls = J.cls;
+    const int32_t n_items = J.n_items;
+    const int64_t line_stride = J.line_stride, item_stride = J.item_stride;
+    int32_t* __restrict__ count = J.count;
+    uint32_t* __restrict__ list = J.list;
+    const int line = (int)blockIdx.x - (second ? jobs.j[0].n_lines : 0);
     const int lane = threadIdx.x;
     int base = 0;
     for (int j0 = 0; j0 < n_items; j0 += kWave) {
@@ -193,13 +208,30 @@ __device__ void slice_cols(const int32_t* __restrict__ count, int32_t nk, int32_
 constexpr int kRankThreads = 256;
 static_assert(kRankThreads == kSliceThreads, "slice_cols runs in the ranking kernel's first workgroup");
 constexpr int kRankChunk = 2048;
+struct RankJob {
+    const int32_t* count;
+    int32_t n_lines, n_items, n_wgs;     // n_wgs: workgroups of this job in the grid
+    int32_t* order;
+    int32_t* csz_out;
+    int32_t groups;
+    ColSlicing cs;
+};
+struct RankJobs { RankJob j[2]; };
+
+// One launch serves up to two sets of lines (the second set's workgroups follow the first's).
 __global__ void __launch_bounds__(kRankThreads)
-rank_lines_kernel(const int32_t* __restrict__ count, int32_t n_lines, int32_t n_items,
-                  int32_t* __restrict__ order, int32_t* __restrict__ csz_out, int32_t groups,
-                  const ColSlicing cs) {
+rank_lines_kernel(const RankJobs jobs) {
+    const bool second = (int)blockIdx.x >= jobs.j[0].n_wgs;        // workgroup-uniform
+    const RankJob& J = jobs.j[second ? 1 : 0];
+    const int32_t* __restrict__ count = J.count;
+    const int32_t n_lines = J.n_lines, n_items = J.n_items, groups = J.groups;
+    int32_t* __restrict__ order = J.order;
+    int32_t* __restrict__ csz_out = J.csz_out;
+    const ColSlicing cs = J.cs;
+    const int wg = (int)blockIdx.x - (second ? jobs.j[0].n_wgs : 0);
     __shared__ __attribute__((aligned(16))) int32_t cnt_s[kRankChunk];
     const int tid = threadIdx.x;
-    const int a = blockIdx.x * kRankThreads + tid;
+    const int a = wg * kRankThreads + tid;
     const int ca = a < n_lines ? count[a] : 0;
     int pos = 0;
     for (int b0 = 0; b0 < n_lines; b0 += kRankChunk) {
@@ -218,7 +250,7 @@ rank_lines_kernel(const int32_t* __restrict__ count, int32_t n_lines, int32_t n_
     }
     if (a < n_lines) order[pos] = a;
 
-    if (csz_out && blockIdx.x == 0) {          // workgroup-uniform
+    if (csz_out && wg == 0) {                  // workgroup-uniform
         __shared__ int64_t tot_s[kRankThreads];
         __shared__ int32_t max_s[kRankThreads], num_s[kRankThreads];
         int64_t total = 0;
@@ -241,17 +273,36 @@ rank_lines_kernel(const int32_t* __restrict__ count, int32_t n_lines, int32_t n_
         }
         if (tid == 0) *csz_out = slice_length(tot_s[0], max_s[0], num_s[0], groups, n_items);
     }
-    if (cs.slicing && blockIdx.x == 0) slice_cols(count, n_lines, n_items, cs);    // workgroup-uniform
+    if (cs.slicing && wg == 0) slice_cols(count, n_lines, n_items, cs);            // workgroup-uniform
 }
 
-static int launch_lists(const uint8_t* cls, int32_t n_lines, int32_t n_items, int64_t line_stride,
-                        int64_t item_stride, int32_t* count, uint32_t* list, int32_t* order,
-                        int32_t* csz_out, int32_t groups, const ColSlicing& cs, hipStream_t st) {
-    hipLaunchKernelGGL(compact_kernel, dim3(n_lines), dim3(64), 0, st, cls, n_lines, n_items,
-                       line_stride, item_stride, count, list);
-    hipLaunchKernelGGL(rank_lines_kernel, dim3((n_lines + kRankThreads - 1) / kRankThreads),
-                       dim3(kRankThreads), 0, st, (const int32_t*)count, n_lines, n_items, order,
-                       csz_out, groups, cs);
+static const ColSlicing kNoSlicing = {0, 0, 0, 0, nullptr, nullptr, nullptr};
+
+static CompactJob compact_job_rows(const TilePlan& p) {
+    return CompactJob{p.cls, p.nq, p.nk, (int64_t)p.nk, (int64_t)1, p.kcount, p.klist};
+}
+static CompactJob compact_job_cols(const TilePlanT& p) {
+    return CompactJob{p.cls, p.nk, p.nq, (int64_t)1, (int64_t)p.nk, p.qcount, p.qlist};
+}
+static RankJob rank_job_rows(const TilePlan& p) {
+    return RankJob{p.kcount, p.nq, p.nk, (p.nq + kRankThreads - 1) / kRankThreads, p.qorder, p.csz, p.groups,
+                   kNoSlicing};
+}
+static RankJob rank_job_cols(const TilePlanT& p) {
+    return RankJob{p.qcount, p.nk, p.nq, (p.nk + kRankThreads - 1) / kRankThreads, p.korder, nullptr, 1,
+                   ColSlicing{p.hpc, p.hc, p.groups, p.n_extra, p.slicing, p.pbase, p.extra}};
+}
+// compaction and ranking of one or two sets of lists: two launches
+static int launch_lists(const CompactJob& ca, const RankJob& ra, const CompactJob* cb, const RankJob* rb,
+                        hipStream_t st) {
+    CompactJobs cj;
+    RankJobs rj;
+    cj.j[0] = ca; rj.j[0] = ra;
+    cj.j[1] = cb ? *cb : ca; rj.j[1] = rb ? *rb : ra;
+    const int lines = ca.n_lines + (cb ? cb->n_lines : 0);
+    const int wgs = ra.n_wgs + (rb ? rb->n_wgs : 0);
+    hipLaunchKernelGGL(compact_kernel, dim3(lines), dim3(64), 0, st, cj);
+    hipLaunchKernelGGL(rank_lines_kernel, dim3(wgs), dim3(kRankThreads), 0, st, rj);
     MM_LAUNCH_CHECK();
     return MMATTN_OK;
 }
@@ -276,14 +327,18 @@ int launch_zero_kv(void* dk, void* dv, size_t bytes_each, hipStream_t st) {
 }
 
 int launch_compact_rows(const TilePlan& p, hipStream_t st) {
-    return launch_lists(p.cls, p.nq, p.nk, (int64_t)p.nk, (int64_t)1, p.kcount, p.klist, p.qorder,
-                        p.csz, p.groups, ColSlicing{0, 0, 0, 0, nullptr, nullptr, nullptr}, st);
+    return launch_lists(compact_job_rows(p), rank_job_rows(p), nullptr, nullptr, st);
 }
 
 int launch_compact_cols(const TilePlanT& p, hipStream_t st) {
-    return launch_lists(p.cls, p.nk, p.nq, (int64_t)1, (int64_t)p.nk, p.qcount, p.qlist, p.korder,
-                        nullptr, 1, ColSlicing{p.hpc, p.hc, p.groups, p.n_extra, p.slicing, p.pbase, p.extra},
-                        st);
+    return launch_lists(compact_job_cols(p), rank_job_cols(p), nullptr, nullptr, st);
+}
+
+// the query-outer and the key-outer plan of one share together
+int launch_compact_both(const TilePlan& pa, const TilePlanT& pb, hipStream_t st) {
+    const CompactJob cb = compact_job_cols(pb);
+    const RankJob rb = rank_job_cols(pb);
+    return launch_lists(compact_job_rows(pa), rank_job_rows(pa), &cb, &rb, st);
 }
 
 }  // namespace mm

@@ -29,13 +29,29 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
     return v;
 }
 
+// One launch serves up to two maps of the same rows (blockIdx.z picks the map; the grid
+// is the larger of the two, surplus workgroups exit).
 // kpw: k-tiles per wavefront (each wavefront walks kpw consecutive k-tiles, so that on
 // large maps the q-tile's words are staged once for 4*kpw tile pairs)
+struct TileMapJob {
+    int32_t tq, tk, nk, kpw;
+    uint32_t gx, gy;                     // workgroups this map needs
+    uint8_t* cls;
+    uint32_t* cnt;
+    int32_t* window_flag;
+};
+struct TileMapJobs { TileMapJob j[2]; };
+
 __global__ void __launch_bounds__(kTmThreads)
 tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
                 const int32_t* __restrict__ blocks, int32_t block, int64_t n_rows,
-                int32_t tq, int32_t tk, int32_t nk, int32_t kpw,
-                uint8_t* __restrict__ cls, uint32_t* __restrict__ cnt, int32_t* __restrict__ window_flag) {
+                const TileMapJobs jobs) {
+    const TileMapJob& J = jobs.j[blockIdx.z];
+    if (blockIdx.x >= J.gx || blockIdx.y >= J.gy) return;    // workgroup-uniform
+    const int32_t tq = J.tq, tk = J.tk, nk = J.nk, kpw = J.kpw;
+    uint8_t* __restrict__ cls = J.cls;
+    uint32_t* __restrict__ cnt = J.cnt;
+    int32_t* __restrict__ window_flag = J.window_flag;
     __shared__ uint32_t q_ss[kTmQChunk];
     __shared__ uint32_t q_att[kTmQChunk];
     __shared__ int64_t q_pos[kTmQChunk];
@@ -129,26 +145,48 @@ row_pairs_kernel(const uint32_t* __restrict__ cnt, int32_t nk, uint64_t* __restr
     if (threadIdx.x == 0) rowpairs[i] = part[0];
 }
 
-int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
-                    int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls, uint32_t* d_cnt,
-                    uint64_t* d_rowpairs, int32_t* d_window_flag, hipStream_t st) {
+static TileMapJob tile_map_job(int64_t S, int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls,
+                               uint32_t* d_cnt, int32_t* d_window_flag) {
     const int64_t nq = (n_rows + tq - 1) / tq;
     const int32_t nk = (int32_t)(S / tk);
-    if (nq == 0) return MMATTN_OK;
     // k-tiles per wavefront: one while the map has few tile pairs, up to 8 once there are
     // enough pairs for a thousand workgroups anyway
     const int64_t kpw64 = nq * nk / (kTmWaves * 1024);
     const int32_t kpw = (int32_t)std::max<int64_t>(1, std::min<int64_t>(8, kpw64));
     const int32_t per_wg = kTmWaves * kpw;
-    dim3 grid((unsigned)((nk + per_wg - 1) / per_wg), (unsigned)nq);
-    hipLaunchKernelGGL(tile_map_kernel, grid, dim3(kTmThreads), 0, st, d_bits, S, d_blocks, block,
-                       n_rows, tq, tk, nk, kpw, d_cls, d_cnt, d_window_flag);
+    return TileMapJob{tq, tk, nk, kpw, (uint32_t)((nk + per_wg - 1) / per_wg), (uint32_t)nq, d_cls, d_cnt,
+                      d_window_flag};
+}
+
+int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
+                    int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls, uint32_t* d_cnt,
+                    uint64_t* d_rowpairs, int32_t* d_window_flag, hipStream_t st) {
+    if (n_rows <= 0) return MMATTN_OK;
+    TileMapJobs jobs;
+    jobs.j[0] = jobs.j[1] = tile_map_job(S, n_rows, tq, tk, d_cls, d_cnt, d_window_flag);
+    hipLaunchKernelGGL(tile_map_kernel, dim3(jobs.j[0].gx, jobs.j[0].gy, 1), dim3(kTmThreads), 0, st, d_bits,
+                       S, d_blocks, block, n_rows, jobs);
     MM_LAUNCH_CHECK();
     if (d_rowpairs) {
-        hipLaunchKernelGGL(row_pairs_kernel, dim3((unsigned)nq), dim3(256), 0, st, d_cnt, nk,
+        hipLaunchKernelGGL(row_pairs_kernel, dim3(jobs.j[0].gy), dim3(256), 0, st, d_cnt, jobs.j[0].nk,
                            d_rowpairs);
         MM_LAUNCH_CHECK();
     }
+    return MMATTN_OK;
+}
+
+// two class maps of the same rows (different tile shapes) in one launch
+int launch_tile_maps(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
+                     int64_t n_rows, int32_t tq_a, int32_t tk_a, uint8_t* d_cls_a, int32_t tq_b,
+                     int32_t tk_b, uint8_t* d_cls_b, int32_t* d_window_flag, hipStream_t st) {
+    if (n_rows <= 0) return MMATTN_OK;
+    TileMapJobs jobs;
+    jobs.j[0] = tile_map_job(S, n_rows, tq_a, tk_a, d_cls_a, nullptr, d_window_flag);
+    jobs.j[1] = tile_map_job(S, n_rows, tq_b, tk_b, d_cls_b, nullptr, nullptr);
+    hipLaunchKernelGGL(tile_map_kernel,
+                       dim3(std::max(jobs.j[0].gx, jobs.j[1].gx), std::max(jobs.j[0].gy, jobs.j[1].gy), 2),
+                       dim3(kTmThreads), 0, st, d_bits, S, d_blocks, block, n_rows, jobs);
+    MM_LAUNCH_CHECK();
     return MMATTN_OK;
 }
 
