@@ -29,8 +29,8 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
     return v;
 }
 
-// One launch serves up to two maps of the same rows (blockIdx.z picks the map; the grid
-// is the larger of the two, surplus workgroups exit).
+// One launch serves up to two maps of the same rows (the second map's workgroups follow
+// the first's in the one-dimensional grid).
 // kpw: k-tiles per wavefront (each wavefront walks kpw consecutive k-tiles, so that on
 // large maps the q-tile's words are staged once for 4*kpw tile pairs)
 struct TileMapJob {
@@ -46,8 +46,11 @@ __global__ void __launch_bounds__(kTmThreads)
 tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
                 const int32_t* __restrict__ blocks, int32_t block, int64_t n_rows,
                 const TileMapJobs jobs) {
-    const TileMapJob& J = jobs.j[blockIdx.z];
-    if (blockIdx.x >= J.gx || blockIdx.y >= J.gy) return;    // workgroup-uniform
+    const uint32_t n_first = jobs.j[0].gx * jobs.j[0].gy;
+    const bool second = blockIdx.x >= n_first;               // workgroup-uniform
+    const TileMapJob& J = jobs.j[second ? 1 : 0];
+    const uint32_t wg = blockIdx.x - (second ? n_first : 0u);
+    const uint32_t wg_x = wg % J.gx, wg_y = wg / J.gx;       // k-tile group, q-tile
     const int32_t tq = J.tq, tk = J.tk, nk = J.nk, kpw = J.kpw;
     uint8_t* __restrict__ cls = J.cls;
     uint32_t* __restrict__ cnt = J.cnt;
@@ -58,7 +61,7 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int64_t i = blockIdx.y;
+    const int64_t i = wg_y;
     const int64_t r0 = i * tq;
     const int64_t rows = min((int64_t)tq, n_rows - r0);      // ragged last q-tile
     // words of the q rows c0 .. c0+n-1 of the tile into LDS (all threads; two barriers)
@@ -71,7 +74,7 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
             q_ss[threadIdx.x] = word_ss(w);
             q_att[threadIdx.x] = word_att(w);
             // every writer stores the same value; the attention kernels read it after this launch
-            if (window_flag && blockIdx.x == 0 && att_window(word_att(w)) != 0) *window_flag = 1;
+            if (window_flag && wg_x == 0 && att_window(word_att(w)) != 0) *window_flag = 1;
         }
         __syncthreads();
     };
@@ -79,7 +82,7 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
     if (single) stage_rows(0, (int)rows);
 
     for (int jj = 0; jj < kpw; ++jj) {
-        const int64_t j = ((int64_t)blockIdx.x * kTmWaves + wave) * kpw + jj;
+        const int64_t j = ((int64_t)wg_x * kTmWaves + wave) * kpw + jj;
         const bool wave_active = j < nk;
         const int64_t k0 = j * tk;
         uint32_t part = 0;
@@ -164,8 +167,8 @@ int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, 
     if (n_rows <= 0) return MMATTN_OK;
     TileMapJobs jobs;
     jobs.j[0] = jobs.j[1] = tile_map_job(S, n_rows, tq, tk, d_cls, d_cnt, d_window_flag);
-    hipLaunchKernelGGL(tile_map_kernel, dim3(jobs.j[0].gx, jobs.j[0].gy, 1), dim3(kTmThreads), 0, st, d_bits,
-                       S, d_blocks, block, n_rows, jobs);
+    hipLaunchKernelGGL(tile_map_kernel, dim3(jobs.j[0].gx * jobs.j[0].gy), dim3(kTmThreads), 0, st, d_bits, S,
+                       d_blocks, block, n_rows, jobs);
     MM_LAUNCH_CHECK();
     if (d_rowpairs) {
         hipLaunchKernelGGL(row_pairs_kernel, dim3(jobs.j[0].gy), dim3(256), 0, st, d_cnt, jobs.j[0].nk,
@@ -183,8 +186,7 @@ int launch_tile_maps(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks,
     TileMapJobs jobs;
     jobs.j[0] = tile_map_job(S, n_rows, tq_a, tk_a, d_cls_a, nullptr, d_window_flag);
     jobs.j[1] = tile_map_job(S, n_rows, tq_b, tk_b, d_cls_b, nullptr, nullptr);
-    hipLaunchKernelGGL(tile_map_kernel,
-                       dim3(std::max(jobs.j[0].gx, jobs.j[1].gx), std::max(jobs.j[0].gy, jobs.j[1].gy), 2),
+    hipLaunchKernelGGL(tile_map_kernel, dim3(jobs.j[0].gx * jobs.j[0].gy + jobs.j[1].gx * jobs.j[1].gy),
                        dim3(kTmThreads), 0, st, d_bits, S, d_blocks, block, n_rows, jobs);
     MM_LAUNCH_CHECK();
     return MMATTN_OK;
