@@ -17,7 +17,10 @@
 //                  to fill the chip, a unit's heads are split over several workgroups
 //                  (the intra-GPU balancing idea of paper section 3.2.2 applied to
 //                  the key-outer pass: split the work of a block, write partial
-//                  results, aggregate in one more launch); the partials are fp32 and
+//                  results, aggregate in one more launch), and a k-tile whose list of
+//                  query tiles is far longer than the others' (keys that nearly every
+//                  row attends) is cut into list slices, each a workgroup of its own;
+//                  the partials are fp32, live in a pool of per-k-tile slots and are
 //                  summed in a fixed order by dkv_reduce_kernel;
 //   dq_kernel      query-outer: a workgroup of four wavefronts owns 128 query rows of one
 //                  head and walks the active 64-key tiles (two-stage K/V ring).
