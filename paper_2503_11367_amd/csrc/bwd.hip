@@ -733,7 +733,10 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     constexpr int NI = kStageBytes / 1024 / NW;
     static_assert(NI >= 1, "tile too small for this many wavefronts");
     __shared__ DqSmem<D, NST> sm;
-    if (*err) return;
+    // independent loads of the work-item lookup are issued together and the early exits are
+    // taken after the row's own loads (see the forward kernel)
+    const int err_flag = *err;
+    const int csz_dev = *plan.csz;
 
     const int rep = Hq / Hkv;
     int tile_rank, h0;
@@ -754,11 +757,9 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     }
     const int g = h0 / rep;
     const int qt = plan.qorder[tile_rank];
+    if (err_flag) return;
     const int kc_total = plan.kcount[qt];
-    const int csz = max(*plan.csz, split.csz);
-    const int nchunk = max(1, (kc_total + csz - 1) / csz);
-    if (chunk >= nchunk) return;          // workgroup-uniform
-    const int n_active = max(0, min(kc_total - chunk * csz, csz));
+    const int csz = max(csz_dev, split.csz);
     const uint32_t* klist = plan.klist + (int64_t)qt * plan.nk + chunk * csz;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -790,6 +791,14 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             dof[ds] = __builtin_bit_cast(bf16x8, *(const u32x4*)(dO + off + ds * 16));
         }
     }
+    // entries past the list's length, inside the q-tile's row of the list array, are read
+    // but never used
+    uint32_t list_chunk = chunk * csz + lane < plan.nk ? klist[lane] : 0u;
+
+    const int nchunk = max(1, (kc_total + csz - 1) / csz);
+    if (chunk >= nchunk) return;          // workgroup-uniform
+    const int n_active = max(0, min(kc_total - chunk * csz, csz));
+
     floatx16 dq[NDB];
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
@@ -854,7 +863,6 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
 
-    uint32_t list_chunk = lane < n_active ? klist[lane] : 0u;
     auto entry_at = [&](int it) -> uint32_t {
         return __builtin_amdgcn_readlane(list_chunk, it & 63);
     };

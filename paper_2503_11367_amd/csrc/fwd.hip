@@ -68,7 +68,12 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     constexpr int NI = kStageBytes / 1024 / NW;      // 1 KiB transfers per wave per tensor
     static_assert(NI >= 1, "tile too small for this many wavefronts");
     __shared__ FwdSmem<D, NST> sm;
-    if (*err) return;
+    // The loads that find the work item form a chain (error flag, q-tile of this rank,
+    // its list length, the list, the tiles); the independent ones are issued together and
+    // the early exits are taken after the row's own loads have been issued, so that a
+    // work item starts after three round trips instead of six.
+    const int err_flag = *err;
+    const int csz_dev = *plan.csz;
 
     // ---- work decode: KV heads are pinned to XCDs (workgroups are dealt
     // round-robin to the 8 XCDs) so that one head's K/V stays in one L2 --------
@@ -91,13 +96,11 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     }
     const int g = h0 / rep;
     const int qt = plan.qorder[tile_rank];
+    if (err_flag) return;
     // this workgroup's slice of the active list: csz entries from chunk * csz on; the
     // length is the list builder's suggestion, but never below what the grid provides for
     const int kc_total = plan.kcount[qt];
-    const int csz = max(*plan.csz, split.csz);
-    const int nchunk = max(1, (kc_total + csz - 1) / csz);
-    if (chunk >= nchunk) return;          // workgroup-uniform
-    const int n_active = max(0, min(kc_total - chunk * csz, csz));
+    const int csz = max(csz_dev, split.csz);
     const uint32_t* klist = plan.klist + (int64_t)qt * plan.nk + chunk * csz;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -124,6 +127,16 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds) qf[ds] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
     }
+
+    // the k-tile list is fetched 64 entries at a time, one per lane, and read back
+    // with readlane: no vector load inside the steady-state loop besides the tiles.
+    // (Fetched before the list length is known: entries past it, inside the q-tile's row
+    // of the list array, are read but never used.)
+    uint32_t list_chunk = chunk * csz + lane < plan.nk ? klist[lane] : 0u;
+
+    const int nchunk = max(1, (kc_total + csz - 1) / csz);
+    if (chunk >= nchunk) return;          // workgroup-uniform
+    const int n_active = max(0, min(kc_total - chunk * csz, csz));
 
     floatx16 o[NDB];
 #pragma unroll
@@ -171,9 +184,6 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         vaddr[db] = lds_addr_of(sm.v[0]) + VT::byte_of(4 * hh + s16 / 4, 4 * db + 2 * (grp & 1) + ((s16 & 3) >> 1)) +
                    8 * (s16 & 1);
 
-    // the k-tile list is fetched 64 entries at a time, one per lane, and read back
-    // with readlane: no vector load inside the steady-state loop besides the tiles
-    uint32_t list_chunk = lane < n_active ? klist[lane] : 0u;
     auto entry_at = [&](int it) -> uint32_t {
         return __builtin_amdgcn_readlane(list_chunk, it & 63);
     };
