@@ -893,6 +893,10 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         // ahead and waits before almost every MFMA), across the two halves of the tile.
         constexpr int NP = 2 * NDS;        // MFMA pairs of the tile
         bf16x8 kfr[2], vfr[2];
+        // this phase is almost only matrix instructions: it runs at the lower priority, the
+        // element-wise phase at the higher one, so that of the two workgroups on a CU the one
+        // with vector work to do gets the issue slots first (measured: -2.3 %)
+        __builtin_amdgcn_s_setprio(0);
         auto fetch = [&](int i) __attribute__((always_inline)) {
             const int off = tile + (i / NDS) * kHalf;
             kfr[i & 1] = read_row(krow_a[i % NDS], off);
@@ -938,6 +942,7 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // phase 2: dS = P o (dP - Delta) as bf16, then dQ^T += K^T dS^T
     auto phase_dq = [&](int tile) __attribute__((always_inline)) {
         bf16x8 dsf[4];
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
