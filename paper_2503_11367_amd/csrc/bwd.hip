@@ -400,6 +400,26 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
         }
     };
     auto mask_unit = [&](floatx16& x, int imm) __attribute__((always_inline)) {
+        // Usually the unit's 32 rows are one run: equal mask fields, consecutive positions.
+        // Then the rows that see this lane's key are one contiguous range, found once, an
+        // element costs a subtraction and a comparison, and a wavefront all of whose keys are
+        // seen by all 32 rows does nothing.
+        const uint32_t ra = lds_info + (uint32_t)imm + (uint32_t)li * 4u;
+        const uint32_t ss_r = *(lds_u1)(uintptr_t)ra, ca_r = *(lds_u1)(uintptr_t)(ra + 4 * kKvBM);
+        const uint32_t ps_r = *(lds_u1)(uintptr_t)(ra + 8 * kKvBM);
+        const uint32_t ss0 = __builtin_amdgcn_readfirstlane(ss_r), ca0 = __builtin_amdgcn_readfirstlane(ca_r);
+        const uint32_t ps0 = __builtin_amdgcn_readfirstlane(ps_r);
+        if (__all(ss_r == ss0 && ca_r == ca0 && ps_r == ps0 + (uint32_t)li)) {      // wave-uniform
+            const KeyRange r = visible_rows(ss0, ca0, (int32_t)ps0, k_ss, k_mod, (int32_t)key, 32);
+            if (!__all(r.all_of(32))) {
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (!r.sees(4u * hh + (uint32_t)(8 * q4 + j))) x[q4 * 4 + j] = -INFINITY;
+            }
+            return;
+        }
         if (windows) mask_with(std::true_type{}, x, imm);      // workgroup-uniform
         else mask_with(std::false_type{}, x, imm);
     };

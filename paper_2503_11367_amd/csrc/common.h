@@ -94,6 +94,25 @@ __device__ __forceinline__ KeyRange visible_range(uint32_t ss_q, uint32_t att_q,
     return KeyRange{empty ? 0x40000000u : (uint32_t)lo, empty ? 0u : (uint32_t)(hi - lo)};
 }
 
+// The transposed case: n query rows at consecutive positions q_first, q_first + 1, ... that
+// all carry the fields (ss_q, att_q), seen from one key: the rows that see the key are one
+// contiguous range (all of them for the key's own span; else the rows from the key's
+// position on, as far as their look-back window reaches).
+__device__ __forceinline__ KeyRange visible_rows(uint32_t ss_q, uint32_t att_q, int32_t q_first, uint32_t ss_k,
+                                                 uint32_t mod_k, int32_t k, int32_t n) {
+    const bool same_sample = (ss_q >> 16) == (ss_k >> 16);
+    const bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_k;
+    const bool attends = (att_q >> mod_k) & 1u;
+    const int32_t rel = k - q_first;                       // index of the first row at or after the key
+    const int32_t win = (int32_t)att_window(att_q);
+    const bool windowed = win != 0 && mod_k == att_modality(att_q);
+    int32_t lo = same_sample && attends ? max(rel, 0) : n;
+    int32_t hi = windowed ? min(rel + win - 1, n - 1) : n - 1;
+    if (same_span) { lo = 0; hi = n - 1; }
+    const bool empty = hi < lo;
+    return KeyRange{empty ? 0x40000000u : (uint32_t)lo, empty ? 0u : (uint32_t)(hi - lo)};
+}
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Global token position of local row r of a rank share (blocks == nullptr:
