@@ -113,7 +113,7 @@ int mmattn_tile_map(const uint64_t* d_bits, int64_t S, int32_t tq, int32_t tk, u
     if (S <= 0 || tq <= 0 || tk <= 0 || S % tq != 0 || S % tk != 0) return MMATTN_ERR_SHAPE;
     if ((int64_t)tq * tk > ((int64_t)1 << 31)) return MMATTN_ERR_SHAPE;
     if (S / tq > 65535 || S / tk > ((int64_t)1 << 24)) return MMATTN_ERR_UNSUPPORTED;
-    return launch_tile_map(d_bits, S, nullptr, 1, S, tq, tk, d_cls, d_cnt, d_rowpairs, nullptr,
+    return launch_tile_map(d_bits, S, nullptr, 1, S, tq, tk, d_cls, d_cnt, d_rowpairs,
                            (hipStream_t)stream);
 }
 

@@ -245,10 +245,8 @@ struct TilePlanT {
 };
 constexpr int kSliceLen = 0, kSlicedTiles = 1, kExtraUsed = 2, kSliceInts = 4;
 
-// int32 words cleared by launch_validate_blocks at `err`: the error flag, the flag "some
-// query row of the share has a look-back window" (set by the tile map) and spare words;
+// int32 words cleared by launch_validate_blocks at `err`: the error flag and spare words;
 // the word after them holds the slice length chosen by the list builder
-constexpr int kWindowFlag = 1;
 constexpr int kFlagInts = 4;
 int launch_compact_rows(const TilePlan& p, hipStream_t st);
 int launch_compact_cols(const TilePlanT& p, hipStream_t st);

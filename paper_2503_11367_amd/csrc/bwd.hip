@@ -185,7 +185,6 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     constexpr int PER = 16 * QT::RPS, NV = PER / 8;    // transpose-read address period
     __shared__ KvSmem<D> sm;
     if (*err) return;
-    const bool windows = err[kWindowFlag] != 0;      // some query row has a look-back window
 
     // ---- work decode: chunk index slowest, then work item (longest first: the first
     // slices of the sliced lists, the other slices, the unsliced lists; then the unused
@@ -387,7 +386,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     };
     // PARTIAL steps: rows 8*q4 + 4*hh + 0..3 (+32 per unit) of the step's mask inputs, 16 bytes per read
     const uint32_t info_addr = lds_info + hh * 16;
-    auto mask_with = [&](auto with_windows, floatx16& x, int imm) __attribute__((always_inline)) {
+    auto mask_elements = [&](floatx16& x, int imm) __attribute__((always_inline)) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const u32x4 ss = *(lds_u4)(uintptr_t)(info_addr + (uint32_t)(imm + q4 * 32));
@@ -395,7 +394,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             const u32x4 ps = *(lds_u4)(uintptr_t)(info_addr + (uint32_t)(imm + q4 * 32 + 8 * kKvBM));
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (!visible<decltype(with_windows)::value>(ss[j], ca[j], (int64_t)ps[j], k_ss, k_mod, key))
+                if (!visible(ss[j], ca[j], (int64_t)ps[j], k_ss, k_mod, key))
                     x[q4 * 4 + j] = -INFINITY;
         }
     };
@@ -420,8 +419,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             }
             return;
         }
-        if (windows) mask_with(std::true_type{}, x, imm);      // workgroup-uniform
-        else mask_with(std::false_type{}, x, imm);
+        mask_elements(x, imm);
     };
     // One unit: NS slots, each one MFMA, one fragment request and a share of the
     // element-wise work (see the forward kernel).  KR: std::true_type for the K role.
@@ -733,6 +731,7 @@ struct DqSmem {
     alignas(1024) unsigned char k[NST][kDqBN * D * 2];    // MODE 0: rows (S^T) and transpose (dQ^T)
     alignas(1024) unsigned char v[NST][kDqBN * D * 2];    // same layout: rows (dP^T)
     uint32_t kss[2][kDqBN];                               // sample/span field and modality of a PARTIAL tile's keys
+    alignas(16) float park[4][3][64][4];                  // per wavefront: twelve registers parked while a tile is masked
 };
 
 template <int D, int HPW, int NST>
@@ -943,8 +942,36 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             // across the whole loop
             uint32_t qs = q_ss, qa = q_causal, qp = (uint32_t)q_pos;
             asm volatile("" : "+v"(qs), "+v"(qa), "+v"(qp));
+            // The kernel has no register to spare, so twelve accumulator registers are parked in
+            // LDS while a PARTIAL tile is masked (rare) and fetched back afterwards: the masking
+            // code gets room without costing the main loop anything.
+            uint32_t zero = 0u;
+            asm volatile("" : "+v"(zero));                   // lane index taken afresh, see below
+            const uint32_t ln = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, zero));
+            const uint32_t park_a = lds_addr_of(sm.park) + (uint32_t)(wave & 3) * 3072u + ln * 16u;
+            typedef floatx4 __attribute__((address_space(3))) * lds_f4;
+            *(lds_f4)(uintptr_t)park_a = floatx4{dq[NDB - 1][0], dq[NDB - 1][1], dq[NDB - 1][2], dq[NDB - 1][3]};
+            *(lds_f4)(uintptr_t)(park_a + 1024u) = floatx4{dq[NDB - 1][4], dq[NDB - 1][5], dq[NDB - 1][6], dq[NDB - 1][7]};
+            *(lds_f4)(uintptr_t)(park_a + 2048u) = floatx4{dq[NDB - 1][8], dq[NDB - 1][9], dq[NDB - 1][10], dq[NDB - 1][11]};
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb) {
+                // usually the 32 keys of the half tile are one run of equal mask fields: every row
+                // then sees one contiguous range of them (see the forward kernel)
+                const uint32_t ka = lds_addr_of(sm.kss) + (uint32_t)(kb * 128) + (ln & 31u) * 4u;
+                const uint32_t ss_k = *(lds_u1)(uintptr_t)ka, mod_k = *(lds_u1)(uintptr_t)(ka + 4 * kDqBN);
+                const uint32_t ss0 = __builtin_amdgcn_readfirstlane(ss_k), mod0 = __builtin_amdgcn_readfirstlane(mod_k);
+                if (__all(ss_k == ss0 && mod_k == mod0)) {       // wave-uniform
+                    const KeyRange r = visible_range(qs, qa, (int32_t)qp, ss0, mod0, (int32_t)k0 + kb * 32, 32);
+                    if (!__all(r.all_of(32))) {
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                if (!r.sees((ln >> 5) * 4u + (uint32_t)(8 * q4 + j))) sv[kb][q4 * 4 + j] = -INFINITY;
+                    }
+                    continue;
+                }
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
                     const u32x4 kw = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(kb * 128 + q4 * 32));
@@ -952,11 +979,19 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
-                        if (!visible<true>(qs, qa, (int64_t)qp, kw[j], km[j], k0 + kl)) sv[kb][q4 * 4 + j] = -INFINITY;
+                        if (!visible(qs, qa, (int64_t)qp, kw[j], km[j], k0 + kl)) sv[kb][q4 * 4 + j] = -INFINITY;
                         // one element at a time: no register is free for a second one's temporaries
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                const floatx4 p0 = *(lds_f4)(uintptr_t)park_a, p1 = *(lds_f4)(uintptr_t)(park_a + 1024u);
+                const floatx4 p2 = *(lds_f4)(uintptr_t)(park_a + 2048u);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { dq[NDB - 1][u] = p0[u]; dq[NDB - 1][4 + u] = p1[u]; dq[NDB - 1][8 + u] = p2[u]; }
+            }
         }
     };
     // phase 2: dS = P o (dP - Delta) as bf16, then dQ^T += K^T dS^T
@@ -1204,7 +1239,7 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     if (rc) return rc;
     // both plans (query-outer for dQ, key-outer for dK/dV) side by side: three launches
     rc = launch_tile_maps(a.bits, a.S, clean, a.block, n_loc, kDqBM, kDqBN, pa.cls, kKvBM, kKvBN, pb.cls,
-                          err + kWindowFlag, st);
+                          st);
     if (rc) return rc;
     rc = launch_compact_both(pa, pb, st);
     if (rc) return rc;

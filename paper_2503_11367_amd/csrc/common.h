@@ -47,26 +47,17 @@ __host__ __device__ inline uint32_t att_modality(uint32_t att) { return (att >> 
 // vis(q,k) = same_sample && ((causal(q) && k<=q && attend(q)[modality(k)] &&
 //                             (window(q)==0 || modality(k)!=modality(q) || q-k<window(q))) ||
 //                            (span(q)!=0 && span(q)==span(k)))
-// WINDOWS = false leaves the window term out: for launches none of whose query rows has
-// a window (the usual case), where the query-side fields change per element and the
-// extra comparisons would be wasted.
-template <bool WINDOWS>
 __device__ __forceinline__ bool visible(uint32_t ss_q, uint32_t att_q, int64_t q,
                                         uint32_t ss_k, uint32_t mod_k, int64_t k) {
     const bool same_sample = (ss_q >> 16) == (ss_k >> 16);
     const bool same_span = (ss_q & 0xFFFFu) != 0 && ss_q == ss_k;
     const bool attends = (att_q >> mod_k) & 1u;
-    // positions are below 2^31, so 32-bit arithmetic serves
-    if constexpr (!WINDOWS) {
-        return same_span || (same_sample && attends && (int32_t)k <= (int32_t)q);
-    } else {
-        // k <= q  <=>  the 32-bit difference is below 2^31.  Farthest visible look-back:
-        // window - 1 for keys of the own modality (no window: 0 - 1 wraps to the maximum),
-        // unlimited otherwise
-        const uint32_t back = (uint32_t)q - (uint32_t)k;
-        const uint32_t reach = mod_k == att_modality(att_q) ? att_window(att_q) - 1u : 0x7FFFFFFFu;
-        return same_span || (same_sample && attends && back <= min(reach, 0x7FFFFFFFu));
-    }
+    // positions are below 2^31, so 32-bit arithmetic serves: k <= q  <=>  the 32-bit
+    // difference is below 2^31.  Farthest visible look-back: window - 1 for keys of the own
+    // modality (no window: 0 - 1 wraps to the maximum), unlimited otherwise
+    const uint32_t back = (uint32_t)q - (uint32_t)k;
+    const uint32_t reach = mod_k == att_modality(att_q) ? att_window(att_q) - 1u : 0x7FFFFFFFu;
+    return same_span || (same_sample && attends && back <= min(reach, 0x7FFFFFFFu));
 }
 
 // A stretch of n consecutive keys, the first at position k_first, that all carry the
@@ -128,13 +119,12 @@ int launch_mfma_ceiling(int32_t iters, int32_t random_operands, float* sink, dou
                         hipStream_t st);
 int launch_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* sample_off,
                   int32_t n_samples, int64_t S, uint64_t* d_bits, void* ws, hipStream_t st);
-// d_window_flag (may be null): set to 1 if any of the rows has a look-back window
 int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
                     int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls, uint32_t* d_cnt,
-                    uint64_t* d_rowpairs, int32_t* d_window_flag, hipStream_t st);
+                    uint64_t* d_rowpairs, hipStream_t st);
 int launch_tile_maps(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
                      int64_t n_rows, int32_t tq_a, int32_t tk_a, uint8_t* d_cls_a, int32_t tq_b,
-                     int32_t tk_b, uint8_t* d_cls_b, int32_t* d_window_flag, hipStream_t st);
+                     int32_t tk_b, uint8_t* d_cls_b, hipStream_t st);
 int launch_balance(const uint64_t* d_W, int32_t nB, int32_t P, int32_t* d_rank_of_block,
                    uint64_t* d_load, int32_t* d_rank_off, int32_t* d_rank_blocks, hipStream_t st);
 

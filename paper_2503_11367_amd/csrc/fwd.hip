@@ -267,7 +267,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
-                    if (!visible<true>(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
+                    if (!visible(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
                 }
                 // four elements at a time: the comparison results live in scalar registers
                 __builtin_amdgcn_sched_barrier(0);
@@ -629,7 +629,7 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
         int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
         if (rc) return rc;
         rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kFwdBM, kFwdBN, plan.cls, nullptr,
-                             nullptr, nullptr, st);
+                             nullptr, st);
         if (rc) return rc;
         rc = launch_compact_rows(plan, st);
         if (rc) return rc;

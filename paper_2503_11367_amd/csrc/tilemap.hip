@@ -38,7 +38,6 @@ struct TileMapJob {
     uint32_t gx, gy;                     // workgroups this map needs
     uint8_t* cls;
     uint32_t* cnt;
-    int32_t* window_flag;
 };
 struct TileMapJobs { TileMapJob j[2]; };
 
@@ -54,7 +53,6 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
     const int32_t tq = J.tq, tk = J.tk, nk = J.nk, kpw = J.kpw;
     uint8_t* __restrict__ cls = J.cls;
     uint32_t* __restrict__ cnt = J.cnt;
-    int32_t* __restrict__ window_flag = J.window_flag;
     __shared__ uint32_t q_ss[kTmQChunk];
     __shared__ uint32_t q_att[kTmQChunk];
     __shared__ int64_t q_pos[kTmQChunk];
@@ -73,8 +71,6 @@ tile_map_kernel(const uint64_t* __restrict__ bits, int64_t S,
             q_pos[threadIdx.x] = p;
             q_ss[threadIdx.x] = word_ss(w);
             q_att[threadIdx.x] = word_att(w);
-            // every writer stores the same value; the attention kernels read it after this launch
-            if (window_flag && wg_x == 0 && att_window(word_att(w)) != 0) *window_flag = 1;
         }
         __syncthreads();
     };
@@ -149,7 +145,7 @@ row_pairs_kernel(const uint32_t* __restrict__ cnt, int32_t nk, uint64_t* __restr
 }
 
 static TileMapJob tile_map_job(int64_t S, int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls,
-                               uint32_t* d_cnt, int32_t* d_window_flag) {
+                               uint32_t* d_cnt) {
     const int64_t nq = (n_rows + tq - 1) / tq;
     const int32_t nk = (int32_t)(S / tk);
     // k-tiles per wavefront: one while the map has few tile pairs, up to 8 once there are
@@ -157,16 +153,15 @@ static TileMapJob tile_map_job(int64_t S, int64_t n_rows, int32_t tq, int32_t tk
     const int64_t kpw64 = nq * nk / (kTmWaves * 1024);
     const int32_t kpw = (int32_t)std::max<int64_t>(1, std::min<int64_t>(8, kpw64));
     const int32_t per_wg = kTmWaves * kpw;
-    return TileMapJob{tq, tk, nk, kpw, (uint32_t)((nk + per_wg - 1) / per_wg), (uint32_t)nq, d_cls, d_cnt,
-                      d_window_flag};
+    return TileMapJob{tq, tk, nk, kpw, (uint32_t)((nk + per_wg - 1) / per_wg), (uint32_t)nq, d_cls, d_cnt};
 }
 
 int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
                     int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls, uint32_t* d_cnt,
-                    uint64_t* d_rowpairs, int32_t* d_window_flag, hipStream_t st) {
+                    uint64_t* d_rowpairs, hipStream_t st) {
     if (n_rows <= 0) return MMATTN_OK;
     TileMapJobs jobs;
-    jobs.j[0] = jobs.j[1] = tile_map_job(S, n_rows, tq, tk, d_cls, d_cnt, d_window_flag);
+    jobs.j[0] = jobs.j[1] = tile_map_job(S, n_rows, tq, tk, d_cls, d_cnt);
     hipLaunchKernelGGL(tile_map_kernel, dim3(jobs.j[0].gx * jobs.j[0].gy), dim3(kTmThreads), 0, st, d_bits, S,
                        d_blocks, block, n_rows, jobs);
     MM_LAUNCH_CHECK();
@@ -181,11 +176,11 @@ int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, 
 // two class maps of the same rows (different tile shapes) in one launch
 int launch_tile_maps(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
                      int64_t n_rows, int32_t tq_a, int32_t tk_a, uint8_t* d_cls_a, int32_t tq_b,
-                     int32_t tk_b, uint8_t* d_cls_b, int32_t* d_window_flag, hipStream_t st) {
+                     int32_t tk_b, uint8_t* d_cls_b, hipStream_t st) {
     if (n_rows <= 0) return MMATTN_OK;
     TileMapJobs jobs;
-    jobs.j[0] = tile_map_job(S, n_rows, tq_a, tk_a, d_cls_a, nullptr, d_window_flag);
-    jobs.j[1] = tile_map_job(S, n_rows, tq_b, tk_b, d_cls_b, nullptr, nullptr);
+    jobs.j[0] = tile_map_job(S, n_rows, tq_a, tk_a, d_cls_a, nullptr);
+    jobs.j[1] = tile_map_job(S, n_rows, tq_b, tk_b, d_cls_b, nullptr);
     hipLaunchKernelGGL(tile_map_kernel, dim3(jobs.j[0].gx * jobs.j[0].gy + jobs.j[1].gx * jobs.j[1].gy),
                        dim3(kTmThreads), 0, st, d_bits, S, d_blocks, block, n_rows, jobs);
     MM_LAUNCH_CHECK();
