@@ -30,7 +30,7 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published figure
 # HBM bytes per launch (fetched + written) of the dominant kernel, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/attention_kernels_vlm_8k.md
 # (scaled by the copy-kernel calibration given there); None for workloads not profiled.
-MEASURED_TRAFFIC_BYTES = {("vlm_8k", "dkv_kernel"): 485479730}
+MEASURED_TRAFFIC_BYTES = {("vlm_8k", "dkv_kernel"): 443705661}
 
 
 def build_inputs(w, device):
