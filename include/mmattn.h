@@ -115,7 +115,10 @@ size_t mmattn_workspace_size(int op, int64_t S, int32_t n_blocks, int32_t block,
  *              sample each, modality in 1..7; span id = index+1
  *   sample_off host, n_samples+1 increasing offsets, [0]=0, [n_samples]=S
  *   d_bits     device, S words, overwritten
- *   ws         device scratch (staging of the two host lists)
+ *   ws         device scratch (staging of the two lists when there are more than
+ *              64 spans or samples; both lists travel as kernel arguments, so
+ *              the host arrays are read before the call returns and may be
+ *              freed or changed right after it, whatever memory they are in)
  * MMATTN_ERR_LAYOUT for unsorted/overlapping/out-of-range spans, a span that
  * crosses a sample boundary, or bad offsets. */
 int mmattn_mask_encode(const mmattn_span* spans, int32_t n_spans,
@@ -161,7 +164,16 @@ int mmattn_balance(const uint64_t* d_W, int32_t nB, int32_t P,
  * 16-byte aligned tensors, S <= 2^30, Hq <= 4096, n_blocks * block <=
  * 65535 * 64 (else MMATTN_ERR_UNSUPPORTED).  n_blocks may be 0 (Alg. 1 leaves a rank empty when
  * there are more ranks than blocks): nothing is read or written, and q_loc,
- * blocks, o_loc, lse may be null. */
+ * blocks, o_loc, lse may be null.
+ * Block indices live on the device, so their range is checked there: the first
+ * int32 of `ws` is the call's status word, 0 after a good call and non-zero when
+ * some blocks[i] lay outside [0, S/block).  In that case the attention kernels
+ * return at once and the outputs keep whatever they held before the call; the
+ * call itself still returns MMATTN_OK (the host never waits for the device).
+ * The same holds for mmattn_fwd_heads, mmattn_fwd_staged and mmattn_bwd (there
+ * dq_loc, dk, dv are the outputs left untouched).  Repeated block indices are
+ * not detected: the rows are then simply computed twice, and in the backward
+ * they contribute twice to dk, dv. */
 int mmattn_fwd(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
                const int32_t* blocks, int32_t n_blocks, int32_t block,
                int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,

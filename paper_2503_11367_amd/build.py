@@ -22,7 +22,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-         "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]
+         "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option", "-Wno-inline-asm"]
 
 
 def sources():

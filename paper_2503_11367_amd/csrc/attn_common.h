@@ -140,7 +140,7 @@ __device__ __forceinline__ void dma16(const void* base_uniform, uint32_t off, ui
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(off), "s"(sb), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;

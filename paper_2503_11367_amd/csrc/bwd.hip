@@ -119,7 +119,7 @@ __device__ __forceinline__ void dma4(const void* base_uniform, uint32_t off, uin
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                  :
                  : "v"(off), "s"(sb), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // ---------------------------------------------------------------- dK / dV ----
@@ -790,7 +790,10 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     const bool row_ok = row < n_loc;
     int64_t q_pos = 0;
     uint32_t q_ss = 0, q_causal = 0;
-    const float my_lse2 = ld_g[(int64_t)h * 2 * n_pad + row];           // +inf on padding rows
+    // +inf on padding rows; a row that sees no key has LSE = -inf and all its scores masked
+    // (-inf): taking +inf for it as well makes every probability 0 instead of exp2(-inf + inf)
+    const float lse2_raw = ld_g[(int64_t)h * 2 * n_pad + row];
+    const float my_lse2 = lse2_raw == -INFINITY ? INFINITY : lse2_raw;
     const float my_delta = ld_g[((int64_t)h * 2 + 1) * n_pad + row];
     bf16x8 qf[NDS], dof[NDS];
 #pragma unroll

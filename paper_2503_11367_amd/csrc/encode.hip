@@ -2,6 +2,7 @@
 // sample offsets (paper section 4.2, bitfield attention mask; App. C packing).
 // One thread per token; binary search over the (sorted) sample offsets and
 // span starts that were staged into the workspace.
+#include <algorithm>
 #include "common.h"
 
 namespace mm {
@@ -62,6 +63,16 @@ encode_inline_kernel(const InlineLayout lay, int32_t n_spans, int32_t n_samples,
     encode_token(lay.spans, n_spans, lay.sample_off, n_samples, S, bits);
 }
 
+// one batch of the long lists: entries first .. first + ns - 1 of the spans and first ..
+// first + no - 1 of the sample offsets, from the kernel arguments into the workspace
+__global__ void __launch_bounds__(kInlineSpans)
+stage_lists_kernel(const InlineLayout lay, int32_t first, int32_t ns, int32_t no,
+                   DevSpan* __restrict__ d_spans, int64_t* __restrict__ d_off) {
+    const int i = threadIdx.x;
+    if (i < ns) d_spans[first + i] = lay.spans[i];
+    if (i < no) d_off[first + i] = lay.sample_off[i];
+}
+
 int launch_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* sample_off,
                   int32_t n_samples, int64_t S, uint64_t* d_bits, void* ws, hipStream_t st) {
     const unsigned n_wg = (unsigned)((S + 255) / 256);
@@ -75,14 +86,25 @@ int launch_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* samp
         MM_LAUNCH_CHECK();
         return MMATTN_OK;
     }
+    // Long lists are staged into the workspace through kernel arguments as well, one batch of
+    // entries per launch: the host lists are read here, before the call returns, whatever kind
+    // of host memory they live in, and the call stays free of copy nodes.
     char* base = (char*)ws;
     DevSpan* d_spans = (DevSpan*)base;
     int64_t* d_off = (int64_t*)(base + align_up((size_t)n_spans * sizeof(DevSpan), 256));
-    if (n_spans > 0)
-        MM_HIP_TRY(hipMemcpyAsync(d_spans, spans, (size_t)n_spans * sizeof(DevSpan),
-                                  hipMemcpyHostToDevice, st));
-    MM_HIP_TRY(hipMemcpyAsync(d_off, sample_off, (size_t)(n_samples + 1) * sizeof(int64_t),
-                              hipMemcpyHostToDevice, st));
+    for (int32_t first = 0; first < n_spans || first <= n_samples; first += kInlineSpans) {
+        InlineLayout lay{};
+        const int32_t ns = std::max(0, std::min(kInlineSpans, n_spans - first));
+        const int32_t no = std::max(0, std::min(kInlineSpans, n_samples + 1 - first));
+        for (int j = 0; j < ns; ++j) {
+            const mmattn_span& sp = spans[first + j];
+            lay.spans[j] = DevSpan{sp.start, sp.len, sp.modality, sp.flags};
+        }
+        for (int i = 0; i < no; ++i) lay.sample_off[i] = sample_off[first + i];
+        hipLaunchKernelGGL(stage_lists_kernel, dim3(1), dim3(kInlineSpans), 0, st, lay, first, ns, no,
+                           d_spans, d_off);
+    }
+    MM_LAUNCH_CHECK();
     unsigned grid = (unsigned)((S + 255) / 256);
     hipLaunchKernelGGL(encode_kernel, dim3(grid), dim3(256), 0, st, d_spans, n_spans, d_off,
                        n_samples, S, d_bits);
