@@ -59,49 +59,72 @@ def plan_on_gpu(w, device, readback=True):
     return bits, W, rblocks, load_h, off_h
 
 
-def in_order_greedy_loads(Wf, P):
+def in_order_greedy_loads(W, P):
     """Harness-side list scheduling in index order (Alg. 1 as printed, no sort):
-    each block to the least-loaded rank, lowest rank on ties."""
-    load = np.zeros(P, dtype=np.float64)
-    for wb in Wf:
-        load[int(np.argmin(load))] += wb
+    each block to the least-loaded rank, lowest rank on ties.  Exact integers."""
+    load = [0] * P
+    for wb in W:
+        g = min(range(P), key=lambda r: (load[r], r))
+        load[g] += int(wb)
     return load
 
 
-def imbalance_report(device):
+def zigzag_loads(W, P):
+    """Section 2.2's split for causal masks: 2P equal chunks of consecutive blocks,
+    rank i takes chunks i and 2P-1-i."""
+    c = len(W) // (2 * P)
+    ch = [sum(int(x) for x in W[i * c:(i + 1) * c]) for i in range(2 * P)]
+    return [ch[i] + ch[2 * P - 1 - i] for i in range(P)]
+
+
+def contiguous_loads(W, P):
+    c = len(W) // P
+    return [sum(int(x) for x in W[i * c:(i + 1) * c]) for i in range(P)]
+
+
+def max_over_mean(load):
+    return float(max(load)) * len(load) / float(sum(load))
+
+
+def imbalance_report(device, workloads=(1, 3, 4, 5), with_loads=False):
     """max/mean load (in unmasked pairs) over virtual ranks for the balanced
     workloads: LPT on pair workloads (GPU), LPT on tile-count workloads (GPU
     balancer fed the number of non-empty tiles per block), next to index-order
     greedy, the zigzag split and the contiguous split; plus the tile-class
-    histogram of the N_B x N_B tile map."""
+    histogram of the N_B x N_B tile map.  with_loads: also the per-rank loads
+    behind every ratio, as exact integers (what the parity test compares)."""
     import torch
     from paper_2503_11367_amd import binding as mb
     from paper_2503_11367_amd import workloads as wl
     out = {}
-    for c in (1, 3, 4, 5):
+    for c in workloads:
         w = wl.workload(c)
         bits, W, _, load_h, _ = plan_on_gpu(w, device)
         cls, cnt, _ = mb.tile_map(bits, w.N_B, w.N_B)
         cls_h = cls.cpu().numpy()
-        Wh = W.cpu().numpy().view(np.uint64).astype(np.float64)
-        nB, P = Wh.size, w.P
-        entry = {"P": P, "lpt": float(load_h.max() * P / load_h.sum()),
+        Wh = [int(x) for x in W.cpu().numpy().view(np.uint64)]
+        nB, P = len(Wh), w.P
+        loads = {"lpt": [int(x) for x in load_h]}
+        entry = {"P": P,
                  "tiles": {"empty": int((cls_h == 0).sum()), "full": int((cls_h == 1).sum()),
                            "partial": int((cls_h == 2).sum())}}
         # Alg. 1's literal workload: non-empty tiles per block; loads still measured in pairs
         Wt = (cnt.view(nB, -1) > 0).sum(dim=1).to(torch.int64).contiguous()
         rob_t = mb.balance(Wt, P)[0].cpu().numpy()
-        lt = np.bincount(rob_t, weights=Wh, minlength=P)
-        entry["lpt_tile_count"] = float(lt.max() * P / lt.sum())
-        lg = in_order_greedy_loads(Wh, P)
-        entry["in_order"] = float(lg.max() * P / lg.sum())
+        lt = [0] * P
+        for b, g in enumerate(rob_t):
+            lt[int(g)] += Wh[b]
+        loads["lpt_tile_count"] = lt
+        loads["in_order"] = in_order_greedy_loads(Wh, P)
         if nB % (2 * P) == 0:
-            ch = Wh.reshape(2 * P, -1).sum(axis=1)
-            zz = ch[:P] + ch[::-1][:P]
-            entry["zigzag"] = float(zz.max() * P / zz.sum())
+            loads["zigzag"] = zigzag_loads(Wh, P)
         if nB % P == 0:
-            ct = Wh.reshape(P, -1).sum(axis=1)
-            entry["contiguous"] = float(ct.max() * P / ct.sum())
+            loads["contiguous"] = contiguous_loads(Wh, P)
+        for k, v in loads.items():
+            entry[k] = max_over_mean(v)
+        if with_loads:
+            entry["loads"] = loads
+            entry["tile_count_workloads"] = [int(x) for x in Wt.cpu().numpy()]
         out[w.name] = entry
     return out
 

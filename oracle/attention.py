@@ -27,7 +27,8 @@ Pins: tests/test_oracle_attention.py -- all-text = causal softmax attention
 via torch's CPU scaled_dot_product_attention, one all-covering span = unmasked
 attention, packed samples = per-sample attention, probabilities sum to 1,
 V constant => O constant, Q = 0 => mean of visible V rows, central finite
-differences for dQ/dK/dV, sum_k dS_ik = 0, union over ranks = full result,
+differences for dQ/dK/dV, sum_k dS_ik = 0 (seen from outside as sum_k dK[k,g] = 0
+and as dQ = 0 when all keys are equal), union over ranks = full result,
 torch autograd for the causal special case.
 """
 import numpy as np

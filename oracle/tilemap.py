@@ -13,7 +13,7 @@ is `tile_count_workload`.
 `tile_map_c` is the same double loop in plain C (oracle/tilemap_ref.c) for
 the 128k-token case; tests pin it to `tile_map` and both to closed forms.
 
-Pins: tests/test_oracle_mask.py, tests/test_oracle_tilemap.py -- hand-derived
+Pins: tests/test_oracle_mask.py -- hand-derived
 values for the 512-token text/image/text layout (tests/golden/tiny_tilemap.txt),
 lower-triangular FULL/PARTIAL/EMPTY pattern for all-text, closed-form totals.
 """

@@ -2,7 +2,7 @@
  * the literal double loop over (query, key) pairs, in plain C, for sequence
  * lengths where the NumPy version is too slow.  Shares nothing with the HIP
  * library.  Pinned against oracle/tilemap.py and closed forms in
- * tests/test_oracle_tilemap.py.
+ * tests/test_oracle_mask.py.
  *
  *   vis(q,k) = sample[q]==sample[k] &&
  *              ((causal[q] && k<=q && bit modality[k] of attend[q] &&

@@ -236,28 +236,157 @@ def test_workload2_full_sequence():
     sampled_dq_and_dv_sums(w, blocks, t, outs, heads=(0, 13, 31))
 
 
-@pytest.mark.parametrize("c", [3, 5])
-def test_workload_heaviest_rank_one_group(c):
-    w = wl.workload(c)
+def key_range_check(w, blocks, t, outs, g, k_lo, k_hi, max_rows):
+    """dK and dV of the keys [k_lo, k_hi) of KV head g, element by element: the
+    oracle runs on exactly the share's rows that see any of these keys (the
+    other rows contribute nothing to them), for all query heads of the group.
+    Returns the two relative L2 errors."""
+    from oracle import mask as om
+    f = fields(w.layout)
+    rep = w.Hq // w.Hkv
+    hs = slice(g * rep, (g + 1) * rep)
+    rows = oa.rows_of_blocks(blocks, w.N_B)
+    seers = np.flatnonzero(om.visible(rows, np.arange(k_lo, k_hi), f[0], f[1], f[2]).any(axis=1))
+    assert 0 < seers.size <= max_rows, seers.size
+    Q, K, V, dO = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"]), f64(t["do_bits"])
+    _, dk_ref, dv_ref = oa.backward(Q[seers][:, hs], K[:, g:g + 1], V[:, g:g + 1], dO[seers][:, hs],
+                                    rows[seers], f[0], f[1], f[2], chunk=256)
+    _, _, _, dk, dv = outs
+    ks = slice(k_lo, k_hi)
+    e_k = rel_l2(bf16_to_f64(dk[ks, g:g + 1]), dk_ref[ks])
+    e_v = rel_l2(bf16_to_f64(dv[ks, g:g + 1]), dv_ref[ks])
+    assert e_k < TOL and e_v < TOL, (k_lo, k_hi, seers.size, e_k, e_v)
+    return seers.size
+
+
+def heaviest_share(w):
     f = fields(w.layout)
     _, _, W = ot.tile_map_c(f[0], f[1], f[2], w.N_B, w.N_B)
     _, load, off, rb = ob.lpt(W, w.P)
     g = int(np.argmax(load))
-    blocks = rb[off[g]:off[g + 1]].tolist()
+    return rb[off[g]:off[g + 1]].tolist()
+
+
+def test_workload3_heaviest_rank_one_group():
+    w = wl.workload(3)
+    blocks = heaviest_share(w)
     t = make_tensors(w.tensor_seed, len(blocks) * w.N_B, w.layout.S, w.Hq, w.Hkv, w.D)
     outs = gpu_fwd_bwd(w.layout, blocks, w.N_B, t)
     sampled_dq_and_dv_sums(w, blocks, t, outs, heads=(1, w.Hq - 2))
-    if c == 3:
-        group_check(w, blocks, t, outs, g=2)
+    group_check(w, blocks, t, outs, g=2)
+
+
+def test_workload5_packed_samples_element_wise():
+    """64 / 8 heads (the only shape with eight query heads per KV head): dK and
+    dV of every key of two packed samples, one KV group each, against the oracle
+    on exactly the share's rows of that sample (rows of other samples see none
+    of its keys)."""
+    w = wl.workload(5)
+    blocks = heaviest_share(w)
+    t = make_tensors(w.tensor_seed, len(blocks) * w.N_B, w.layout.S, w.Hq, w.Hkv, w.D)
+    outs = gpu_fwd_bwd(w.layout, blocks, w.N_B, t)
+    sampled_dq_and_dv_sums(w, blocks, t, outs, heads=(1, w.Hq - 2))
+    rows = oa.rows_of_blocks(blocks, w.N_B)
+    off = np.asarray(w.layout.sample_off)
+    per_sample = np.histogram(rows, bins=off)[0]
+    # the sample with the most rows of the share among those the oracle finishes in seconds,
+    # and the one with the fewest (at least one block)
+    ok = np.flatnonzero((per_sample >= w.N_B) & (per_sample <= 1280))
+    big = int(ok[np.argmax(per_sample[ok])])
+    small = int(ok[np.argmin(per_sample[ok])])
+    assert big != small
+    for smp, g in ((big, 3), (small, 6)):
+        n = key_range_check(w, blocks, t, outs, g, int(off[smp]), int(off[smp + 1]), max_rows=1280)
+        assert n == per_sample[smp]
 
 
 def test_workload4_sampled():
+    """131072 keys, 16384 rows: dQ of sampled rows, column sums of dV, and dK / dV
+    element by element on two 128-key blocks -- one in late text, one inside an
+    image span -- for a whole KV group (oracle on the share's rows that see
+    them)."""
+    from oracle import mask as om
     w = wl.workload(4)
     f = fields(w.layout)
-    _, _, W = ot.tile_map_c(f[0], f[1], f[2], w.N_B, w.N_B)
-    _, load, off, rb = ob.lpt(W, w.P)
-    g = int(np.argmax(load))
-    blocks = rb[off[g]:off[g + 1]].tolist()
+    blocks = heaviest_share(w)
     t = make_tensors(w.tensor_seed, len(blocks) * w.N_B, w.layout.S, w.Hq, w.Hkv, w.D)
     outs = gpu_fwd_bwd(w.layout, blocks, w.N_B, t)
     sampled_dq_and_dv_sums(w, blocks, t, outs, n_rows=12, heads=(3, 30))
+    rows = oa.rows_of_blocks(blocks, w.N_B)
+    span_of = f[1]
+
+    def latest_block(in_span):
+        """Last 128-key block wholly inside a span (or wholly text) that between 384 and
+        1536 rows of the share see."""
+        for k0 in range(w.layout.S - 128, -1, -128):
+            ids = span_of[k0:k0 + 128]
+            if (ids != 0).all() != in_span or (ids == 0).all() == in_span or len(set(ids.tolist())) != 1:
+                continue
+            n = int(om.visible(rows, np.arange(k0, k0 + 128), f[0], f[1], f[2]).any(axis=1).sum())
+            if 384 <= n <= 1536:
+                return k0
+        raise AssertionError("no such block")
+
+    for in_span, g in ((False, 1), (True, 6)):
+        k0 = latest_block(in_span)
+        key_range_check(w, blocks, t, outs, g, k0, k0 + 128, max_rows=1536)
+
+
+def test_row_that_sees_no_key():
+    """Hand-built mask words (the encoder never produces such a token): one
+    token without the causal bit and outside every span sees nothing, not even
+    itself.  Forward: O = 0, LSE = -inf; backward: dQ = 0 for that row, finite
+    dK / dV that match the oracle."""
+    from oracle import mask as om
+    S, block, Hq, Hkv, D = 512, 64, 4, 2, 128
+    lay = wl.Layout(S, [(100, 150, 1)], [0, 300, S])
+    sample, span, causal, modality, attend = fields(lay)
+    blind = [77, 301, 448]                 # text tokens: span id 0
+    causal = causal.copy()
+    causal[blind] = 0
+    words = om.encode(sample, span, causal, modality, attend)
+    bits = torch.from_numpy(words.view(np.int64)).to(DEV)
+    blocks = list(range(S // block))
+    bl = torch.tensor(blocks, dtype=torch.int32, device=DEV)
+    t = make_tensors(123, S, S, Hq, Hkv, D)
+    o, lse = mb.fwd(t["q"], t["k"], t["v"], bits, bl, block)
+    dq, dk, dv = mb.bwd(t["q"], t["k"], t["v"], bits, bl, block, o, lse, t["do"])
+    torch.cuda.synchronize()
+    assert (o[blind] == 0).all() and torch.isneginf(lse[:, blind]).all()
+    assert (dq[blind] == 0).all()
+    rows = np.arange(S)
+    Q, K, V, dO = f64(t["q_bits"]), f64(t["k_bits"]), f64(t["v_bits"]), f64(t["do_bits"])
+    o_ref, lse_ref = oa.forward(Q, K, V, rows, sample, span, causal, modality=modality, attend=attend)
+    dq_ref, dk_ref, dv_ref = oa.backward(Q, K, V, dO, rows, sample, span, causal, modality=modality,
+                                         attend=attend)
+    assert np.isneginf(lse_ref[:, blind]).all() and (dq_ref[blind] == 0).all()
+    seeing = np.setdiff1d(rows, blind)
+    assert max_abs(bf16_to_f64(o), o_ref) < 2e-2 and rel_l2(bf16_to_f64(o), o_ref) < 5e-3
+    assert np.abs(lse.cpu().numpy().astype(np.float64)[:, seeing] - lse_ref[:, seeing]).max() < 4.5e-3
+    for name, got, ref in (("dq", dq, dq_ref), ("dk", dk, dk_ref), ("dv", dv, dv_ref)):
+        gg = bf16_to_f64(got)
+        assert np.isfinite(gg).all(), name
+        assert rel_l2(gg, ref) < TOL, (name, rel_l2(gg, ref))
+
+
+def test_bad_block_index_leaves_outputs_untouched():
+    """A block index outside [0, S/block) raises the status word (first int32 of
+    the workspace); dq, dk, dv keep what they held."""
+    lay = wl.Layout(512, [(100, 200, 1)], [0, 512])
+    t = make_tensors(6, 128, lay.S, 2, 1, 64)
+    bits = gpu_bits(lay)
+    o, lse = mb.fwd(t["q"], t["k"], t["v"], bits, torch.tensor([1, 2], dtype=torch.int32, device=DEV), 64)
+    ws = torch.zeros(mb.workspace_size(mb.OP_BWD, lay.S, 2, 64, 2, 1, 64), dtype=torch.uint8, device=DEV)
+    for bad in ([1, 8], [-1, 2]):
+        dq = torch.full_like(t["q"], 5.0)
+        dk = torch.full_like(t["k"], 3.0)
+        dv = torch.full_like(t["v"], -2.0)
+        mb.bwd(t["q"], t["k"], t["v"], bits, torch.tensor(bad, dtype=torch.int32, device=DEV), 64, o, lse,
+               t["do"], ws=ws, out=(dq, dk, dv))
+        torch.cuda.synchronize()
+        assert int(ws[:4].view(torch.int32)[0]) != 0
+        assert (dq == 5.0).all() and (dk == 3.0).all() and (dv == -2.0).all()
+    dq, dk, dv = mb.bwd(t["q"], t["k"], t["v"], bits, torch.tensor([1, 2], dtype=torch.int32, device=DEV), 64,
+                        o, lse, t["do"], ws=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32)[0]) == 0 and torch.isfinite(dq.float()).all()

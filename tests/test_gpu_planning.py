@@ -52,6 +52,38 @@ def test_encode_long_lists():
         assert np.array_equal(to_np_u64(gpu_bits(lay)), oracle_bits(lay))
 
 
+def test_encode_reads_host_lists_before_it_returns():
+    """The host span / offset arrays may be changed or freed as soon as the call
+    returns, also on the long-list path (pinned host memory included, where an
+    asynchronous copy would still be reading): here they are overwritten with
+    garbage right after the call, before the stream is synchronised."""
+    import ctypes
+    lay = wl.layout_random(4, S=8192, n_samples=200, max_spans=4, noncausal_prob=0.2, deny_prob=0.2)
+    n, ns = len(lay.spans), len(lay.sample_off) - 1
+    assert n > 64 and ns > 64
+    # both lists inside one pinned host buffer: spans (24 bytes each) first, then the offsets
+    pinned = torch.empty(n * 24 + (ns + 1) * 8, dtype=torch.uint8, pin_memory=True)
+    base = pinned.data_ptr()
+    spans = (mb.Span * n).from_address(base)
+    off = (ctypes.c_int64 * (ns + 1)).from_address(base + n * 24)
+    for i, ((st, ln, mod), fl) in enumerate(zip(lay.spans, lay.span_flags())):
+        spans[i] = mb.Span(int(st), int(ln), int(mod), int(fl))
+    off[:] = [int(x) for x in lay.sample_off]
+    bits = torch.zeros(lay.S, dtype=torch.int64, device=DEV)
+    ws = torch.empty(mb.workspace_size(mb.OP_ENCODE, lay.S, n, ns), dtype=torch.uint8, device=DEV)
+    # a long-running kernel ahead on the stream, so the encode kernels cannot have run yet
+    a = torch.randn(4096, 4096, device=DEV)
+    for _ in range(8):
+        a = a @ a
+        a = a / a.norm()
+    rc = mb.lib().mmattn_mask_encode(base, n, base + n * 24, ns, lay.S, bits.data_ptr(), ws.data_ptr(),
+                                     ws.numel(), torch.cuda.current_stream().cuda_stream)
+    pinned.fill_(0xEE)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np_u64(bits), oracle_bits(lay))
+
+
 @pytest.mark.parametrize("c", [1, 2, 3, 4, 5])
 def test_encode_workloads(c):
     lay = wl.workload(c).layout

@@ -1,0 +1,143 @@
+"""GPU parity where the scores leave the range the usual N(0,1) inputs keep
+them in.  The forward takes its probabilities relative to a per-row shift that
+starts at 0 and follows the running maximum only when the two drift far apart
+(section 3.2.2's online softmax, with a lazy shift); these cases make the shift
+move, up and down, inside one workgroup and across the list slices whose
+partial results are aggregated afterwards, and feed the backward an LSE far
+from 0.  Same tolerances as everywhere: O max-abs 2e-2 and relative L2 5e-3,
+LSE 4.5e-3 absolute, gradients relative L2 1e-2."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from paper_2503_11367_amd import binding as mb
+from paper_2503_11367_amd import workloads as wl
+
+from gpu_util import DEV, bf16_to_f64, f64, fields, gpu_bits, make_tensors, max_abs, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TOL_MAX, TOL_L2, TOL_LSE, TOL_GRAD = 2e-2, 5e-3, 4.5e-3, 1e-2
+
+
+def set_feature(t, name, value):
+    """Overwrite head-dim element 0 of tensor `name` (all heads) with `value`
+    (a scalar or one value per row; exactly representable in bf16), on the host
+    pattern and on the device copy."""
+    x = wl.bf16_bits_to_f32(t[name + "_bits"]).copy()
+    v = np.asarray(value, dtype=np.float32)
+    x[:, :, 0] = v if v.ndim == 0 else v[:, None]
+    b = wl.f32_to_bf16_bits(x)
+    assert np.array_equal(wl.bf16_bits_to_f32(b), x)
+    t[name + "_bits"] = b
+    t[name] = mb.bf16_from_bits(b, DEV)
+
+
+def check(lay, blocks, block, Hq, Hkv, D, seed, scale=None, prepare=None, lse_far=None, group=None):
+    """GPU forward and backward on all heads; the oracle on all of them, or (group
+    given) on the query heads of that KV head, which gives complete dK / dV for it."""
+    f = fields(lay)
+    n_loc = len(blocks) * block
+    t = make_tensors(seed, n_loc, lay.S, Hq, Hkv, D)
+    rows = oa.rows_of_blocks(blocks, block)
+    if prepare is not None:
+        prepare(t, rows)
+    bits = gpu_bits(lay)
+    bl = torch.tensor(blocks, dtype=torch.int32, device=DEV)
+    o, lse = mb.fwd(t["q"], t["k"], t["v"], bits, bl, block, scale=scale)
+    dq, dk, dv = mb.bwd(t["q"], t["k"], t["v"], bits, bl, block, o, lse, t["do"], scale=scale)
+    torch.cuda.synchronize()
+    rep = Hq // Hkv
+    hs = slice(0, Hq) if group is None else slice(group * rep, (group + 1) * rep)
+    gs = slice(0, Hkv) if group is None else slice(group, group + 1)
+    Q, K, V, dO = f64(t["q_bits"])[:, hs], f64(t["k_bits"])[:, gs], f64(t["v_bits"])[:, gs], f64(t["do_bits"])[:, hs]
+    o_ref, lse_ref = oa.forward(Q, K, V, rows, f[0], f[1], f[2], scale=scale)
+    if lse_far is not None:                # the case does what it is meant to do
+        assert np.abs(lse_ref).max() > lse_far, np.abs(lse_ref).max()
+    o_gpu = bf16_to_f64(o[:, hs])
+    assert np.isfinite(o_gpu).all()
+    errs = {"o_max": max_abs(o_gpu, o_ref), "o_l2": rel_l2(o_gpu, o_ref),
+            "lse": max_abs(lse[hs].cpu().numpy().astype(np.float64), lse_ref)}
+    assert errs["o_max"] < TOL_MAX and errs["o_l2"] < TOL_L2 and errs["lse"] < TOL_LSE, errs
+    dq_ref, dk_ref, dv_ref = oa.backward(Q, K, V, dO, rows, f[0], f[1], f[2], scale=scale)
+    for name, got, ref in (("dq", dq[:, hs], dq_ref), ("dk", dk[:, gs], dk_ref), ("dv", dv[:, gs], dv_ref)):
+        g = bf16_to_f64(got)
+        assert np.isfinite(g).all(), name
+        errs[name] = rel_l2(g, ref)
+        assert errs[name] < TOL_GRAD, errs
+    print(errs)
+    return errs
+
+
+# 16 q-tiles x 32 head pairs = 512 work items: the lists are not cut; oracle on one KV group
+
+
+def whole(seed, group, **kw):
+    return check(wl.layout_random(92, S=2048, n_samples=1, max_spans=3), list(range(16)), 128, 64, 16, 128,
+                 seed=seed, group=group, **kw)
+
+
+LAY_SPLIT = lambda: wl.layout_random(91, S=4096, n_samples=2)          # few work items: lists cut into slices
+
+
+@pytest.mark.parametrize("factor", [4.0, 16.0])
+def test_large_softmax_scale(factor):
+    """scale = factor / sqrt(D): at 16 the row maxima reach about 90 in base-2
+    units (past the 64 the shift tolerates) and the softmax is close to one-hot;
+    with and without list slices, both head dims."""
+    whole(201, 3, scale=factor / np.sqrt(128.0),
+          lse_far=40.0 if factor == 16.0 else None)
+    # 11 q-tiles x 2 head pairs: every list cut into slices, aggregated by the combine kernel
+    check(LAY_SPLIT(), list(range(0, 32, 3)), 128, 4, 2, 128, seed=202, scale=factor / np.sqrt(128.0))
+    check(LAY_SPLIT(), [31, 2, 17], 128, 2, 2, 64, seed=203, scale=factor / 8.0)
+
+
+def test_all_scores_far_above_zero():
+    """Every score carries the same offset of +130.6 base-2 units (one head-dim
+    element is 32 in every query and key; softmax does not see a common offset):
+    the shift has to move up at once, the probabilities are as spread out as
+    usual."""
+    def prep(t, rows):
+        set_feature(t, "q", 32.0)
+        set_feature(t, "k", 32.0)
+    whole(204, 6, prepare=prep, lse_far=85.0)
+    check(LAY_SPLIT(), list(range(0, 32, 3)), 128, 4, 2, 128, seed=205, prepare=prep, lse_far=85.0)
+
+
+def test_scores_far_below_zero_then_far_above():
+    """The first 1024 keys score 130 base-2 units below 0 with every query, the
+    later ones 130 above: rows that see only early keys need the shift to move
+    down (their probabilities would all underflow otherwise), the others move
+    down first and then up by 260, which wipes the early keys' share; the list
+    slices of one q-tile end with shifts 260 apart."""
+    def prep(t, rows):
+        set_feature(t, "q", 32.0)
+        set_feature(t, "k", np.where(np.arange(t["k_bits"].shape[0]) < 1024, -32.0, 32.0))
+    whole(206, 9, prepare=prep, lse_far=85.0)
+    check(LAY_SPLIT(), list(range(0, 32, 3)), 128, 4, 2, 128, seed=207, prepare=prep, lse_far=85.0)
+    check(LAY_SPLIT(), list(range(32)), 128, 2, 1, 64, seed=208,
+          prepare=lambda t, rows: (set_feature(t, "q", 32.0),
+                                   set_feature(t, "k", np.where(np.arange(4096) % 1024 < 512, -16.0, 16.0))))
+
+
+def test_scores_far_above_zero_then_far_below():
+    """The reverse order: once a row has seen the high-scoring early keys the low
+    ones contribute nothing and the shift must stay where it is."""
+    def prep(t, rows):
+        set_feature(t, "q", 32.0)
+        set_feature(t, "k", np.where(np.arange(t["k_bits"].shape[0]) < 1024, 32.0, -32.0))
+    whole(209, 12, prepare=prep, lse_far=85.0)
+    check(LAY_SPLIT(), list(range(0, 32, 3)), 128, 4, 2, 128, seed=210, prepare=prep)
+
+
+def test_per_row_offsets():
+    """Every query row has its own offset (-160 ... +160 base-2 units): rows of
+    one wavefront move their shifts in different directions at different
+    times."""
+    def prep(t, rows):
+        n = t["q_bits"].shape[0]
+        set_feature(t, "q", ((np.arange(n) * 7) % 81 - 40).astype(np.float32))
+        set_feature(t, "k", 32.0)
+    whole(211, 15, prepare=prep, lse_far=100.0)
+    check(LAY_SPLIT(), [30, 1, 12, 7], 128, 2, 2, 64, seed=212, prepare=prep)

@@ -200,3 +200,17 @@ def test_dv_column_sums_property():
     f, rows, Q, K, V, dO = setup(lay, 4, 2, 8, 9)
     dQ, dK, dV = oa.backward(Q, K, V, dO, rows, f[0], f[1], f[2])
     assert np.allclose(dV.sum(axis=0), dO.reshape(80, 2, 2, 8).sum(axis=(0, 2)), atol=1e-12)
+
+
+def test_ds_rows_sum_to_zero():
+    """sum_k dS_ik = sum_k P_ik dP_ik - Delta_i = 0 for every row, whatever the mask.
+    Seen from outside: sum_k dK[k,g] = scale sum_i (sum_k dS_ik) Q_i = 0, and when all
+    keys of a head are the same vector dQ = scale (sum_k dS_ik) K = 0."""
+    lay = wl.layout_random(13, 96, n_samples=2, noncausal_prob=0.3)
+    f, rows, Q, K, V, dO = setup(lay, 4, 2, 8, 10, rows=oa.rows_of_blocks([1, 4, 5], 16))
+    dQ, dK, dV = oa.backward(Q, K, V, dO, rows, f[0], f[1], f[2])
+    assert np.abs(dK).max() > 1e-2
+    assert np.allclose(dK.sum(axis=0), 0.0, atol=1e-12)
+    K_same = np.broadcast_to(K[:1], K.shape).copy()
+    dQ2, dK2, _ = oa.backward(Q, K_same, V, dO, rows, f[0], f[1], f[2])
+    assert np.allclose(dQ2, 0.0, atol=1e-12) and np.abs(dK2).max() > 1e-3

@@ -85,6 +85,29 @@ def test_paper_bitfield_example():
     assert int(bits[4]) & 0xFF == 0xFF        # text attends all modalities
 
 
+def test_word_written_out_bit_by_bit():
+    """One token with every field set, against the word typed out from the layout
+    (attend-set bits 0-7, modality 8-11, span id 12-27, sample id 28-43, look-back
+    window 44-59, causal bit 63): sample 3, span 5, modality 2, window 7, causal,
+    attends everything  ->  0x8000_7000_3000_52FF."""
+    one = lambda x: np.array([x], dtype=np.int64)
+    w = om.encode(one(3), one(5), one(1), one(2), attend=one(0xFF), window=one(7))
+    assert int(w[0]) == 0x80007000300052FF
+    # every field alone lands where the layout says, and nowhere else
+    assert int(om.encode(one(0), one(0), one(0), one(0), attend=one(0))[0]) == 0
+    assert int(om.encode(one(1), one(0), one(0), one(0), attend=one(0))[0]) == 1 << 28
+    assert int(om.encode(one(0), one(1), one(0), one(0), attend=one(0))[0]) == 1 << 12
+    assert int(om.encode(one(0), one(0), one(0), one(1), attend=one(0))[0]) == 1 << 8
+    assert int(om.encode(one(0), one(0), one(0), one(0), attend=one(0), window=one(1))[0]) == 1 << 44
+    assert int(om.encode(one(0xFFFF), one(0), one(0), one(0), attend=one(0))[0]) == 0xFFFF << 28
+    assert int(om.encode(one(0), one(0xFFFF), one(0), one(0), attend=one(0))[0]) == 0xFFFF << 12
+    assert int(om.encode(one(0), one(0), one(0), one(0), attend=one(0), window=one(0xFFFF))[0]) == 0xFFFF << 44
+    # a packed layout through the layout expansion: token 70 is in sample 1, span 2 (audio)
+    lay = wl.Layout(128, [(10, 20, wl.IMAGE), (64, 16, wl.AUDIO)], [0, 50, 128])
+    f = fields(lay)
+    assert int(om.encode(*f)[70]) == (1 << 63) | (1 << 28) | (2 << 12) | (wl.AUDIO << 8) | 0xFF
+
+
 def test_attend_set_rows_by_hand():
     """text[0:2] audio[2:4] text[4:5] image[5:8] text[8:9]; the image span does not
     attend audio: its rows lose the two audio columns, nothing else changes
@@ -327,7 +350,7 @@ def test_c_tilemap_matches_numpy(seed):
         assert np.array_equal(x, y)
 
 
-@pytest.mark.parametrize("c", [2, 3, 5])
+@pytest.mark.parametrize("c", [2, 3, 4, 5])
 def test_workload_totals_closed_form(c):
     w = wl.workload(c)
     sample, span, causal = fields(w.layout)[:3]
@@ -337,3 +360,6 @@ def test_workload_totals_closed_form(c):
         assert int(W.sum()) == 35653632
     if c == 3:
         assert int(W.sum()) == 553961064
+    if c == 4:
+        # 131072 * 131073 / 2 + 24 * 4096 * 4095 / 2; beyond 2^32, so the workloads are 64-bit
+        assert int(W.sum()) == 8791277568
