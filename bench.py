@@ -27,10 +27,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published figure
-# HBM bytes per launch (fetched + written) of the dominant kernel, from the rocprofv3
-# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/attention_kernels_vlm_8k.md
-# (scaled by the copy-kernel calibration given there); None for workloads not profiled.
-MEASURED_TRAFFIC_BYTES = {("vlm_8k", "dkv_kernel"): 443705661}
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch (fetched + written) of `kernel` on `workload` from the
+    table of rocprofv3 FETCH_SIZE / WRITE_SIZE readings kept beside the profile
+    summaries (profiles/hbm_traffic.txt, rewritten whenever the profiles are
+    regenerated; already scaled by the copy-kernel calibration stated there).
+    None when that pair has not been profiled."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 4 and not line.startswith("#") and f[0] == workload and f[1] == kernel:
+                return int(f[2]) + int(f[3])
+    except OSError:
+        pass
+    return None
 
 
 def build_inputs(w, device):
@@ -216,6 +229,158 @@ def cpu_baseline(w, blocks, host_q, host_k, host_v, host_do, groups, pairs):
                       f"{n_heads} of {w.Hq} Q heads ({groups} of {w.Hkv} KV groups)"}
 
 
+class Share:
+    """Inputs of one workload resident on the GPU: K, V for the whole sequence, Q
+    and dO for the heaviest rank's blocks, outputs and workspaces."""
+
+    def __init__(self, w, device):
+        import torch
+        from paper_2503_11367_amd import binding as mb
+        from paper_2503_11367_amd import workloads as wl
+        self.w, self.device = w, device
+        S = w.layout.S
+        self.host, self.dev = build_inputs(w, device)
+        # plan once up front to size the share-dependent inputs (Q_loc, dO_loc)
+        self.bits, _, self.rblocks, load_h, off_h = plan_on_gpu(w, device)
+        self.load_h, self.off_h = load_h, off_h
+        g = int(np.argmax(load_h))                 # heaviest rank (lowest id on ties)
+        self.rank = g
+        self.nb = int(off_h[g + 1] - off_h[g])
+        self.n_loc = self.nb * w.N_B
+        self.pairs = int(load_h[g])
+        self.host["q"] = wl.normal_bf16(w.tensor_seed * 10 + 0, (self.n_loc, w.Hq, w.D))
+        self.host["do"] = wl.normal_bf16(w.tensor_seed * 10 + 3, (self.n_loc, w.Hq, w.D))
+        dev = self.dev
+        dev["q"] = mb.bf16_from_bits(self.host["q"], device)
+        dev["do"] = mb.bf16_from_bits(self.host["do"], device)
+        self.o = torch.empty_like(dev["q"])
+        self.lse = torch.empty((w.Hq, self.n_loc), dtype=torch.float32, device=device)
+        self.dq = torch.empty_like(dev["q"])
+        self.dk = torch.empty_like(dev["k"])
+        self.dv = torch.empty_like(dev["v"])
+        self.ws_f = torch.empty(mb.workspace_size(mb.OP_FWD, S, self.nb, w.N_B, w.Hq, w.Hkv, w.D),
+                                dtype=torch.uint8, device=device)
+        self.ws_b = torch.empty(mb.workspace_size(mb.OP_BWD, S, self.nb, w.N_B, w.Hq, w.Hkv, w.D),
+                                dtype=torch.uint8, device=device)
+        # With several virtual ranks the host reads the loads and offsets back to pick the
+        # heaviest rank's block list (its length is a host-side argument of the attention
+        # calls).  With one rank the share is the whole list the balancer wrote: nothing to
+        # read, and the step runs without a host synchronisation.
+        self.readback = w.P > 1
+
+    def share_blocks(self):
+        return self.rblocks[int(self.off_h[self.rank]):int(self.off_h[self.rank + 1])]
+
+    def step(self, call_events=None):
+        """One pass of the whole path.  call_events: optional (fwd start, fwd stop, bwd
+        start, bwd stop) events recorded around the two attention calls."""
+        from paper_2503_11367_amd import binding as mb
+        w, dev = self.w, self.dev
+        bits_, _, rblocks_, load_, off_ = plan_on_gpu(w, self.device, self.readback)
+        if self.readback:
+            g_ = int(np.argmax(load_))
+            bl = rblocks_[int(off_[g_]):int(off_[g_ + 1])]
+        else:
+            bl = rblocks_
+        if call_events:
+            call_events[0].record()
+        mb.fwd(dev["q"], dev["k"], dev["v"], bits_, bl, w.N_B, ws=self.ws_f, out=(self.o, self.lse))
+        if call_events:
+            call_events[1].record()
+            call_events[2].record()
+        mb.bwd(dev["q"], dev["k"], dev["v"], bits_, bl, w.N_B, self.o, self.lse, dev["do"], ws=self.ws_b,
+               out=(self.dq, self.dk, self.dv))
+        if call_events:
+            call_events[3].record()
+
+
+STAGE_KERNEL = {"fwd": "fwd_kernel", "dkv": "dkv_kernel", "dq": "dq_kernel"}
+
+
+def measure(sh, steps, warmup, all_stage_events=False, after_warmup=None):
+    """Warm up, then time exactly `steps` steps between two synchronisations (mean),
+    with one event per step for the median and the minimum, and the dominant kernel
+    (dK/dV) bracketed by events inside the timed region; then a short second pass with
+    events around all four main kernels and around the two attention calls."""
+    import torch
+    from paper_2503_11367_amd import binding as mb
+    w = sh.w
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    for _ in range(warmup):
+        sh.step()
+    torch.cuda.synchronize()
+    if after_warmup:
+        after_warmup()
+
+    # HIP events recorded by the library around each main kernel, one pair per step
+    stages = {"fwd": mb.STAGE_FWD, "dkv": mb.STAGE_DKV, "dkv_reduce": mb.STAGE_DKV_REDUCE,
+              "dq": mb.STAGE_DQ}
+    evs = {n: [(ev(), ev()) for _ in range(steps)] for n in stages}
+    marks = [ev() for _ in range(steps + 1)]
+    for n in stages:
+        for a, b in evs[n]:
+            a.record(); b.record()             # materialise the handles
+    for m in marks:
+        m.record()
+    torch.cuda.synchronize()
+
+    # Timed region: only the dominant kernel (the key-outer backward pass, 8 of the 14
+    # contractions) is bracketed by events; every event record costs a few microseconds on
+    # the stream.  The other kernels are timed in a second, untimed pass of the same steps.
+    timed = stages if all_stage_events else {"dkv": stages["dkv"]}
+    t0 = time.perf_counter()
+    for i in range(steps):
+        for n, sid in timed.items():
+            mb.stage_events(sid, evs[n][i][0].cuda_event, evs[n][i][1].cuda_event)
+        marks[i].record()
+        sh.step()
+    marks[steps].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for sid in stages.values():
+        mb.stage_events(sid, 0, 0)
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    # step i as the stream saw it: from its first launch to the next step's first launch
+    per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+    kern = {n: [a.elapsed_time(b) for a, b in evs[n]] for n in timed}
+    n2 = min(steps, 5)
+    calls = [(ev(), ev(), ev(), ev()) for _ in range(n2)]
+    for i in range(n2):
+        for n, sid in stages.items():
+            mb.stage_events(sid, evs[n][i][0].cuda_event, evs[n][i][1].cuda_event)
+        sh.step(calls[i])
+    torch.cuda.synchronize()
+    for sid in stages.values():
+        mb.stage_events(sid, 0, 0)
+    for n in stages:
+        if n not in kern:
+            kern[n] = [a.elapsed_time(b) for a, b in evs[n][:n2]]
+    kern_ms = {n: float(np.mean(v)) for n, v in kern.items()}
+    call_ms = {"fwd": float(np.mean([c[0].elapsed_time(c[1]) for c in calls])),
+               "bwd": float(np.mean([c[2].elapsed_time(c[3]) for c in calls]))}
+    flops_fwd = 4.0 * w.D * w.Hq * sh.pairs
+    flops_bwd = 10.0 * w.D * w.Hq * sh.pairs
+    bwd_ms = kern_ms["dkv"] + kern_ms["dkv_reduce"] + kern_ms["dq"]
+    tf = lambda fl, ms: fl / (ms * 1e-3) / 1e12
+    return {
+        "ms_per_step": ms_per_step, "ms_per_step_median": float(np.median(per_step)),
+        "ms_per_step_min": float(np.min(per_step)),
+        "value": tf(flops_fwd + flops_bwd, ms_per_step),
+        "kernels_ms": kern_ms,
+        "kernels_ms_median": {n: float(np.median(v)) for n, v in kern.items()},
+        "kernels_ms_min": {n: float(np.min(v)) for n, v in kern.items()},
+        # whole mmattn_fwd / mmattn_bwd calls: plan, preparation pass and aggregation included
+        "calls_ms": call_ms,
+        # main kernels only (fwd_kernel; dkv_kernel + dkv_reduce_kernel + dq_kernel)
+        "tflops": {"fwd": tf(flops_fwd, kern_ms["fwd"]), "bwd": tf(flops_bwd, bwd_ms)},
+        "frac_of_peak": {"fwd": tf(flops_fwd, kern_ms["fwd"]) / PEAK_BF16_TFLOPS,
+                         "bwd": tf(flops_bwd, bwd_ms) / PEAK_BF16_TFLOPS},
+        "frac_of_peak_whole_calls": {"fwd": tf(flops_fwd, call_ms["fwd"]) / PEAK_BF16_TFLOPS,
+                                     "bwd": tf(flops_bwd, call_ms["bwd"]) / PEAK_BF16_TFLOPS},
+        "timed_stages": sorted(timed),
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -224,7 +389,7 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2, the metric's config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path-only", action="store_true",
-                    help="skip the side reports (imbalance of the other workloads, matrix-pipe "
+                    help="skip the side reports (the other workloads, imbalance, matrix-pipe "
                          "ceiling, staged forward) so that a profiler sees the timed path only")
     ap.add_argument("--all-stage-events", action="store_true",
                     help="bracket all four main kernels with events inside the timed region "
@@ -249,128 +414,44 @@ def main():
     mb.lib()
 
     w = wl.workload(args.workload)
-    lay = w.layout
-    S = lay.S
-    host, dev = build_inputs(w, device)
+    sh = Share(w, device)
 
-    # plan once up front to size the share-dependent inputs (Q_loc, dO_loc)
-    bits, W, rblocks, load_h, off_h = plan_on_gpu(w, device)
-    g = int(np.argmax(load_h))                 # heaviest rank (lowest id on ties)
-    nb = int(off_h[g + 1] - off_h[g])
-    n_loc = nb * w.N_B
-    pairs = int(load_h[g])
-    host["q"] = wl.normal_bf16(w.tensor_seed * 10 + 0, (n_loc, w.Hq, w.D))
-    host["do"] = wl.normal_bf16(w.tensor_seed * 10 + 3, (n_loc, w.Hq, w.D))
-    dev["q"] = mb.bf16_from_bits(host["q"], device)
-    dev["do"] = mb.bf16_from_bits(host["do"], device)
+    def calibrate():
+        if args.calibrate_copy:
+            src = torch.empty(256 << 20, dtype=torch.uint8, device=device)
+            dst = torch.empty_like(src)
+            src.fill_(1)
+            dst.copy_(src)
+            torch.cuda.synchronize()
 
-    o = torch.empty_like(dev["q"])
-    lse = torch.empty((w.Hq, n_loc), dtype=torch.float32, device=device)
-    dq = torch.empty_like(dev["q"])
-    dk = torch.empty_like(dev["k"])
-    dv = torch.empty_like(dev["v"])
-    ws_f = torch.empty(mb.workspace_size(mb.OP_FWD, S, nb, w.N_B, w.Hq, w.Hkv, w.D),
-                       dtype=torch.uint8, device=device)
-    ws_b = torch.empty(mb.workspace_size(mb.OP_BWD, S, nb, w.N_B, w.Hq, w.Hkv, w.D),
-                       dtype=torch.uint8, device=device)
-
-    # With several virtual ranks the host reads the loads and offsets back to pick the
-    # heaviest rank's block list (its length is a host-side argument of the attention
-    # calls).  With one rank the share is the whole list the balancer wrote: nothing to
-    # read, and the step runs without a host synchronisation.
-    readback = w.P > 1
-
-    def step():
-        bits_, _, rblocks_, load_, off_ = plan_on_gpu(w, device, readback)
-        if readback:
-            g_ = int(np.argmax(load_))
-            bl = rblocks_[int(off_[g_]):int(off_[g_ + 1])]
-        else:
-            bl = rblocks_
-        mb.fwd(dev["q"], dev["k"], dev["v"], bits_, bl, w.N_B, ws=ws_f, out=(o, lse))
-        mb.bwd(dev["q"], dev["k"], dev["v"], bits_, bl, w.N_B, o, lse, dev["do"], ws=ws_b,
-               out=(dq, dk, dv))
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    if args.calibrate_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=device)
-        dst = torch.empty_like(src)
-        src.fill_(1)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    # HIP events recorded by the library around each main kernel, one pair per step
-    stages = {"fwd": mb.STAGE_FWD, "dkv": mb.STAGE_DKV, "dkv_reduce": mb.STAGE_DKV_REDUCE,
-              "dq": mb.STAGE_DQ}
-    evs = {n: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for _ in range(args.steps)] for n in stages}
-    for n in stages:
-        for a, b in evs[n]:
-            a.record(); b.record()             # materialise the handles
-    torch.cuda.synchronize()
-
-    # Timed region: only the dominant kernel (the key-outer backward pass, 8 of the 14
-    # contractions) is bracketed by events; every event record costs a few microseconds on
-    # the stream.  The other kernels are timed in a second, untimed pass of the same steps.
-    timed = stages if args.all_stage_events else {"dkv": stages["dkv"]}
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        for n, sid in timed.items():
-            mb.stage_events(sid, evs[n][i][0].cuda_event, evs[n][i][1].cuda_event)
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for sid in stages.values():
-        mb.stage_events(sid, 0, 0)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = {n: float(np.mean([a.elapsed_time(b) for a, b in evs[n]])) for n in timed}
-    if not args.all_stage_events:
-        n2 = min(args.steps, 5)
-        for i in range(n2):
-            for n, sid in stages.items():
-                mb.stage_events(sid, evs[n][i][0].cuda_event, evs[n][i][1].cuda_event)
-            step()
-        torch.cuda.synchronize()
-        for sid in stages.values():
-            mb.stage_events(sid, 0, 0)
-        for n in stages:
-            if n not in kern_ms:
-                kern_ms[n] = float(np.mean([a.elapsed_time(b) for a, b in evs[n][:n2]]))
-    flops_fwd = 4.0 * w.D * w.Hq * pairs
-    flops_bwd = 10.0 * w.D * w.Hq * pairs
-    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+    m = measure(sh, args.steps, args.warmup, args.all_stage_events, calibrate)
+    kern_ms = m["kernels_ms"]
 
     # dominant kernel and its algorithmic flops: dkv runs S, dP, dV, dK (8*D*Hq*pairs),
     # dq's own product is dQ (2*D*Hq*pairs), fwd runs S and PV (4*D*Hq*pairs)
-    alg = {"fwd": flops_fwd, "dkv": 8.0 * w.D * w.Hq * pairs, "dq": 2.0 * w.D * w.Hq * pairs}
-    kname = {"fwd": "fwd_kernel", "dkv": "dkv_kernel", "dq": "dq_kernel"}
-    bwd_ms = kern_ms["dkv"] + kern_ms["dkv_reduce"] + kern_ms["dq"]
+    alg = {"fwd": 4.0 * w.D * w.Hq * sh.pairs, "dkv": 8.0 * w.D * w.Hq * sh.pairs,
+           "dq": 2.0 * w.D * w.Hq * sh.pairs}
     dom = max(alg, key=lambda n: kern_ms[n])
-    dom_in_timed_region = dom in timed
     achieved = alg[dom] / (kern_ms[dom] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": kname[dom], "achieved": achieved,
+    roofline = {"bound": "mfma", "kernel": STAGE_KERNEL[dom], "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, kname[dom])), "avg_ms": kern_ms[dom],
-                "events_in_timed_region": dom_in_timed_region}
+                "traffic": measured_traffic(w.name, STAGE_KERNEL[dom]), "avg_ms": kern_ms[dom],
+                "median_ms": m["kernels_ms_median"][dom], "min_ms": m["kernels_ms_min"][dom],
+                "events_in_timed_region": dom in m["timed_stages"]}
 
     out = {
         "metric": "masked-attention effective TFLOP/s (unmasked pairs) fwd+bwd",
-        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "value": m["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "S": S, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "N_B": w.N_B,
-                   "P": w.P, "rank": g, "n_loc": n_loc, "pairs": pairs,
-                   "host_readback_in_step": readback},
+        "config": {"workload": w.name, "S": w.layout.S, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "N_B": w.N_B,
+                   "P": w.P, "rank": sh.rank, "n_loc": sh.n_loc, "pairs": sh.pairs,
+                   "host_readback_in_step": sh.readback},
         "roofline": roofline,
-        "kernels_ms": kern_ms,
-        "tflops": {"fwd": flops_fwd / (kern_ms["fwd"] * 1e-3) / 1e12,
-                   "bwd": flops_bwd / (bwd_ms * 1e-3) / 1e12},
-        "frac_of_peak": {"fwd": flops_fwd / (kern_ms["fwd"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                         "bwd": flops_bwd / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
     }
+    for k in ("ms_per_step_median", "ms_per_step_min", "kernels_ms", "kernels_ms_median", "kernels_ms_min",
+              "calls_ms", "tflops", "frac_of_peak", "frac_of_peak_whole_calls"):
+        out[k] = m[k]
 
     # planning time (encode + tile map + balance + readback), outside the timed region
     torch.cuda.synchronize()
@@ -382,14 +463,41 @@ def main():
     if not args.path_only:
         out["imbalance"] = imbalance_report(device)
         out["mfma_ceiling_tflops"] = mfma_ceiling(device)
-        out["kv_staging"] = kv_staging_report(dev, bits, rblocks[int(off_h[g]):int(off_h[g + 1])], w)
+        out["kv_staging"] = kv_staging_report(sh.dev, sh.bits, sh.share_blocks(), w)
 
+    cpu = None
     if not args.no_cpu_baseline:
-        blocks = rblocks[int(off_h[g]):int(off_h[g + 1])].cpu().numpy()
+        blocks = sh.share_blocks().cpu().numpy()
         # two KV groups at the 8k workload is 10-15 s of oracle time; one for the long ones
-        groups = min(w.Hkv, 2 if S <= 8192 else 1)
-        out["cpu_baseline"] = cpu_baseline(w, blocks, host["q"], host["k"], host["v"], host["do"],
-                                           groups, pairs)
+        groups = min(w.Hkv, 2 if w.layout.S <= 8192 else 1)
+        cpu = cpu_baseline(w, blocks, sh.host["q"], sh.host["k"], sh.host["v"], sh.host["do"],
+                           groups, sh.pairs)
+
+    if not args.path_only:
+        # the other balanced workloads (heaviest rank's share, whole steps): 3 warm-up and 5
+        # timed steps each; the headline stays the workload above
+        del sh
+        torch.cuda.empty_cache()
+        others = {}
+        for c in (3, 4, 5):
+            if c == args.workload:
+                continue
+            wo = wl.workload(c)
+            so = Share(wo, device)
+            mo = measure(so, 5, 3)
+            others[wo.name] = {"n_loc": so.n_loc, "S": wo.layout.S, "Hq": wo.Hq, "Hkv": wo.Hkv,
+                               "P": wo.P, "pairs": so.pairs, "ms_per_step": mo["ms_per_step"],
+                               "ms_per_step_median": mo["ms_per_step_median"],
+                               "ms_per_step_min": mo["ms_per_step_min"], "value": mo["value"],
+                               "tflops": mo["tflops"], "frac_of_peak": mo["frac_of_peak"],
+                               "frac_of_peak_whole_calls": mo["frac_of_peak_whole_calls"],
+                               "kernels_ms": mo["kernels_ms"], "calls_ms": mo["calls_ms"],
+                               "dkv_avg_ms": mo["kernels_ms"]["dkv"]}
+            del so
+            torch.cuda.empty_cache()
+        out["workloads"] = others
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 

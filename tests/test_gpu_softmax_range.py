@@ -65,15 +65,13 @@ def check(lay, blocks, block, Hq, Hkv, D, seed, scale=None, prepare=None, lse_fa
         g = bf16_to_f64(got)
         assert np.isfinite(g).all(), name
         errs[name] = rel_l2(g, ref)
-        assert errs[name] < TOL_GRAD, errs
     print(errs)
+    assert max(errs["dq"], errs["dk"], errs["dv"]) < TOL_GRAD, errs
     return errs
 
 
-# 16 q-tiles x 32 head pairs = 512 work items: the lists are not cut; oracle on one KV group
-
-
 def whole(seed, group, **kw):
+    """16 q-tiles x 32 head pairs = 512 work items: the lists are not cut; oracle on one KV group."""
     return check(wl.layout_random(92, S=2048, n_samples=1, max_spans=3), list(range(16)), 128, 64, 16, 128,
                  seed=seed, group=group, **kw)
 
@@ -95,12 +93,14 @@ def test_large_softmax_scale(factor):
 
 def test_all_scores_far_above_zero():
     """Every score carries the same offset of +130.6 base-2 units (one head-dim
-    element is 32 in every query and key; softmax does not see a common offset):
+    element is 128 in every query and 8 in every key; softmax does not see a common
+    offset; the key-side value is kept small because dQ multiplies sum_k dS_ik, which
+    is zero only up to the rounding of the bf16 O behind Delta, by it):
     the shift has to move up at once, the probabilities are as spread out as
     usual."""
     def prep(t, rows):
-        set_feature(t, "q", 32.0)
-        set_feature(t, "k", 32.0)
+        set_feature(t, "q", 128.0)
+        set_feature(t, "k", 8.0)
     whole(204, 6, prepare=prep, lse_far=85.0)
     check(LAY_SPLIT(), list(range(0, 32, 3)), 128, 4, 2, 128, seed=205, prepare=prep, lse_far=85.0)
 
@@ -112,21 +112,21 @@ def test_scores_far_below_zero_then_far_above():
     down first and then up by 260, which wipes the early keys' share; the list
     slices of one q-tile end with shifts 260 apart."""
     def prep(t, rows):
-        set_feature(t, "q", 32.0)
-        set_feature(t, "k", np.where(np.arange(t["k_bits"].shape[0]) < 1024, -32.0, 32.0))
+        set_feature(t, "q", 128.0)
+        set_feature(t, "k", np.where(np.arange(t["k_bits"].shape[0]) < 1024, -8.0, 8.0))
     whole(206, 9, prepare=prep, lse_far=85.0)
     check(LAY_SPLIT(), list(range(0, 32, 3)), 128, 4, 2, 128, seed=207, prepare=prep, lse_far=85.0)
     check(LAY_SPLIT(), list(range(32)), 128, 2, 1, 64, seed=208,
-          prepare=lambda t, rows: (set_feature(t, "q", 32.0),
-                                   set_feature(t, "k", np.where(np.arange(4096) % 1024 < 512, -16.0, 16.0))))
+          prepare=lambda t, rows: (set_feature(t, "q", 64.0),
+                                   set_feature(t, "k", np.where(np.arange(4096) % 1024 < 512, -8.0, 8.0))))
 
 
 def test_scores_far_above_zero_then_far_below():
     """The reverse order: once a row has seen the high-scoring early keys the low
     ones contribute nothing and the shift must stay where it is."""
     def prep(t, rows):
-        set_feature(t, "q", 32.0)
-        set_feature(t, "k", np.where(np.arange(t["k_bits"].shape[0]) < 1024, 32.0, -32.0))
+        set_feature(t, "q", 128.0)
+        set_feature(t, "k", np.where(np.arange(t["k_bits"].shape[0]) < 1024, 8.0, -8.0))
     whole(209, 12, prepare=prep, lse_far=85.0)
     check(LAY_SPLIT(), list(range(0, 32, 3)), 128, 4, 2, 128, seed=210, prepare=prep)
 
@@ -137,7 +137,7 @@ def test_per_row_offsets():
     times."""
     def prep(t, rows):
         n = t["q_bits"].shape[0]
-        set_feature(t, "q", ((np.arange(n) * 7) % 81 - 40).astype(np.float32))
-        set_feature(t, "k", 32.0)
+        set_feature(t, "q", ((np.arange(n) * 7) % 81 - 40).astype(np.float32) * 4.0)
+        set_feature(t, "k", 8.0)
     whole(211, 15, prepare=prep, lse_far=100.0)
     check(LAY_SPLIT(), [30, 1, 12, 7], 128, 2, 2, 64, seed=212, prepare=prep)
