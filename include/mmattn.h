@@ -179,6 +179,30 @@ int mmattn_fwd(const void* q_loc, const void* k, const void* v, const uint64_t* 
                int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,
                void* o_loc, float* lse, void* ws, size_t ws_bytes, void* stream);
 
+/* mmattn_fwd for callers that cannot allocate device memory or carry a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and checks as mmattn_fwd without
+ * `ws`: the scratch is an array of MMATTN_STATIC_SCRATCH_BYTES that is part of
+ * the library's code object (every GPU the library runs on holds its own copy
+ * until the process ends).  The call allocates and frees nothing.
+ *   - the device that `stream` belongs to must be the current device;
+ *   - shares needing more scratch than that (mmattn_workspace_size(
+ *     MMATTN_OP_FWD, ...) says how much) give MMATTN_ERR_WORKSPACE; nothing is
+ *     launched then.  Shares with at least 512 (128-row tile, head pair) work
+ *     items need about 5 bytes per (128-row tile, 64-key tile) pair, 1.3 MiB at
+ *     131072 keys x 16384 rows; smaller shares are cut into list slices whose
+ *     fp32 partial results can take far more (up to 64 x the size of O in fp32);
+ *   - all calls on one GPU share the one array: calls that overlap on a GPU
+ *     (different streams, different threads) race and must be ordered by the
+ *     caller.  The status word of the block-index check lives in that array and
+ *     is not visible to the caller: out-of-range indices leave the outputs
+ *     untouched, as in mmattn_fwd. */
+#define MMATTN_STATIC_SCRATCH_BYTES (32u << 20)
+int mmattn_fwd_static(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
+                      const int32_t* blocks, int32_t n_blocks, int32_t block,
+                      int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale, int dtype,
+                      void* o_loc, float* lse, void* stream);
+
 /* Section 4.3 (keys and values are gathered head by head and the attention of
  * the heads already gathered overlaps the transfers of the next ones):
  * mmattn_fwd restricted to the KV heads [kv_head_begin, kv_head_begin +

@@ -64,6 +64,9 @@ def lib() -> ctypes.CDLL:
         L.mmattn_fwd.restype = ctypes.c_int
         L.mmattn_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
                                  ctypes.c_int, _vp, _vp, _vp, _sz, _vp]
+        L.mmattn_fwd_static.restype = ctypes.c_int
+        L.mmattn_fwd_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
+                                        ctypes.c_int, _vp, _vp, _vp]
         L.mmattn_fwd_heads.restype = ctypes.c_int
         L.mmattn_fwd_heads.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i32, _i32, _i32, _f32,
                                        ctypes.c_int, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]
@@ -185,6 +188,22 @@ def fwd(q_loc: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bits: torch.Tenso
                           S, Hq, Hkv, D, scale, BF16, _ptr(o), _ptr(lse), _ptr(ws), ws.numel(),
                           _stream(stream))
     _check("mmattn_fwd", rc)
+    return o, lse
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def fwd_static(q_loc, k, v, bits, blocks, block: int, out, scale: Optional[float] = None, stream=None):
+    """mmattn_fwd_static: the forward on the library's own per-GPU scratch array;
+    `out` = (o_loc, lse) must be given, nothing is allocated here or in the call."""
+    n_loc, Hq, D = q_loc.shape
+    S, Hkv, _ = k.shape
+    scale = float(D) ** -0.5 if scale is None else float(scale)
+    o, lse = out
+    rc = lib().mmattn_fwd_static(_ptr(q_loc), _ptr(k), _ptr(v), _ptr(bits), _ptr(blocks), blocks.numel(),
+                                 block, S, Hq, Hkv, D, scale, BF16, _ptr(o), _ptr(lse), _stream(stream))
+    _check("mmattn_fwd_static", rc)
     return o, lse
 
 

@@ -142,6 +142,21 @@ int mmattn_fwd(const void* q_loc, const void* k, const void* v, const uint64_t* 
     return launch_fwd(a, o_loc, lse, ws, (hipStream_t)stream);
 }
 
+int mmattn_fwd_static(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
+                      const int32_t* blocks, int32_t n_blocks, int32_t block, int64_t S, int32_t Hq,
+                      int32_t Hkv, int32_t D, float scale, int dtype, void* o_loc, float* lse,
+                      void* stream) {
+    if (n_blocks > 0 && (!o_loc || !lse)) return MMATTN_ERR_NULL;
+    int rc = check_attn(q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale, dtype);
+    if (rc != MMATTN_OK) return rc;
+    if (!aligned(o_loc, 16) || !aligned(lse, 4)) return MMATTN_ERR_SHAPE;
+    if (n_blocks == 0) return MMATTN_OK;
+    if (fwd_workspace(S, (int64_t)n_blocks * block, Hq, Hkv, D) > (size_t)MMATTN_STATIC_SCRATCH_BYTES)
+        return MMATTN_ERR_WORKSPACE;
+    AttnArgs a{q_loc, k, v, bits, blocks, n_blocks, block, S, Hq, Hkv, D, scale, 0, Hkv, 0};
+    return launch_fwd_static(a, o_loc, lse, (hipStream_t)stream);
+}
+
 int mmattn_fwd_heads(const void* q_loc, const void* k, const void* v, const uint64_t* bits,
                      const int32_t* blocks, int32_t n_blocks, int32_t block, int64_t S, int32_t Hq,
                      int32_t Hkv, int32_t D, float scale, int dtype, int32_t kv_head_begin,

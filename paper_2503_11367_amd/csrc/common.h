@@ -154,6 +154,7 @@ size_t fwd_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t 
 size_t fwd_heads_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t D);
 size_t bwd_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t D);
 int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st);
+int launch_fwd_static(const AttnArgs& a, void* o, float* lse, hipStream_t st);
 int launch_zero_kv(void* dk, void* dv, size_t bytes_each, hipStream_t st);
 int launch_bwd(const AttnArgs& a, const void* o, const float* lse, const void* d_o,
                void* dq, void* dk, void* dv, void* ws, hipStream_t st);

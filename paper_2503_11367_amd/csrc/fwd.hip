@@ -27,6 +27,7 @@
 // slot by slot (see `step`).
 // FULL tiles skip the predicate; PARTIAL tiles evaluate it per element from the
 // 64-bit words (query word in registers, key words from LDS).
+#include <mutex>
 #include "attn_common.h"
 
 namespace mm {
@@ -606,6 +607,39 @@ static void launch_fwd_kernel(const AttnArgs& a, int64_t n_loc, int32_t nq, floa
                        a.bits, clean, a.block, n_loc, a.S, Hq_run, a.kv_count, a.Hq, a.Hkv, scale_log2,
                        plan, split, err, (ushort_t*)o + qo, lse + (int64_t)a.kv_begin * rep * n_loc,
                        opart, mlpart);
+}
+
+// ---- forward without a caller workspace ---------------------------------------------
+// The scratch of mmattn_fwd_static: one array per GPU, part of the loaded code object, so
+// that callers that may not allocate (graph capture, tight serving loops) need no workspace
+// of their own.  In host code the array's name stands for the symbol only, not for device
+// memory: its device address is looked up once per device and that pointer is what the
+// kernels get.
+static __device__ __align__(256) unsigned char scratch[MMATTN_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+int launch_fwd_static(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
+    int dev = -1;
+    MM_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return MMATTN_ERR_UNSUPPORTED;
+    void* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            MM_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (!p) return MMATTN_ERR_HIP;
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    // nothing in the scratch has to start at zero: every call rebuilds the status word, the
+    // block list and the plan before reading them, and reads back only the partial results
+    // its own workgroups wrote
+    return launch_fwd(a, o, lse, ptr, st);
 }
 
 int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st) {
