@@ -265,23 +265,36 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     const uint32_t lds_ld = lds_addr_of(sm.ld[0][0]);
     const uint32_t lds_info = lds_addr_of(sm.info[0][0]);
     const uint32_t* info_g = (const uint32_t*)(ld_g + (int64_t)Hq * 2 * n_pad);
-    auto issue_q = [&](uint32_t entry, int hq, int stage) {     // Q tile and the rows' (lse2, delta)
-        const int64_t r0 = (int64_t)(entry & ~kPartialFlag) * kKvBM;
-        const int64_t tile = ((int64_t)hq * n_pad + r0) * D;    // 64 consecutive rows, padded with zeros
+    // Tile addresses are kept as running pointers (the head's base advances by one head
+    // stride when the walk reaches the next head), so that issuing a step's transfers costs
+    // a shift and an add per tensor: a wave issues one instruction every four cycles, and
+    // what it spends on address arithmetic here the matrix pipe of its SIMD spends idle.
+    const int64_t head_stride = n_pad * D;                      // elements per head of Qh / dOh
+    const ushort_t* qh_next = Qh + (int64_t)head0 * head_stride;     // head of the next Q tile to issue
+    const ushort_t* doh_next = dOh + (int64_t)head0 * head_stride;
+    // the rows' constants and mask inputs travel with the Q tile, one 256-byte piece per wave:
+    // wave 0: -LSE rows, wave 1: -Delta rows (per head), waves 2-4: the rows' mask inputs
+    const float* row_next = wave < 2 ? ldk_g + ((int64_t)head0 * 2 + wave) * n_pad
+                                     : (const float*)(info_g + (int64_t)(wave - 2) * n_pad);
+    const int64_t row_stride = wave < 2 ? 2 * n_pad : 0;
+    const uint32_t row_lds = wave < 2 ? lds_ld + wave * (4 * kKvBM) : lds_info + (wave - 2) * (4 * kKvBM);
+    const uint32_t row_lds_stage = wave < 2 ? 8 * kKvBM : 12 * kKvBM;
+    auto issue_q = [&](uint32_t entry, int stage) {             // Q tile and the rows' constants / mask inputs
+        const int64_t r0 = (int64_t)(entry & ~kPartialFlag) * kKvBM;   // 64 consecutive rows, padded with zeros
+        const ushort_t* tile = qh_next + r0 * D;
 #pragma unroll
-        for (int i = 0; i < NI; ++i) dma16(Qh + tile, tr_off[i], lds_q + stage * kStage + i * 1024);
-        if (wave < 2)                                           // wave 0: -LSE/scale rows, wave 1: -Delta rows
-            dma4(ldk_g + ((int64_t)hq * 2 + wave) * n_pad + r0, (uint32_t)(lane * 4),
-                 lds_ld + stage * (8 * kKvBM) + wave * (4 * kKvBM));
-        else if (wave < 5)                                      // waves 2-4: the rows' mask inputs
-            dma4(info_g + (int64_t)(wave - 2) * n_pad + r0, (uint32_t)(lane * 4),
-                 lds_info + stage * (12 * kKvBM) + (wave - 2) * (4 * kKvBM));
+        for (int i = 0; i < NI; ++i) dma16(tile, tr_off[i], lds_q + stage * kStage + i * 1024);
+        if (wave < 5) dma4(row_next + r0, (uint32_t)(lane * 4), row_lds + stage * row_lds_stage);
     };
-    auto issue_d = [&](uint32_t entry, int hq, int stage) {
-        const int64_t r0 = (int64_t)(entry & ~kPartialFlag) * kKvBM;
-        const int64_t tile = ((int64_t)hq * n_pad + r0) * D;
+    auto next_head = [&]() {
+        qh_next += head_stride;
+        doh_next += head_stride;
+        row_next += row_stride;
+    };
+    auto issue_d = [&](uint32_t entry, const ushort_t* head_base, int stage) {
+        const ushort_t* tile = head_base + (int64_t)(entry & ~kPartialFlag) * (kKvBM * D);
 #pragma unroll
-        for (int i = 0; i < NI; ++i) dma16(dOh + tile, tr_off[i], lds_d + stage * kStage + i * 1024);
+        for (int i = 0; i < NI; ++i) dma16(tile, tr_off[i], lds_d + stage * kStage + i * 1024);
     };
 
     // Step s is query tile qlist[n_q-1 - s%n_q] of head head0 + s/n_q: every k-tile
@@ -294,8 +307,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
         return s_ < n_steps ? qlist[n_q - 1 - s_ % n_q] : 0u;
     };
     uint32_t list_chunk = n_steps > 0 ? fetch_chunk(0) : 0u;
-    int hq_next = head0;                               // head of the step whose Q tile is issued next
-    int qi_next = 0;                                   // its position in the walk
+    int qi_next = 0;                                   // position in the walk of the step whose Q tile is issued next
 
     // ---- fragment addresses (LDS byte addresses at ring stage 0) ---------------------
     // row fragments feed the first product (V role: Q ring, K role: dO ring), transpose
@@ -342,19 +354,19 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     // prologue: Q tiles of steps 0 and 1 and the dO tile of step 0; ent[] holds the
     // list entries of steps i, i+1, i+2 and hq_d the head of the next dO tile
     uint32_t ent[3] = {0u, 0u, 0u};
-    int hq_d = head0, hq_d1 = head0;                   // heads of steps i+1 and i+2 (dO is issued one step after Q)
+    const ushort_t *doh_d = doh_next, *doh_d1 = doh_next;     // dO heads of steps i+1 and i+2 (dO is issued one step after Q)
     if (n_steps > 0) {
         ent[0] = __builtin_amdgcn_readlane(list_chunk, 0);
-        issue_q(ent[0], hq_next, 0);
-        issue_d(ent[0], hq_next, 0);
-        if (++qi_next == n_q) { qi_next = 0; ++hq_next; }
-        hq_d = hq_next;
+        issue_q(ent[0], 0);
+        issue_d(ent[0], doh_next, 0);
+        if (++qi_next == n_q) { qi_next = 0; next_head(); }
+        doh_d = doh_next;
         if (n_steps > 1) {
             ent[1] = __builtin_amdgcn_readlane(list_chunk, 1);
-            issue_q(ent[1], hq_next, 1);
-            if (++qi_next == n_q) { qi_next = 0; ++hq_next; }
+            issue_q(ent[1], 1);
+            if (++qi_next == n_q) { qi_next = 0; next_head(); }
         }
-        hq_d1 = hq_next;
+        doh_d1 = doh_next;
     }
 
 #define MM_SLOT_END() __builtin_amdgcn_sched_barrier(0)
@@ -515,7 +527,10 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
             if (KR && t == (slot_of(8) > 4 ? slot_of(8) - 4 : 0)) pin[1] = read_p(p_imm + 1024);
             if (KR && t == SLV + 2 && p_imm_n >= 0) pin[0] = read_p(p_imm_n);
             MM_SLOT_END();
-            if (t == 1) hook();
+            // the two roles of a key block share a SIMD and leave the barrier together: the K
+            // role issues its transfers half a unit after the V role, so that the SIMD's matrix
+            // pipe always has one of the two feeding it
+            if (t == (KR ? NS / 2 + 1 : 1)) hook();
         }
     };
 
@@ -540,16 +555,16 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
                 wait_vmcnt<0>();           // nothing else is in flight here
             }
             ent[2] = __builtin_amdgcn_readlane(list_chunk, (i + 2) & 63);
-            issue_q(ent[2], hq_next, (i + 2) & (kKvQst - 1));
-            if (++qi_next == n_q) { qi_next = 0; ++hq_next; }
+            issue_q(ent[2], (i + 2) & (kKvQst - 1));
+            if (++qi_next == n_q) { qi_next = 0; next_head(); }
         }
         if (i + 1 < n_steps) {
             int dn = dst + 1;
             if (dn == kKvDst) dn = 0;
-            issue_d(ent[1], hq_d, dn);
+            issue_d(ent[1], doh_d, dn);
         }
-        hq_d = hq_d1;
-        hq_d1 = hq_next;
+        doh_d = doh_d1;
+        doh_d1 = doh_next;
         ent[0] = ent[1];
         ent[1] = ent[2];
     };
