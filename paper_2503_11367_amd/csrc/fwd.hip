@@ -28,6 +28,7 @@
 // FULL tiles skip the predicate; PARTIAL tiles evaluate it per element from the
 // 64-bit words (query word in registers, key words from LDS).
 #include <mutex>
+#include <type_traits>
 #include "attn_common.h"
 
 namespace mm {
@@ -38,6 +39,45 @@ constexpr int kFwdBN = 64;      // keys per k-tile
 // the probabilities are taken relative to before the shift follows it; inside
 // this band probabilities stay within 2^+-kShiftSlack, harmless in fp32/bf16
 constexpr float kShiftSlack = 64.0f;
+
+// A bound on the scores of a wavefront's rows: |s| <= |q| |k| scale log2(e) (Cauchy-Schwarz)
+// with the largest key norm of the KV head.  When it stays below kScoreBound for all 32
+// rows, the probabilities 2^s are within 2^+-kScoreBound of 1 with the shift at 0, nothing
+// can overflow or vanish, and the wavefront runs without tracking the running maximum at
+// all (the results are those of the tracked path whenever that one would not have moved
+// its shift).  2^kScoreBound times 2^30 keys still fits fp32.
+constexpr float kScoreBound = 90.0f;
+constexpr int kNormChunks = 64;     // partial maxima of the squared key norms per KV head
+
+// Largest squared key norm of every KV head, as kNormChunks partial maxima per head (no
+// atomics: the attention kernel takes the maximum of its head's partials).  grid
+// (kNormChunks, heads of the launch); a chunk is S / kNormChunks consecutive keys.
+template <int D>
+__global__ void __launch_bounds__(256)
+key_norm_kernel(const ushort_t* __restrict__ K, int64_t S, int32_t Hkv_s, float* __restrict__ knorm) {
+    constexpr int TPK = D / 8;                            // threads per key, 8 elements each
+    constexpr int KPP = 256 / TPK;                        // keys per pass
+    __shared__ float wmax[4];
+    const int chunk = blockIdx.x, g = blockIdx.y;
+    const int64_t per = S / kNormChunks, k0 = chunk * per;
+    const int sub = threadIdx.x % TPK, kk = threadIdx.x / TPK;
+    float best = 0.f;
+    for (int64_t k = kk; k < per; k += KPP) {
+        const bf16x8 x = __builtin_bit_cast(bf16x8, *(const u32x4*)(K + ((k0 + k) * Hkv_s + g) * (int64_t)D + sub * 8));
+        float a = 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += (float)x[u] * (float)x[u];
+#pragma unroll
+        for (int off = TPK / 2; off > 0; off >>= 1) a += __shfl_xor(a, off);
+        best = fmaxf(best, a);                            // a NaN norm is dropped here and caught by the row bound
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) best = fmaxf(best, __shfl_xor(best, off));
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        knorm[(int64_t)g * kNormChunks + chunk] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+}
 
 template <int D, int NST>
 struct FwdSmem {
@@ -54,8 +94,9 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
            const ushort_t* __restrict__ V, const uint64_t* __restrict__ bits,
            const int32_t* __restrict__ blocks, int32_t block, int64_t n_loc, int64_t S,
            int32_t Hq, int32_t Hkv, int32_t Hq_s, int32_t Hkv_s, float scale_log2, TilePlan plan,
-           FwdSplit split, const int32_t* __restrict__ err, ushort_t* __restrict__ O,
-           float* __restrict__ LSE, float* __restrict__ Opart, float* __restrict__ MLpart) {
+           FwdSplit split, const int32_t* __restrict__ err, const float* __restrict__ knorm,
+           ushort_t* __restrict__ O, float* __restrict__ LSE, float* __restrict__ Opart,
+           float* __restrict__ MLpart) {
     // Hq, Hkv: heads this launch runs (a window of KV heads and their query heads, the
     // tensor pointers already advanced to its first head); Hq_s, Hkv_s: heads per token
     // in memory
@@ -134,6 +175,9 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // (Fetched before the list length is known: entries past it, inside the q-tile's row
     // of the list array, are read but never used.)
     uint32_t list_chunk = chunk * csz + lane < plan.nk ? klist[lane] : 0u;
+    // this lane's partial maximum of the head's squared key norms (see kScoreBound)
+    static_assert(kNormChunks == 64, "one partial maximum per lane");
+    float kn2 = knorm[(int64_t)g * kNormChunks + lane];
 
     const int nchunk = max(1, (kc_total + csz - 1) / csz);
     if (chunk >= nchunk) return;          // workgroup-uniform
@@ -194,6 +238,21 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // starts and inserts no waits of its own inside it (such a wait would also
     // drain the tile transfers, which it cannot see).
     wait_vmcnt<0>();
+
+    // does this wavefront need the running maximum at all?
+    bool tracked;
+    {
+        float qn2 = 0.f;
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds)
+#pragma unroll
+            for (int u = 0; u < 8; ++u) qn2 += (float)qf[ds][u] * (float)qf[ds][u];
+        qn2 += __shfl_xor(qn2, 32);                       // the row's other 64 head-dim values
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) kn2 = fmaxf(kn2, __shfl_xor(kn2, off));
+        const float bound = __builtin_sqrtf(qn2 * kn2) * scale_log2 * 1.01f;
+        tracked = !__all(bound <= kScoreBound);           // NaN or infinite norms take the tracked path
+    }
 
     // ---- software pipeline over half tiles (32 keys) ---------------------------------
     // While the probabilities of one half tile are exponentiated and multiplied into
@@ -319,8 +378,9 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // and an even share of the vector work: a wave cannot issue for some cycles after
     // an MFMA and the matrix pipe is busy for 32, so about four plain vector
     // instructions per slot are free and more stretch the slot.
-    auto step = [&](int kn, floatx16& s_next, const floatx16& s_cur, int vb, int kp, bf16x8 (&kf)[NKF],
+    auto step = [&](auto TRACK_, int kn, floatx16& s_next, const floatx16& s_cur, int vb, int kp, bf16x8 (&kf)[NKF],
                     uint32_t e_next, int parity_next, int kb_next, bool live_next) __attribute__((always_inline)) {
+        constexpr bool TRACK = decltype(TRACK_)::value;    // follow the running maximum (else the shift stays 0)
         constexpr int PPS = EPS / 2;       // probability pairs exponentiated per S slot
         constexpr int MPS = 16 / NDB;      // scores scaled per early / folded into the maximum per late PV slot
         constexpr int DPS = 8 / NDB;       // row-sum updates per late PV slot
@@ -387,14 +447,17 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
                     l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[pr]),
                                                             bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l_run, false);
                 }
+                if (TRACK) {
 #pragma unroll
-                for (int u = 0; u < MPS; ++u) m_loc = fmaxf(m_loc, s_next[(t - NDS - NDB) * MPS + u]);
-                asm volatile("" : "+v"(l_run), "+v"(m_loc));
+                    for (int u = 0; u < MPS; ++u) m_loc = fmaxf(m_loc, s_next[(t - NDS - NDB) * MPS + u]);
+                    asm volatile("" : "+v"(m_loc));
+                }
+                asm volatile("" : "+v"(l_run));
             }
             MM_SLOT_END();
             if (t == NDS + NDB - 1) mask_scores(e_next, parity_next, kb_next, s_next);
         }
-        if (live_next) new_max(pair_max(m_loc), s_next);   // past the last tile the scores are stale data
+        if (TRACK && live_next) new_max(pair_max(m_loc), s_next);   // past the last tile the scores are stale data
     };
     auto wait_landed = [&](int younger) __attribute__((always_inline)) {
         if (younger >= 2) wait_vmcnt<4 * NI>();
@@ -402,68 +465,80 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         else wait_vmcnt<0>();
     };
 
-    uint32_t pend[NST - 1];                // list entries of tiles j .. j+NST-2
+    // the whole walk over the active tiles, once with and once without maximum tracking
+    auto walk = [&](auto TRACK_) __attribute__((always_inline)) {
+        constexpr bool TRACK = decltype(TRACK_)::value;
+        uint32_t pend[NST - 1];                // list entries of tiles j .. j+NST-2
 #pragma unroll
-    for (int j = 0; j < NST - 1; ++j) {
-        pend[j] = 0u;
-        if (j < n_active) {
-            pend[j] = entry_at(j);
-            issue_tile(pend[j], j);
-        }
-    }
-    floatx16 s_a, s_b;                     // scores of the current / next half tile, alternating
-    bf16x8 kf[NKF];                        // leading K fragments of the next half tile
-    if (n_active > 0) {
-        wait_landed(min(NST - 2, n_active - 1));
-        __syncthreads();
-        stage_keys(pend[0], 0);
-        scores(0, s_a);
-        mask_scores(pend[0], 0, 0, s_a);
-        float m_loc = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) m_loc = fmaxf(m_loc, s_a[r]);
-        new_max(pair_max(m_loc), s_a);
-#pragma unroll
-        for (int i = 0; i < NKF; ++i) kf[i] = read_k(32 * RB, i);
-    }
-    // The ring position of tile j is j mod NST; the loop is unrolled NST-fold so that
-    // every stage index below is a compile-time constant.
-    for (int j0 = 0; j0 < n_active; j0 += NST) {
-#pragma unroll
-        for (int st = 0; st < NST; ++st) {
-            const int j = j0 + st;
-            if (j >= n_active) break;
-            constexpr int kHalf = 32 * RB;
-            const int st1 = (st + 1) % NST, sn = (st + NST - 1) % NST;
-            const bool more = j + 1 < n_active;
-            // tile j+1 has landed once at most the transfers of the tiles after it remain
-            wait_landed(max(0, min(NST - 3, n_active - 2 - j)));
-            __syncthreads();               // everyone's share landed; stage of tile j-1 is free
-            uint32_t fresh = 0u;
-            if (j + NST - 1 < n_active) {
-                if (((j + NST - 1) & 63) == 0) {
-                    // next 64 list entries (this vector load also drains the transfers in flight)
-                    const int i = j + NST - 1 + lane;
-                    list_chunk = i < n_active ? klist[i] : 0u;
-                    wait_vmcnt<0>();       // awaited here so that no wait is needed after the branch
-                }
-                fresh = entry_at(j + NST - 1);
-                issue_tile(fresh, sn);
+        for (int j = 0; j < NST - 1; ++j) {
+            pend[j] = 0u;
+            if (j < n_active) {
+                pend[j] = entry_at(j);
+                issue_tile(pend[j], j);
             }
-            const uint32_t e_cur = pend[0], e_next = pend[1];
-#pragma unroll
-            for (int i = 0; i + 1 < NST - 1; ++i) pend[i] = pend[i + 1];
-            pend[NST - 2] = fresh;
-            // first half of tile j (scores in s_a) while the second half's scores form in s_b
-            step(st * kStageBytes + kHalf, s_b, s_a, st * kStageBytes, st1 * kStageBytes, kf, e_cur, j & 1,
-                 1, true);
-            // second half of tile j while the first half of tile j+1 forms in s_a (stale but
-            // harmless data past the last tile)
-            if (more) stage_keys(e_next, (j + 1) & 1);
-            step(st1 * kStageBytes, s_a, s_b, st * kStageBytes + kHalf, st1 * kStageBytes + kHalf, kf,
-                 more ? e_next : 0u, (j + 1) & 1, 0, more);
         }
-    }
+        floatx16 s_a, s_b;                     // scores of the current / next half tile, alternating
+        bf16x8 kf[NKF];                        // leading K fragments of the next half tile
+        if (n_active > 0) {
+            wait_landed(min(NST - 2, n_active - 1));
+            __syncthreads();
+            stage_keys(pend[0], 0);
+            scores(0, s_a);
+            mask_scores(pend[0], 0, 0, s_a);
+            if (TRACK) {
+                float m_loc = -INFINITY;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) m_loc = fmaxf(m_loc, s_a[r]);
+                new_max(pair_max(m_loc), s_a);
+            }
+#pragma unroll
+            for (int i = 0; i < NKF; ++i) kf[i] = read_k(32 * RB, i);
+        }
+        // The ring position of tile j is j mod NST; the loop is unrolled NST-fold so that
+        // every stage index below is a compile-time constant.
+        for (int j0 = 0; j0 < n_active; j0 += NST) {
+#pragma unroll
+            for (int st = 0; st < NST; ++st) {
+                const int j = j0 + st;
+                if (j >= n_active) break;
+                constexpr int kHalf = 32 * RB;
+                const int st1 = (st + 1) % NST, sn = (st + NST - 1) % NST;
+                const bool more = j + 1 < n_active;
+                // tile j+1 has landed once at most the transfers of the tiles after it remain
+                wait_landed(max(0, min(NST - 3, n_active - 2 - j)));
+                __syncthreads();               // everyone's share landed; stage of tile j-1 is free
+                uint32_t fresh = 0u;
+                if (j + NST - 1 < n_active) {
+                    if (((j + NST - 1) & 63) == 0) {
+                        // next 64 list entries (this vector load also drains the transfers in flight)
+                        const int i = j + NST - 1 + lane;
+                        list_chunk = i < n_active ? klist[i] : 0u;
+                        wait_vmcnt<0>();       // awaited here so that no wait is needed after the branch
+                    }
+                    fresh = entry_at(j + NST - 1);
+                    // the two heads' wavefronts share the SIMDs pairwise and leave the barrier together:
+                    // the first head's issue their transfers now, the second head's after the first half
+                    // tile, so that each SIMD's matrix pipe is fed by one of the two meanwhile
+                    if (HPW == 1 || wave < 4) issue_tile(fresh, sn);
+                }
+                const uint32_t e_cur = pend[0], e_next = pend[1];
+#pragma unroll
+                for (int i = 0; i + 1 < NST - 1; ++i) pend[i] = pend[i + 1];
+                pend[NST - 2] = fresh;
+                // first half of tile j (scores in s_a) while the second half's scores form in s_b
+                step(TRACK_, st * kStageBytes + kHalf, s_b, s_a, st * kStageBytes, st1 * kStageBytes, kf, e_cur, j & 1,
+                     1, true);
+                if (HPW > 1 && wave >= 4 && j + NST - 1 < n_active) issue_tile(fresh, sn);
+                // second half of tile j while the first half of tile j+1 forms in s_a (stale but
+                // harmless data past the last tile)
+                if (more) stage_keys(e_next, (j + 1) & 1);
+                step(TRACK_, st1 * kStageBytes, s_a, s_b, st * kStageBytes + kHalf, st1 * kStageBytes + kHalf, kf,
+                     more ? e_next : 0u, (j + 1) & 1, 0, more);
+            }
+        }
+    };
+    if (tracked) walk(std::true_type{});
+    else walk(std::false_type{});
 #undef MM_SLOT_END
     // ---- epilogue -----------------------------------------------------------------
     const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -555,7 +630,7 @@ fwd_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int32_t Hq, int
 // Workspace: the plan (independent of which heads run) first, then the partial
 // results of split q-tile lists for `Hkv_run` KV heads run in one launch.
 struct FwdLayout {
-    size_t err, clean_blocks, cls, kcount, klist, qorder, opart, mlpart, total;
+    size_t err, clean_blocks, cls, kcount, klist, qorder, knorm, opart, mlpart, total;
     int32_t nq, nk;
     FwdSplit split;
 };
@@ -574,6 +649,7 @@ static FwdLayout fwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     L.kcount = off;       off += align_up((size_t)L.nq * 4, 256);
     L.klist = off;        off += align_up((size_t)L.nq * L.nk * 4, 256);
     L.qorder = off;       off += align_up((size_t)L.nq * 4, 256);
+    L.knorm = off;        off += align_up((size_t)Hkv * kNormChunks * 4, 256);
     const size_t prow = L.split.cmax > 1 ? (size_t)L.split.cmax * L.nq * kFwdBM * Hq_run : 0;
     L.opart = off;        off += align_up(prow * D * 4, 256);
     L.mlpart = off;       off += align_up(prow * 8, 256);
@@ -597,15 +673,15 @@ size_t fwd_heads_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, in
 template <int D, int HPW, int NST>
 static void launch_fwd_kernel(const AttnArgs& a, int64_t n_loc, int32_t nq, float scale_log2,
                               const int32_t* clean, const TilePlan& plan, const FwdSplit& split,
-                              const int32_t* err, void* o, float* lse, float* opart, float* mlpart,
-                              hipStream_t st) {
+                              const int32_t* err, const float* knorm, void* o, float* lse, float* opart,
+                              float* mlpart, hipStream_t st) {
     const int32_t rep = a.Hq / a.Hkv, Hq_run = rep * a.kv_count;
     const int64_t qo = (int64_t)a.kv_begin * rep * a.D, ko = (int64_t)a.kv_begin * a.D;
     const unsigned grid = (unsigned)((int64_t)nq * Hq_run / HPW * split.cmax);
     hipLaunchKernelGGL((fwd_kernel<D, HPW, NST>), dim3(grid), dim3(256 * HPW), 0, st,
                        (const ushort_t*)a.q + qo, (const ushort_t*)a.k + ko, (const ushort_t*)a.v + ko,
                        a.bits, clean, a.block, n_loc, a.S, Hq_run, a.kv_count, a.Hq, a.Hkv, scale_log2,
-                       plan, split, err, (ushort_t*)o + qo, lse + (int64_t)a.kv_begin * rep * n_loc,
+                       plan, split, err, knorm, (ushort_t*)o + qo, lse + (int64_t)a.kv_begin * rep * n_loc,
                        opart, mlpart);
 }
 
@@ -672,13 +748,24 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
     const float scale_log2 = a.scale * kLog2e;
     const int32_t rep = a.Hq / a.Hkv;
     const bool pair = rep % 2 == 0;                // two heads of a KV group per workgroup
+    // largest key norms of the window's heads (data, not plan: every call)
+    float* knorm = (float*)(base + L.knorm) + (int64_t)a.kv_begin * kNormChunks;
+    {
+        const ushort_t* kw = (const ushort_t*)a.k + (int64_t)a.kv_begin * a.D;
+        if (a.D == 128)
+            hipLaunchKernelGGL(key_norm_kernel<128>, dim3(kNormChunks, (unsigned)a.kv_count), dim3(256), 0, st, kw,
+                               a.S, a.Hkv, knorm);
+        else
+            hipLaunchKernelGGL(key_norm_kernel<64>, dim3(kNormChunks, (unsigned)a.kv_count), dim3(256), 0, st, kw,
+                               a.S, a.Hkv, knorm);
+    }
     stage_begin(MMATTN_STAGE_FWD, st);
     if (a.D == 128) {
-        if (pair) launch_fwd_kernel<128, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, o, lse, opart, mlpart, st);
-        else      launch_fwd_kernel<128, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, o, lse, opart, mlpart, st);
+        if (pair) launch_fwd_kernel<128, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, knorm, o, lse, opart, mlpart, st);
+        else      launch_fwd_kernel<128, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, knorm, o, lse, opart, mlpart, st);
     } else {
-        if (pair) launch_fwd_kernel<64, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, o, lse, opart, mlpart, st);
-        else      launch_fwd_kernel<64, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, o, lse, opart, mlpart, st);
+        if (pair) launch_fwd_kernel<64, 2, 4>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, knorm, o, lse, opart, mlpart, st);
+        else      launch_fwd_kernel<64, 1, 3>(a, n_loc, L.nq, scale_log2, clean, plan, L.split, err, knorm, o, lse, opart, mlpart, st);
     }
     if (L.split.cmax > 1) {
         const int32_t Hq_run = rep * a.kv_count;
