@@ -141,3 +141,24 @@ def test_per_row_offsets():
         set_feature(t, "k", 8.0)
     whole(211, 15, prepare=prep, lse_far=100.0)
     check(LAY_SPLIT(), [30, 1, 12, 7], 128, 2, 2, 64, seed=212, prepare=prep)
+
+
+def test_offsets_inside_the_untracked_band():
+    """Wavefronts whose score bound |q| |k| scale log2(e) stays below 90 run with
+    the shift fixed at 0 and no maximum tracking.  Here every score is offset by
+    about +41, -41 or (per key range, per row) both, in base-2 units, with
+    bounds of 70-75: still untracked, probabilities between 2^-50 and 2^50."""
+    def up(t, rows):
+        set_feature(t, "q", 40.0)
+        set_feature(t, "k", 8.0)
+    def down(t, rows):
+        set_feature(t, "q", 40.0)
+        set_feature(t, "k", -8.0)
+    def both(t, rows):
+        n = t["q_bits"].shape[0]
+        set_feature(t, "q", np.where(np.arange(n) % 3 == 0, -40.0, 40.0))
+        set_feature(t, "k", np.where(np.arange(t["k_bits"].shape[0]) % 512 < 200, -8.0, 8.0))
+    whole(221, 2, prepare=up, lse_far=25.0)
+    whole(222, 5, prepare=down, lse_far=25.0)
+    whole(223, 11, prepare=both, lse_far=25.0)
+    check(LAY_SPLIT(), list(range(0, 32, 3)), 128, 4, 2, 128, seed=224, prepare=both, lse_far=25.0)
