@@ -142,6 +142,18 @@ __device__ __forceinline__ void dma16(const void* base_uniform, uint32_t off, ui
                  : "v"(off), "s"(sb), "s"(lds_addr)
                  : "memory", "m0");
 }
+// 4-byte-per-lane variant of dma16 (lane l's dword lands at lds_addr + 4*l)
+__device__ __forceinline__ void dma4(const void* base_uniform, uint32_t off, uint32_t lds_addr) {
+    const uint64_t b = (uint64_t)base_uniform;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    const uint64_t sb = ((uint64_t)hi << 32) | lo;
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :
+                 : "v"(off), "s"(sb), "s"(lds_addr)
+                 : "memory", "m0");
+}
 __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }

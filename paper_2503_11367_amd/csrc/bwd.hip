@@ -109,19 +109,6 @@ bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
     }
 }
 
-// 4-byte-per-lane variant of dma16 (lane l's dword lands at lds_addr + 4*l)
-__device__ __forceinline__ void dma4(const void* base_uniform, uint32_t off, uint32_t lds_addr) {
-    const uint64_t b = (uint64_t)base_uniform;
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-    const uint64_t sb = ((uint64_t)hi << 32) | lo;
-    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-                 :
-                 : "v"(off), "s"(sb), "s"(lds_addr)
-                 : "memory", "m0");
-}
-
 // ---------------------------------------------------------------- dK / dV ----
 // Key-outer pass with role-specialised wavefronts.  A workgroup owns 128 keys of
 // one KV head; for each 32-key block there is a "V wave" and a "K wave" (8

@@ -83,7 +83,7 @@ template <int D, int NST>
 struct FwdSmem {
     alignas(1024) unsigned char k[NST][kFwdBN * D * 2];   // rotated tiles, see SwzTile
     alignas(1024) unsigned char v[NST][kFwdBN * D * 2];
-    uint32_t kss[2][2][kFwdBN];                           // sample/span field and modality of a PARTIAL tile's keys, by tile parity
+    alignas(256) uint64_t kw[NST][kFwdBN];                // mask words of a PARTIAL tile's keys, by ring stage
 };
 
 // HPW query heads per workgroup (4 wavefronts each), NST LDS stages; one workgroup per
@@ -203,6 +203,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     }
     const uint32_t lds_k = lds_addr_of(sm.k[0]) + (wave * NI) * 1024;
     const uint32_t lds_v = lds_addr_of(sm.v[0]) + (wave * NI) * 1024;
+    const uint32_t lds_kw = lds_addr_of(sm.kw[0]);
     auto issue_tile = [&](uint32_t entry, int stage) {
         const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
         const ushort_t* kt = K + k0 * Hkv_s * D;       // wave-uniform tile bases
@@ -212,6 +213,10 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             dma16(kt, gk[i], lds_k + stage * kStageBytes + i * 1024);
             dma16(vt, gv[i], lds_v + stage * kStageBytes + i * 1024);
         }
+        // the mask words of a PARTIAL tile's 64 keys travel with the tile (two 256-byte pieces,
+        // the workgroup's first two wavefronts): no load that the workgroup has to wait for
+        if ((entry & kPartialFlag) && wave < 2)
+            dma4(bits + k0, (uint32_t)(wave * 256 + lane * 4), lds_kw + stage * (8 * kFwdBN) + wave * 256);
     };
 
     // ---- LDS read offsets (bytes) ---------------------------------------------------
@@ -294,17 +299,17 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] *= scale_log2;
     };
-    // key words of rows 8*q4 + 4*hh + 0..3 (+32 per half tile), 16 bytes per read
-    const uint32_t kss_a = lds_addr_of(sm.kss) + hh * 16;
     // (the query-side parts of the predicate, window included, are per-lane constants here)
-    auto mask_scores = [&](uint32_t entry, int parity, int kb, floatx16& s) __attribute__((always_inline)) {
+    // `kw_off`: byte offset of the tile's mask words in sm.kw (its ring stage)
+    typedef const uint64_t __attribute__((address_space(3))) * lds_u8;
+    auto mask_scores = [&](uint32_t entry, int kw_off, int kb, floatx16& s) __attribute__((always_inline)) {
         if (entry & kPartialFlag) {            // workgroup-uniform
             const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
             // Usually the 32 keys of the half tile are one run of equal mask fields: then every
             // row sees one contiguous range of them, found once per row, and an element costs a
             // subtraction and a comparison; wavefronts whose rows see all 32 keys do nothing.
-            const uint32_t ka = lds_addr_of(sm.kss) + (uint32_t)(parity * (8 * kFwdBN) + (kb * 32 + li) * 4);
-            const uint32_t ss_k = *(lds_u1)(uintptr_t)ka, mod_k = *(lds_u1)(uintptr_t)(ka + 4 * kFwdBN);
+            const uint64_t wk = *(lds_u8)(uintptr_t)(lds_kw + (uint32_t)(kw_off + (kb * 32 + li) * 8));
+            const uint32_t ss_k = word_ss(wk), mod_k = word_mod(wk);
             const uint32_t ss0 = __builtin_amdgcn_readfirstlane(ss_k), mod0 = __builtin_amdgcn_readfirstlane(mod_k);
             if (__all(ss_k == ss0 && mod_k == mod0)) {       // wave-uniform
                 const KeyRange r = visible_range(q_ss, q_causal, (int32_t)q_pos, ss0, mod0,
@@ -319,15 +324,17 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
                 }
                 return;
             }
+            // element by element: the words of keys 8*q4 + 4*hh + 0..3 of the half tile, 32 bytes
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const uint32_t a = kss_a + (uint32_t)(parity * (8 * kFwdBN) + kb * 128 + q4 * 32);
-                const u32x4 kw = *(lds_u4)(uintptr_t)a;
-                const u32x4 km = *(lds_u4)(uintptr_t)(a + 4 * kFwdBN);
+                const uint32_t a = lds_kw + (uint32_t)(kw_off + (kb * 32 + 8 * q4 + 4 * hh) * 8);
+                const u32x4 w01 = *(lds_u4)(uintptr_t)a, w23 = *(lds_u4)(uintptr_t)(a + 16);
+                const uint64_t w4[4] = {w01[0] | ((uint64_t)w01[1] << 32), w01[2] | ((uint64_t)w01[3] << 32),
+                                        w23[0] | ((uint64_t)w23[1] << 32), w23[2] | ((uint64_t)w23[3] << 32)};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
-                    if (!visible(q_ss, q_causal, q_pos, kw[j], km[j], k0 + kl)) s[q4 * 4 + j] = -INFINITY;
+                    if (!visible(q_ss, q_causal, q_pos, word_ss(w4[j]), word_mod(w4[j]), k0 + kl)) s[q4 * 4 + j] = -INFINITY;
                 }
                 // four elements at a time: the comparison results live in scalar registers
                 __builtin_amdgcn_sched_barrier(0);
@@ -360,18 +367,6 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             for (int r = 0; r < 16; ++r) s[r] -= m_run;
         }
     };
-    // key words of a PARTIAL tile into sm.kss[parity] (followed by a barrier)
-    auto stage_keys = [&](uint32_t entry, int parity) __attribute__((always_inline)) {
-        if (entry & kPartialFlag) {            // workgroup-uniform
-            const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
-            if (tid < kFwdBN) {
-                const uint64_t wk = bits[k0 + tid];
-                sm.kss[parity][0][tid] = word_ss(wk);
-                sm.kss[parity][1][tid] = word_mod(wk);
-            }
-            __syncthreads();
-        }
-    };
     // One pipeline step.  kf[] holds the first NKF K fragments of the NEXT half tile
     // (at kn) on entry and those of the half tile after it (at kp) on exit.  The
     // step is a sequence of NDS + 2*NDB slots, each one MFMA, one fragment request
@@ -379,7 +374,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // an MFMA and the matrix pipe is busy for 32, so about four plain vector
     // instructions per slot are free and more stretch the slot.
     auto step = [&](auto TRACK_, int kn, floatx16& s_next, const floatx16& s_cur, int vb, int kp, bf16x8 (&kf)[NKF],
-                    uint32_t e_next, int parity_next, int kb_next, bool live_next) __attribute__((always_inline)) {
+                    uint32_t e_next, int kw_next, int kb_next, bool live_next) __attribute__((always_inline)) {
         constexpr bool TRACK = decltype(TRACK_)::value;    // follow the running maximum (else the shift stays 0)
         constexpr int PPS = EPS / 2;       // probability pairs exponentiated per S slot
         constexpr int MPS = 16 / NDB;      // scores scaled per early / folded into the maximum per late PV slot
@@ -455,7 +450,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
                 asm volatile("" : "+v"(l_run));
             }
             MM_SLOT_END();
-            if (t == NDS + NDB - 1) mask_scores(e_next, parity_next, kb_next, s_next);
+            if (t == NDS + NDB - 1) mask_scores(e_next, kw_next, kb_next, s_next);
         }
         if (TRACK && live_next) new_max(pair_max(m_loc), s_next);   // past the last tile the scores are stale data
     };
@@ -482,7 +477,6 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         if (n_active > 0) {
             wait_landed(min(NST - 2, n_active - 1));
             __syncthreads();
-            stage_keys(pend[0], 0);
             scores(0, s_a);
             mask_scores(pend[0], 0, 0, s_a);
             if (TRACK) {
@@ -526,14 +520,13 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
                 for (int i = 0; i + 1 < NST - 1; ++i) pend[i] = pend[i + 1];
                 pend[NST - 2] = fresh;
                 // first half of tile j (scores in s_a) while the second half's scores form in s_b
-                step(TRACK_, st * kStageBytes + kHalf, s_b, s_a, st * kStageBytes, st1 * kStageBytes, kf, e_cur, j & 1,
+                step(TRACK_, st * kStageBytes + kHalf, s_b, s_a, st * kStageBytes, st1 * kStageBytes, kf, e_cur, st * (8 * kFwdBN),
                      1, true);
                 if (HPW > 1 && wave >= 4 && j + NST - 1 < n_active) issue_tile(fresh, sn);
                 // second half of tile j while the first half of tile j+1 forms in s_a (stale but
                 // harmless data past the last tile)
-                if (more) stage_keys(e_next, (j + 1) & 1);
                 step(TRACK_, st1 * kStageBytes, s_a, s_b, st * kStageBytes + kHalf, st1 * kStageBytes + kHalf, kf,
-                     more ? e_next : 0u, (j + 1) & 1, 0, more);
+                     more ? e_next : 0u, st1 * (8 * kFwdBN), 0, more);
             }
         }
     };
