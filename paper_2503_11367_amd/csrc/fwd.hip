@@ -303,7 +303,7 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     // `kw_off`: byte offset of the tile's mask words in sm.kw (its ring stage)
     typedef const uint64_t __attribute__((address_space(3))) * lds_u8;
     auto mask_scores = [&](uint32_t entry, int kw_off, int kb, floatx16& s) __attribute__((always_inline)) {
-        if (entry & kPartialFlag) {            // workgroup-uniform
+        if (__builtin_expect((entry & kPartialFlag) != 0u, 0)) {   // workgroup-uniform; FULL tiles fall through
             const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kFwdBN;
             // Usually the 32 keys of the half tile are one run of equal mask fields: then every
             // row sees one contiguous range of them, found once per row, and an element costs a
@@ -488,45 +488,56 @@ fwd_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
             for (int i = 0; i < NKF; ++i) kf[i] = read_k(32 * RB, i);
         }
-        // The ring position of tile j is j mod NST; the loop is unrolled NST-fold so that
-        // every stage index below is a compile-time constant.
-        for (int j0 = 0; j0 < n_active; j0 += NST) {
+        // The ring position of tile j is j mod NST; the loops are unrolled NST-fold so that
+        // every stage index below is a compile-time constant.  STEADY: the tile NST-1 ahead
+        // exists (so does tile j+1), and the number of transfers in flight is known.
+        auto tile = [&](auto STEADY_, int j, int st) __attribute__((always_inline)) {
+            constexpr bool STEADY = decltype(STEADY_)::value;
+            constexpr int kHalf = 32 * RB;
+            const int st1 = (st + 1) % NST, sn = (st + NST - 1) % NST;
+            const bool more = STEADY || j + 1 < n_active;
+            const bool ahead = STEADY || j + NST - 1 < n_active;
+            // tile j+1 has landed once at most the transfers of the tiles after it remain
+            if (STEADY) wait_landed(NST - 3);
+            else wait_landed(max(0, min(NST - 3, n_active - 2 - j)));
+            __syncthreads();               // everyone's share landed; stage of tile j-1 is free
+            uint32_t fresh = 0u;
+            if (ahead) {
+                if (((j + NST - 1) & 63) == 0) {
+                    // next 64 list entries (this vector load also drains the transfers in flight)
+                    const int i = j + NST - 1 + lane;
+                    list_chunk = i < n_active ? klist[i] : 0u;
+                    wait_vmcnt<0>();       // awaited here so that no wait is needed after the branch
+                }
+                fresh = entry_at(j + NST - 1);
+                // the two heads' wavefronts share the SIMDs pairwise and leave the barrier together:
+                // the first head's issue their transfers now, the second head's after the first half
+                // tile, so that each SIMD's matrix pipe is fed by one of the two meanwhile
+                if (HPW == 1 || wave < 4) issue_tile(fresh, sn);
+            }
+            const uint32_t e_cur = pend[0], e_next = pend[1];
+#pragma unroll
+            for (int i = 0; i + 1 < NST - 1; ++i) pend[i] = pend[i + 1];
+            pend[NST - 2] = fresh;
+            // first half of tile j (scores in s_a) while the second half's scores form in s_b
+            step(TRACK_, st * kStageBytes + kHalf, s_b, s_a, st * kStageBytes, st1 * kStageBytes, kf, e_cur, st * (8 * kFwdBN),
+                 1, true);
+            if (HPW > 1 && wave >= 4 && ahead) issue_tile(fresh, sn);
+            // second half of tile j while the first half of tile j+1 forms in s_a (stale but
+            // harmless data past the last tile)
+            step(TRACK_, st1 * kStageBytes, s_a, s_b, st * kStageBytes + kHalf, st1 * kStageBytes + kHalf, kf,
+                 more ? e_next : 0u, st1 * (8 * kFwdBN), 0, more);
+        };
+        int j0 = 0;
+        for (; j0 + 2 * NST - 1 <= n_active; j0 += NST) {
+#pragma unroll
+            for (int st = 0; st < NST; ++st) tile(std::true_type{}, j0 + st, st);
+        }
+        for (; j0 < n_active; j0 += NST) {
 #pragma unroll
             for (int st = 0; st < NST; ++st) {
-                const int j = j0 + st;
-                if (j >= n_active) break;
-                constexpr int kHalf = 32 * RB;
-                const int st1 = (st + 1) % NST, sn = (st + NST - 1) % NST;
-                const bool more = j + 1 < n_active;
-                // tile j+1 has landed once at most the transfers of the tiles after it remain
-                wait_landed(max(0, min(NST - 3, n_active - 2 - j)));
-                __syncthreads();               // everyone's share landed; stage of tile j-1 is free
-                uint32_t fresh = 0u;
-                if (j + NST - 1 < n_active) {
-                    if (((j + NST - 1) & 63) == 0) {
-                        // next 64 list entries (this vector load also drains the transfers in flight)
-                        const int i = j + NST - 1 + lane;
-                        list_chunk = i < n_active ? klist[i] : 0u;
-                        wait_vmcnt<0>();       // awaited here so that no wait is needed after the branch
-                    }
-                    fresh = entry_at(j + NST - 1);
-                    // the two heads' wavefronts share the SIMDs pairwise and leave the barrier together:
-                    // the first head's issue their transfers now, the second head's after the first half
-                    // tile, so that each SIMD's matrix pipe is fed by one of the two meanwhile
-                    if (HPW == 1 || wave < 4) issue_tile(fresh, sn);
-                }
-                const uint32_t e_cur = pend[0], e_next = pend[1];
-#pragma unroll
-                for (int i = 0; i + 1 < NST - 1; ++i) pend[i] = pend[i + 1];
-                pend[NST - 2] = fresh;
-                // first half of tile j (scores in s_a) while the second half's scores form in s_b
-                step(TRACK_, st * kStageBytes + kHalf, s_b, s_a, st * kStageBytes, st1 * kStageBytes, kf, e_cur, st * (8 * kFwdBN),
-                     1, true);
-                if (HPW > 1 && wave >= 4 && j + NST - 1 < n_active) issue_tile(fresh, sn);
-                // second half of tile j while the first half of tile j+1 forms in s_a (stale but
-                // harmless data past the last tile)
-                step(TRACK_, st1 * kStageBytes, s_a, s_b, st * kStageBytes + kHalf, st1 * kStageBytes + kHalf, kf,
-                     more ? e_next : 0u, st1 * (8 * kFwdBN), 0, more);
+                if (j0 + st >= n_active) break;
+                tile(std::false_type{}, j0 + st, st);
             }
         }
     };
