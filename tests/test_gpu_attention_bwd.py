@@ -144,6 +144,19 @@ def test_random_layouts(seed, D):
     run_case(lay, blocks, block, Hq=4, Hkv=2, D=D, seed=20 + seed)
 
 
+@pytest.mark.parametrize("block", [48, 80, 240])
+def test_block_size_not_a_power_of_two(block):
+    """Blocks of 48, 80 and 240 tokens (multiples of 16 that divide S = 1920): the
+    64-row steps of the key-outer pass and the 128-row q-tiles of the dQ pass straddle
+    the blocks of the share."""
+    lay = wl.layout_random(130 + block, S=1920, n_samples=2, max_spans=5)
+    nb = lay.S // block
+    rng = np.random.default_rng(block)
+    blocks = rng.permutation(nb)[: max(3, nb // 2)].tolist()
+    run_case(lay, blocks, block, Hq=4, Hkv=2, D=128, seed=150 + block)
+    run_case(lay, sorted(blocks)[:3], block, Hq=2, Hkv=2, D=64, seed=151 + block)
+
+
 def test_special_masks():
     run_case(wl.Layout(512, [], [0, 512]), list(range(4)), 128, 2, 1, 128, seed=41)
     run_case(wl.Layout(512, [(0, 512, 1)], [0, 512]), list(range(4)), 128, 2, 1, 128, seed=42)

@@ -114,6 +114,19 @@ def test_random_layouts(seed, D):
     run_case(lay, blocks, block, Hq=4, Hkv=2, D=D, seed=20 + seed)
 
 
+@pytest.mark.parametrize("block", [48, 80, 240])
+def test_block_size_not_a_power_of_two(block):
+    """N_B only has to be a multiple of 16 that divides S: the 128-row q-tiles of
+    the kernel then straddle blocks of the share (each row's position comes out
+    of a division), and the share's last q-tile is ragged."""
+    lay = wl.layout_random(130 + block, S=1920, n_samples=2, max_spans=5)
+    nb = lay.S // block
+    rng = np.random.default_rng(block)
+    blocks = rng.permutation(nb)[: max(3, nb // 2)].tolist()                # unsorted, ragged n_loc
+    run_case(lay, blocks, block, Hq=4, Hkv=2, D=128, seed=140 + block)
+    run_case(lay, sorted(blocks)[:3], block, Hq=2, Hkv=2, D=64, seed=141 + block)
+
+
 def test_few_work_items_split_into_list_slices():
     """Shares with few (q-tile, head) work items cut every q-tile's k-tile list
     into slices run by separate workgroups and aggregate the partial results:

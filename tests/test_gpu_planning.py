@@ -119,6 +119,15 @@ def test_encode_and_tile_map_with_attend_sets(idx):
             check_tile_map(lay, tile[0], tile[1], use_c=False)
 
 
+@pytest.mark.parametrize("tile", [(48, 48), (80, 80), (240, 240), (48, 128), (640, 16)])
+def test_tile_map_tiles_not_powers_of_two(tile):
+    """The public tile map with tq = tk = N_B for block sizes such as 48, 80 and
+    240 (S = 1920), and with unequal tile sides."""
+    for seed in (131, 132):
+        lay = wl.layout_random(seed, S=1920, n_samples=3, max_spans=5, noncausal_prob=0.2)
+        check_tile_map(lay, tile[0], tile[1], use_c=False)
+
+
 def test_tile_map_many_short_runs():
     """Hundreds of 1-3 token spans of alternating modality: nearly every key
     starts a new run of equal mask fields."""
