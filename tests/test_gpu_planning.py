@@ -242,3 +242,40 @@ def test_balance_workloads_end_to_end(c):
     assert np.array_equal(load.cpu().numpy().view(np.uint64), ref[1])
     assert np.array_equal(blocks.cpu().numpy(), ref[3])
     assert int(load.sum().item()) == int(Wref.sum())
+
+
+@pytest.mark.parametrize("batch", range(3))
+def test_plan_chain_random_shapes(batch):
+    """encode -> tile map -> balance on randomly drawn layouts, with tile sides any
+    divisor of S (odd ones included) and 1 to 64 ranks: every array bit for bit."""
+    rng = np.random.default_rng(700 + batch)
+    for case in range(25):
+        S = int(rng.choice([64, 128, 192, 256, 480, 960, 1024, 1920, 4096, 6144]))
+        kind = int(rng.integers(0, 4))
+        seed = int(rng.integers(0, 100000))
+        if kind == 0:
+            lay = wl.layout_random(seed, S=S, n_samples=int(rng.integers(1, min(40, S // 4))), max_spans=6,
+                                   noncausal_prob=0.3, deny_prob=0.3)
+        elif kind == 1:
+            lay = wl.layout_random(seed, S=S, n_samples=1, max_spans=12, noncausal_prob=0.1)
+        elif kind == 2:
+            lay = wl.layout_lambda([S], int(rng.integers(1, 20)), int(rng.integers(1, S)))
+        else:
+            lay = wl.layout_block_causal(S, int(rng.choice([b for b in (16, 32, 48, 64, 96) if S % b == 0])))
+        divs = [d for d in range(8, S + 1) if S % d == 0 and S // d <= 4096]
+        tq, tk = int(rng.choice(divs)), int(rng.choice(divs))
+        P = int(rng.choice([1, 2, 3, 4, 8, 17, 64]))
+        what = dict(batch=batch, case=case, S=S, kind=kind, seed=seed, tq=tq, tk=tk, P=P)
+        f = fields(lay)
+        bits = gpu_bits(lay)
+        assert np.array_equal(to_np_u64(bits), oracle_bits(lay)), what
+        cls, cnt, rp = mb.tile_map(bits, tq, tk)
+        ref = ot.tile_map(f[0], f[1], f[2], tq, tk, f[3], f[4], windows(lay))
+        assert np.array_equal(cls.cpu().numpy(), ref[0]), what
+        assert np.array_equal(cnt.cpu().numpy().view(np.uint32), ref[1]), what
+        assert np.array_equal(rp.cpu().numpy().view(np.uint64), ref[2]), what
+        rob, load, off, rb = mb.balance(rp, P)
+        r2 = ob.lpt(ref[2], P)
+        assert np.array_equal(rob.cpu().numpy(), r2[0]), what
+        assert np.array_equal(load.cpu().numpy().view(np.uint64), r2[1]), what
+        assert np.array_equal(off.cpu().numpy(), r2[2]) and np.array_equal(rb.cpu().numpy(), r2[3]), what
