@@ -732,7 +732,7 @@ template <int D, int NST>
 struct DqSmem {
     alignas(1024) unsigned char k[NST][kDqBN * D * 2];    // MODE 0: rows (S^T) and transpose (dQ^T)
     alignas(1024) unsigned char v[NST][kDqBN * D * 2];    // same layout: rows (dP^T)
-    uint32_t kss[2][kDqBN];                               // sample/span field and modality of a PARTIAL tile's keys
+    alignas(256) uint64_t kw[NST][kDqBN];                 // mask words of a PARTIAL tile's keys, by ring stage
     alignas(16) float park[4][3][64][4];                  // per wavefront: twelve registers parked while a tile is masked
 };
 
@@ -841,6 +841,7 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     }
     const uint32_t lds_k = lds_addr_of(sm.k[0]) + (wave * NI) * 1024;
     const uint32_t lds_v = lds_addr_of(sm.v[0]) + (wave * NI) * 1024;
+    const uint32_t lds_kw = lds_addr_of(sm.kw[0]);
     auto issue_tile = [&](uint32_t entry, int stage) {
         const int64_t k0 = (int64_t)(entry & ~kPartialFlag) * kDqBN;
         const ushort_t* kt_ = K + k0 * Hkv * D;
@@ -850,6 +851,9 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             dma16(kt_, gk[i], lds_k + stage * kStageBytes + i * 1024);
             dma16(vt_, gv[i], lds_v + stage * kStageBytes + i * 1024);
         }
+        // the mask words of a PARTIAL tile's 64 keys travel with the tile (see the forward kernel)
+        if ((entry & kPartialFlag) && wave < 2)
+            dma4(bits + k0, (uint32_t)(wave * 256 + lane * 4), lds_kw + stage * (8 * kDqBN) + wave * 256);
     };
 
     // fragment addresses (LDS byte addresses at ring stage 0): K and V rows share the lane
@@ -874,7 +878,6 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
             for (int v = 0; v < NV; ++v) ktr_a[db][v] = lds_addr_of(sm.k[0]) + (uint32_t)ft.off[db][v];
     }
-    const uint32_t kss_a = lds_addr_of(sm.kss) + hh * 16;     // key words of rows 8*q4 + 4*hh + 0..3
     auto read_row = [&](uint32_t a, int imm) __attribute__((always_inline)) -> bf16x8 {
         return __builtin_bit_cast(bf16x8, *(lds_u4)(uintptr_t)(a + (uint32_t)imm));
     };
@@ -911,7 +914,7 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     constexpr int kHalf = 32 * RB;
     floatx16 sv[2], dpv[2];                // scores and dP of the tile's two halves, between the phases
     // phase 1 of the tile at LDS offset `tile`
-    auto phase_sdp = [&](int tile, bool partial, int64_t k0) __attribute__((always_inline)) {
+    auto phase_sdp = [&](int tile, int kw_off, bool partial, int64_t k0) __attribute__((always_inline)) {
         // Two independent accumulation chains, alternated; their K and V row fragments are
         // requested two pairs of MFMAs ahead (the compiler on its own requests them one
         // ahead and waits before almost every MFMA), across the two halves of the tile.
@@ -963,8 +966,9 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             for (int kb = 0; kb < 2; ++kb) {
                 // usually the 32 keys of the half tile are one run of equal mask fields: every row
                 // then sees one contiguous range of them (see the forward kernel)
-                const uint32_t ka = lds_addr_of(sm.kss) + (uint32_t)(kb * 128) + (ln & 31u) * 4u;
-                const uint32_t ss_k = *(lds_u1)(uintptr_t)ka, mod_k = *(lds_u1)(uintptr_t)(ka + 4 * kDqBN);
+                typedef const uint64_t __attribute__((address_space(3))) * lds_u8;
+                const uint64_t wk = *(lds_u8)(uintptr_t)(lds_kw + (uint32_t)(kw_off + kb * 256) + (ln & 31u) * 8u);
+                const uint32_t ss_k = word_ss(wk), mod_k = word_mod(wk);
                 const uint32_t ss0 = __builtin_amdgcn_readfirstlane(ss_k), mod0 = __builtin_amdgcn_readfirstlane(mod_k);
                 if (__all(ss_k == ss0 && mod_k == mod0)) {       // wave-uniform
                     const KeyRange r = visible_range(qs, qa, (int32_t)qp, ss0, mod0, (int32_t)k0 + kb * 32, 32);
@@ -979,12 +983,12 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
                 }
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
-                    const u32x4 kw = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(kb * 128 + q4 * 32));
-                    const u32x4 km = *(lds_u4)(uintptr_t)(kss_a + (uint32_t)(4 * kDqBN + kb * 128 + q4 * 32));
+                    // the words of keys 8*q4 + 4*hh + 0..3 of the half tile, one pair at a time
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const int kl = kb * 32 + 8 * q4 + 4 * hh + j;
-                        if (!visible(qs, qa, (int64_t)qp, kw[j], km[j], k0 + kl)) sv[kb][q4 * 4 + j] = -INFINITY;
+                        const uint64_t w1 = *(lds_u8)(uintptr_t)(lds_kw + (uint32_t)(kw_off + kb * 256 + (8 * q4 + j) * 8) + (ln >> 5) * 32u);
+                        if (!visible(qs, qa, (int64_t)qp, word_ss(w1), word_mod(w1), k0 + kl)) sv[kb][q4 * 4 + j] = -INFINITY;
                         // one element at a time: no register is free for a second one's temporaries
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -1055,20 +1059,12 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
 #pragma unroll
                 for (int j = 0; j + 1 < PD; ++j) pend[j] = pend[j + 1];
                 pend[PD - 1] = fresh;
-                if (partial) {
-                    if (tid < kDqBN) {
-                        const uint64_t wk = bits[k0 + tid];
-                        sm.kss[0][tid] = word_ss(wk);
-                        sm.kss[1][tid] = word_mod(wk);
-                    }
-                    __syncthreads();
-                }
                 body(it, st, partial, k0);
             }
         }
     };
     tiles([&](int it, int st, bool partial, int64_t k0) __attribute__((always_inline)) {
-        phase_sdp(st * kStageBytes, partial, k0);
+        phase_sdp(st * kStageBytes, st * (8 * kDqBN), partial, k0);
         phase_dq(st * kStageBytes);
     });
 
