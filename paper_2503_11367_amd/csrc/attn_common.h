@@ -257,13 +257,10 @@ struct TilePlanT {
 };
 constexpr int kSliceLen = 0, kSlicedTiles = 1, kExtraUsed = 2, kSliceInts = 4;
 
-// int32 words cleared by launch_validate_blocks at `err`: the error flag and spare words;
-// the word after them holds the slice length chosen by the list builder
-constexpr int kFlagInts = 4;
+// The kFlagInts int32 words at `err` (cleared by validate_blocks_body) are the error flag and
+// spare words; the word after them holds the slice length chosen by the list builder.
 int launch_compact_rows(const TilePlan& p, hipStream_t st);
 int launch_compact_cols(const TilePlanT& p, hipStream_t st);
 int launch_compact_both(const TilePlan& pa, const TilePlanT& pb, hipStream_t st);
-int launch_validate_blocks(const int32_t* blocks, int32_t n_blocks, int64_t n_seq_blocks,
-                           int32_t* clean, int32_t* err, hipStream_t st);
 
 }  // namespace mm

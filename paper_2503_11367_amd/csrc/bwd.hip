@@ -6,9 +6,10 @@
 //                                      Hq/Hkv query heads of the KV head)
 //   dQ = scale dS K
 // Launches:
-//   bwd_prep_kernel  Delta and LSE in base-2 units, padded to whole q-tiles, every
+//   bwd_prologue_kernel  Delta and LSE in base-2 units, padded to whole q-tiles, every
 //                  row's mask inputs, and head-major copies of Q and dO for the
-//                  key-outer pass;
+//                  key-outer pass; beside them, in the same launch, the two tile maps
+//                  and the check of the block list;
 //   dkv_kernel     key-outer: a workgroup owns 128 keys of one KV head and streams
 //                  the active 64-row query tiles of its share of the group's heads
 //                  through LDS rings; per 32-key block one wavefront forms P and
@@ -30,6 +31,7 @@
 // ds_read_b128 / ds_read_b64_tr_b16.
 #include <type_traits>
 #include "attn_common.h"
+#include "tilemap_body.h"
 
 namespace mm {
 
@@ -46,15 +48,35 @@ namespace mm {
 //                      which in the token-major layout are Hq*D*2 bytes apart -- a
 //                      power-of-two stride that lands a whole tile stream on a few L2
 //                      sets (measured: half of all tile requests missed).
+// `blocks` is the caller's unchecked list (an entry outside [0, n_seq_blocks) counts as
+// block 0, as in the checked copy the later kernels use).
+struct BwdPrepArgs {
+    const ushort_t *Q, *O, *dO;
+    const float* lse;
+    const uint64_t* bits;
+    const int32_t* blocks;
+    int32_t block, Hq;
+    int64_t n_seq_blocks, n_loc, n_pad;
+    float inv_scale;
+    float *ld, *ldk;
+    ushort_t *qh, *doh;
+};
 template <int D>
-__global__ void __launch_bounds__(256)
-bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
-                const ushort_t* __restrict__ dO, const float* __restrict__ lse,
-                const uint64_t* __restrict__ bits, const int32_t* __restrict__ blocks, int32_t block,
-                int64_t n_loc, int64_t n_pad, int32_t Hq, float inv_scale, float* __restrict__ ld,
-                float* __restrict__ ldk, ushort_t* __restrict__ qh, ushort_t* __restrict__ doh) {
+__device__ __forceinline__ void bwd_prep_body(int64_t wg, const BwdPrepArgs& p) {
+    const ushort_t* __restrict__ Q = p.Q;
+    const ushort_t* __restrict__ O = p.O;
+    const ushort_t* __restrict__ dO = p.dO;
+    const float* __restrict__ lse = p.lse;
+    const uint64_t* __restrict__ bits = p.bits;
+    const int64_t n_loc = p.n_loc, n_pad = p.n_pad;
+    const int32_t Hq = p.Hq;
+    const float inv_scale = p.inv_scale;
+    float* __restrict__ ld = p.ld;
+    float* __restrict__ ldk = p.ldk;
+    ushort_t* __restrict__ qh = p.qh;
+    ushort_t* __restrict__ doh = p.doh;
     constexpr int TPR = D / 8;
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t gid = wg * 256 + threadIdx.x;
     // head-major thread order: a workgroup writes 16 consecutive rows of one head's copies
     // (4 KiB contiguous) and reads 256-byte pieces of the token-major inputs; measured 7 us
     // faster on the 8k workload than contiguous reads with the writes scattered over the heads
@@ -96,7 +118,7 @@ bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
                 uint32_t ss = 0u, ca = 0u;
                 int64_t pos = 0;
                 if (ok) {
-                    pos = row_pos(blocks, block, row);
+                    pos = row_pos_checked(p.blocks, p.block, p.n_seq_blocks, row);
                     const uint64_t w = bits[pos];
                     ss = word_ss(w);
                     ca = word_att(w);
@@ -106,6 +128,31 @@ bwd_prep_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ O,
                 info[2 * n_pad] = (uint32_t)pos;
             }
         }
+    }
+}
+
+// Everything the backward prepares that depends on nothing but the caller's inputs, in
+// one launch: the workgroups of the two tile maps (query-outer for dQ, key-outer for
+// dK/dV) first, then one that checks the block list, then those of the preparation above.
+struct BwdPrologue {
+    TileMapJobs maps;
+    uint32_t n_map_wgs;
+    int32_t n_blocks;
+    int32_t* clean;
+    int32_t* err;
+    BwdPrepArgs prep;
+};
+template <int D>
+__global__ void __launch_bounds__(256)
+bwd_prologue_kernel(const BwdPrologue p) {
+    static_assert(kTmThreads == 256, "one workgroup shape for all three jobs");
+    if (blockIdx.x < p.n_map_wgs) {
+        tile_map_body(blockIdx.x, p.prep.bits, p.prep.blocks, p.prep.block, p.prep.n_seq_blocks,
+                      p.prep.n_loc, p.maps);
+    } else if (blockIdx.x == p.n_map_wgs) {
+        validate_blocks_body(p.prep.blocks, p.n_blocks, p.prep.n_seq_blocks, p.clean, p.err);
+    } else {
+        bwd_prep_body<D>((int64_t)(blockIdx.x - p.n_map_wgs - 1u), p.prep);
     }
 }
 
@@ -1236,22 +1283,26 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     pb.pbase = (int32_t*)(base + L.pbase);
     pb.extra = (int32_t*)(base + L.extra);
 
-    int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
-    if (rc) return rc;
-    // both plans (query-outer for dQ, key-outer for dK/dV) side by side: three launches
-    rc = launch_tile_maps(a.bits, a.S, clean, a.block, n_loc, kDqBM, kDqBN, pa.cls, kKvBM, kKvBN, pb.cls,
-                          st);
-    if (rc) return rc;
-    rc = launch_compact_both(pa, pb, st);
-    if (rc) return rc;
-
+    // both plans side by side with the block-list check and the row constants: one launch,
+    // then the list builder's two
     const float scale_log2 = a.scale * kLog2e;
     {
+        BwdPrologue p;
+        p.maps.j[0] = tile_map_job(a.S, n_loc, kDqBM, kDqBN, pa.cls, nullptr);
+        p.maps.j[1] = tile_map_job(a.S, n_loc, kKvBM, kKvBN, pb.cls, nullptr);
+        p.n_map_wgs = tile_map_workgroups(p.maps, 2);
+        p.n_blocks = a.n_blocks;
+        p.clean = clean; p.err = err;
+        p.prep = BwdPrepArgs{(const ushort_t*)a.q, (const ushort_t*)o, (const ushort_t*)d_o, lse, a.bits,
+                             a.blocks, a.block, a.Hq, a.S / a.block, n_loc, L.n_pad, 1.0f / a.scale,
+                             ld, ldk, qh, doh};
         const int64_t threads = L.n_pad * a.Hq * (D / 8);
-        hipLaunchKernelGGL(bwd_prep_kernel<D>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
-                           st, (const ushort_t*)a.q, (const ushort_t*)o, (const ushort_t*)d_o, lse,
-                           a.bits, clean, a.block, n_loc, L.n_pad, a.Hq, 1.0f / a.scale, ld, ldk, qh, doh);
+        const unsigned grid = p.n_map_wgs + 1u + (unsigned)((threads + 255) / 256);
+        hipLaunchKernelGGL(bwd_prologue_kernel<D>, dim3(grid), dim3(256), 0, st, p);
+        MM_LAUNCH_CHECK();
     }
+    int rc = launch_compact_both(pa, pb, st);
+    if (rc) return rc;
     const int rep = a.Hq / a.Hkv;
     stage_begin(MMATTN_STAGE_DKV, st);
     hipLaunchKernelGGL(dkv_kernel<D>, dim3((unsigned)((int64_t)(L.nk_b + L.n_extra) * a.Hkv * L.ch.cmax)),

@@ -114,6 +114,17 @@ __device__ __forceinline__ int64_t row_pos(const int32_t* blocks, int32_t block,
     return (int64_t)blocks[b] * block + (r - b * block);
 }
 
+// The same for a block list nobody has checked yet: an entry outside [0, n_seq_blocks)
+// counts as block 0.
+__device__ __forceinline__ int64_t row_pos_checked(const int32_t* blocks, int32_t block,
+                                                   int64_t n_seq_blocks, int64_t r) {
+    if (!blocks) return r;
+    const int64_t b = r / block;
+    int64_t g = blocks[b];
+    if (g < 0 || g >= n_seq_blocks) g = 0;
+    return g * block + (r - b * block);
+}
+
 // ---- entry points implemented per translation unit (host side) -------------
 int launch_mfma_ceiling(int32_t iters, int32_t random_operands, float* sink, double* flops,
                         hipStream_t st);
@@ -122,9 +133,6 @@ int launch_encode(const mmattn_span* spans, int32_t n_spans, const int64_t* samp
 int launch_tile_map(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
                     int64_t n_rows, int32_t tq, int32_t tk, uint8_t* d_cls, uint32_t* d_cnt,
                     uint64_t* d_rowpairs, hipStream_t st);
-int launch_tile_maps(const uint64_t* d_bits, int64_t S, const int32_t* d_blocks, int32_t block,
-                     int64_t n_rows, int32_t tq_a, int32_t tk_a, uint8_t* d_cls_a, int32_t tq_b,
-                     int32_t tk_b, uint8_t* d_cls_b, hipStream_t st);
 int launch_balance(const uint64_t* d_W, int32_t nB, int32_t P, int32_t* d_rank_of_block,
                    uint64_t* d_load, int32_t* d_rank_off, int32_t* d_rank_blocks, hipStream_t st);
 

@@ -30,6 +30,7 @@
 #include <mutex>
 #include <type_traits>
 #include "attn_common.h"
+#include "tilemap_body.h"
 
 namespace mm {
 
@@ -50,15 +51,15 @@ constexpr float kScoreBound = 90.0f;
 constexpr int kNormChunks = 64;     // partial maxima of the squared key norms per KV head
 
 // Largest squared key norm of every KV head, as kNormChunks partial maxima per head (no
-// atomics: the attention kernel takes the maximum of its head's partials).  grid
-// (kNormChunks, heads of the launch); a chunk is S / kNormChunks consecutive keys.
+// atomics: the attention kernel takes the maximum of its head's partials).  One workgroup
+// of 256 threads per (chunk, head of the launch); a chunk is S / kNormChunks consecutive keys.
 template <int D>
-__global__ void __launch_bounds__(256)
-key_norm_kernel(const ushort_t* __restrict__ K, int64_t S, int32_t Hkv_s, float* __restrict__ knorm) {
+__device__ __forceinline__ void
+key_norm_body(int chunk, int g, const ushort_t* __restrict__ K, int64_t S, int32_t Hkv_s,
+              float* __restrict__ knorm) {
     constexpr int TPK = D / 8;                            // threads per key, 8 elements each
     constexpr int KPP = 256 / TPK;                        // keys per pass
     __shared__ float wmax[4];
-    const int chunk = blockIdx.x, g = blockIdx.y;
     const int64_t per = S / kNormChunks, k0 = chunk * per;
     const int sub = threadIdx.x % TPK, kk = threadIdx.x / TPK;
     float best = 0.f;
@@ -77,6 +78,46 @@ key_norm_kernel(const ushort_t* __restrict__ K, int64_t S, int32_t Hkv_s, float*
     __syncthreads();
     if (threadIdx.x == 0)
         knorm[(int64_t)g * kNormChunks + chunk] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+}
+
+// grid (kNormChunks, heads of the launch): the key norms alone, for a call whose plan is
+// already in the workspace
+template <int D>
+__global__ void __launch_bounds__(256)
+key_norm_kernel(const ushort_t* __restrict__ K, int64_t S, int32_t Hkv_s, float* __restrict__ knorm) {
+    key_norm_body<D>((int)blockIdx.x, (int)blockIdx.y, K, S, Hkv_s, knorm);
+}
+
+// Everything the forward prepares that depends on nothing but the caller's inputs, in one
+// launch: the workgroups of the tile map first, then one that checks the block list, then
+// those of the key norms.  The tile map reads the caller's list with the same rule for bad
+// entries as the check applies, so neither waits for the other.
+struct FwdPrologue {
+    TileMapJobs maps;
+    uint32_t n_map_wgs;
+    const uint64_t* bits;
+    const int32_t* blocks;
+    int32_t n_blocks, block;
+    int64_t n_seq_blocks, n_rows;
+    int32_t* clean;
+    int32_t* err;
+    const ushort_t* K;
+    int64_t S;
+    int32_t Hkv_s;
+    float* knorm;
+};
+template <int D>
+__global__ void __launch_bounds__(256)
+fwd_prologue_kernel(const FwdPrologue p) {
+    static_assert(kTmThreads == 256, "one workgroup shape for all three jobs");
+    if (blockIdx.x < p.n_map_wgs) {
+        tile_map_body(blockIdx.x, p.bits, p.blocks, p.block, p.n_seq_blocks, p.n_rows, p.maps);
+    } else if (blockIdx.x == p.n_map_wgs) {
+        validate_blocks_body(p.blocks, p.n_blocks, p.n_seq_blocks, p.clean, p.err);
+    } else {
+        const uint32_t w = blockIdx.x - p.n_map_wgs - 1u;
+        key_norm_body<D>((int)(w % kNormChunks), (int)(w / kNormChunks), p.K, p.S, p.Hkv_s, p.knorm);
+    }
 }
 
 template <int D, int NST>
@@ -739,23 +780,27 @@ int launch_fwd(const AttnArgs& a, void* o, float* lse, void* ws, hipStream_t st)
     plan.csz = err + kFlagInts;
     plan.groups = a.Hq / a.Hkv * a.kv_count / (a.Hq / a.Hkv % 2 == 0 ? 2 : 1);
 
-    if (!a.plan_ready) {
-        int rc = launch_validate_blocks(a.blocks, a.n_blocks, a.S / a.block, clean, err, st);
-        if (rc) return rc;
-        rc = launch_tile_map(a.bits, a.S, clean, a.block, n_loc, kFwdBM, kFwdBN, plan.cls, nullptr,
-                             nullptr, st);
-        if (rc) return rc;
-        rc = launch_compact_rows(plan, st);
-        if (rc) return rc;
-    }
-
     const float scale_log2 = a.scale * kLog2e;
     const int32_t rep = a.Hq / a.Hkv;
     const bool pair = rep % 2 == 0;                // two heads of a KV group per workgroup
     // largest key norms of the window's heads (data, not plan: every call)
     float* knorm = (float*)(base + L.knorm) + (int64_t)a.kv_begin * kNormChunks;
-    {
-        const ushort_t* kw = (const ushort_t*)a.k + (int64_t)a.kv_begin * a.D;
+    const ushort_t* kw = (const ushort_t*)a.k + (int64_t)a.kv_begin * a.D;
+    if (!a.plan_ready) {
+        FwdPrologue p;
+        p.maps.j[0] = p.maps.j[1] = tile_map_job(a.S, n_loc, kFwdBM, kFwdBN, plan.cls, nullptr);
+        p.n_map_wgs = tile_map_workgroups(p.maps, 1);
+        p.bits = a.bits; p.blocks = a.blocks; p.n_blocks = a.n_blocks; p.block = a.block;
+        p.n_seq_blocks = a.S / a.block; p.n_rows = n_loc;
+        p.clean = clean; p.err = err;
+        p.K = kw; p.S = a.S; p.Hkv_s = a.Hkv; p.knorm = knorm;
+        const unsigned grid = p.n_map_wgs + 1u + (unsigned)(kNormChunks * a.kv_count);
+        if (a.D == 128) hipLaunchKernelGGL(fwd_prologue_kernel<128>, dim3(grid), dim3(256), 0, st, p);
+        else            hipLaunchKernelGGL(fwd_prologue_kernel<64>, dim3(grid), dim3(256), 0, st, p);
+        MM_LAUNCH_CHECK();
+        const int rc = launch_compact_rows(plan, st);
+        if (rc) return rc;
+    } else {
         if (a.D == 128)
             hipLaunchKernelGGL(key_norm_kernel<128>, dim3(kNormChunks, (unsigned)a.kv_count), dim3(256), 0, st, kw,
                                a.S, a.Hkv, knorm);

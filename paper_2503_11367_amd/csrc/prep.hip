@@ -1,4 +1,4 @@
-// Preparation kernels for the attention passes: block-list sanitising and
+// Preparation kernels for the attention passes:
 // compaction of the tile classes into per-tile work lists (so that fully masked tiles are never visited --
 // the block skipping of paper section 3.2.1) ordered longest first (the
 // intra-GPU balance concern of section 3.2.2: long query blocks start early so
@@ -6,34 +6,6 @@
 #include "attn_common.h"
 
 namespace mm {
-
-// ---- block list ------------------------------------------------------------
-// One workgroup: clears the error flag (the flag block is kFlagInts int32 wide),
-// then copies the block list, replacing
-// out-of-range entries by 0 and raising the flag.
-__global__ void __launch_bounds__(256)
-validate_blocks_kernel(const int32_t* __restrict__ blocks, int32_t n_blocks, int64_t n_seq_blocks,
-                       int32_t* __restrict__ clean, int32_t* __restrict__ err) {
-    int bad = 0;
-    for (int i = threadIdx.x; i < n_blocks; i += 256) {
-        int32_t b = blocks[i];
-        if (b < 0 || b >= n_seq_blocks) {
-            bad = 1;
-            b = 0;
-        }
-        clean[i] = b;
-    }
-    bad = __syncthreads_or(bad);
-    if (threadIdx.x < kFlagInts) err[threadIdx.x] = threadIdx.x == 0 ? bad : 0;
-}
-
-int launch_validate_blocks(const int32_t* blocks, int32_t n_blocks, int64_t n_seq_blocks,
-                           int32_t* clean, int32_t* err, hipStream_t st) {
-    hipLaunchKernelGGL(validate_blocks_kernel, dim3(1), dim3(256), 0, st, blocks, n_blocks,
-                       n_seq_blocks, clean, err);
-    MM_LAUNCH_CHECK();
-    return MMATTN_OK;
-}
 
 // ---- work lists ---------------------------------------------------------------
 // One wavefront per line (a q-tile's row of classes, or a k-tile's column) compacts
