@@ -6,10 +6,14 @@
 //                                      Hq/Hkv query heads of the KV head)
 //   dQ = scale dS K
 // Launches:
-//   bwd_prologue_kernel  Delta and LSE in base-2 units, padded to whole q-tiles, every
-//                  row's mask inputs, and head-major copies of Q and dO for the
-//                  key-outer pass; beside them, in the same launch, the two tile maps
-//                  and the check of the block list;
+//   bwd_prologue_kernel  the two tile maps and the check of the block list; for large
+//                  shares also the inputs of the key-outer pass (see below);
+//   dq_kernel      query-outer: a workgroup of four wavefronts owns 128 query rows of one
+//                  head and walks the active 64-key tiles (two-stage K/V ring).  It forms
+//                  Delta from the O and dO rows it holds.  On small shares it runs first and
+//                  leaves the key-outer pass its inputs: head-major copies of Q and dO padded
+//                  to whole q-tiles, -LSE/scale and -Delta per row, every row's mask inputs;
+//                  on large shares it runs last;
 //   dkv_kernel     key-outer: a workgroup owns 128 keys of one KV head and streams
 //                  the active 64-row query tiles of its share of the group's heads
 //                  through LDS rings; per 32-key block one wavefront forms P and
@@ -22,9 +26,7 @@
 //                  query tiles is far longer than the others' (keys that nearly every
 //                  row attends) is cut into list slices, each a workgroup of its own;
 //                  the partials are fp32, live in a pool of per-k-tile slots and are
-//                  summed in a fixed order by dkv_reduce_kernel;
-//   dq_kernel      query-outer: a workgroup of four wavefronts owns 128 query rows of one
-//                  head and walks the active 64-key tiles (two-stage K/V ring).
+//                  summed in a fixed order by dkv_reduce_kernel.
 // All contractions are 32x32x16 bf16 MFMAs.  Tiles go global -> LDS directly
 // (no registers) into rotation-swizzled layouts; a tile that is needed both as
 // row fragments and transposed is stored once (SwzTile MODE 0) and read with
@@ -36,20 +38,23 @@
 namespace mm {
 
 // ---------------------------------------------------------------- prep -------
-// One thread per 8 elements; D/8 consecutive lanes reduce one (row, head).
-//   ldk[Hq][2][n_pad] = -LSE/scale, then -Delta (padding rows: -inf, 0): the key-outer pass
-//                      starts its S and dP accumulators from these
-//   ld[Hq][2][n_pad] = LSE in base-2 units, then Delta = rowsum(dO o O), per head; rows
-//                      n_loc .. n_pad-1 are padding: LSE = +inf (probability 0), Delta = 0;
-//                      followed by [3][n_pad] uint32: every local row's sample/span field,
-//                      attend-set (0 without the causal bit) and sequence position (the mask inputs of the key-outer pass)
-//   qh, doh [Hq][n_pad][D]  head-major copies of Q and dO (padding rows zero) for the
-//                      key-outer pass: there a tile is 64 consecutive rows of ONE head,
-//                      which in the token-major layout are Hq*D*2 bytes apart -- a
-//                      power-of-two stride that lands a whole tile stream on a few L2
-//                      sets (measured: half of all tile requests missed).
-// `blocks` is the caller's unchecked list (an entry outside [0, n_seq_blocks) counts as
-// block 0, as in the checked copy the later kernels use).
+// What the key-outer pass reads per row:
+//   ldk[Hq][2][n_pad] = -LSE/scale, then -Delta with Delta = rowsum(dO o O) (padding rows
+//                      n_loc .. n_pad-1: -inf, 0): the pass starts its S and dP accumulators
+//                      from these
+//   info[3][n_pad]     uint32: every local row's sample/span field, attend-set (0 without
+//                      the causal bit) and sequence position (the mask inputs of the pass)
+//   ld[Hq][2][n_pad]   (only when a preparation of its own writes all this) LSE in base-2
+//                      units, then Delta, for the query-outer pass (padding rows: +inf, 0)
+//   qh, doh [Hq][n_pad][D]  head-major copies of Q and dO (padding rows zero): there a tile
+//                      is 64 consecutive rows of ONE head, which in the token-major layout
+//                      are Hq*D*2 bytes apart -- a power-of-two stride that lands a whole
+//                      tile stream on a few L2 sets (measured: half of all tile requests
+//                      missed).
+// Written by the query-outer pass on its way when that pass runs first (small shares, see
+// launch_bwd_d), else by the workgroups below: one thread per 8 elements; D/8 consecutive
+// lanes reduce one (row, head).  `blocks` is the caller's unchecked list (an entry outside
+// [0, n_seq_blocks) counts as block 0, as in the checked copy the later kernels use).
 struct BwdPrepArgs {
     const ushort_t *Q, *O, *dO;
     const float* lse;
@@ -59,6 +64,7 @@ struct BwdPrepArgs {
     int64_t n_seq_blocks, n_loc, n_pad;
     float inv_scale;
     float *ld, *ldk;
+    uint32_t* info;
     ushort_t *qh, *doh;
 };
 template <int D>
@@ -66,13 +72,8 @@ __device__ __forceinline__ void bwd_prep_body(int64_t wg, const BwdPrepArgs& p) 
     const ushort_t* __restrict__ Q = p.Q;
     const ushort_t* __restrict__ O = p.O;
     const ushort_t* __restrict__ dO = p.dO;
-    const float* __restrict__ lse = p.lse;
-    const uint64_t* __restrict__ bits = p.bits;
     const int64_t n_loc = p.n_loc, n_pad = p.n_pad;
     const int32_t Hq = p.Hq;
-    const float inv_scale = p.inv_scale;
-    float* __restrict__ ld = p.ld;
-    float* __restrict__ ldk = p.ldk;
     ushort_t* __restrict__ qh = p.qh;
     ushort_t* __restrict__ doh = p.doh;
     constexpr int TPR = D / 8;
@@ -104,36 +105,36 @@ __device__ __forceinline__ void bwd_prep_body(int64_t wg, const BwdPrepArgs& p) 
         *(u32x4*)(qh + e) = qv;
         *(u32x4*)(doh + e) = dv;
         if (c == 0) {
-            float* out = ld + (int64_t)h * 2 * n_pad + row;
-            const float l = ok ? lse[(int64_t)h * n_loc + row] : INFINITY;
+            const float l = ok ? p.lse[(int64_t)h * n_loc + row] : INFINITY;
+            float* out = p.ld + (int64_t)h * 2 * n_pad + row;
             out[0] = l * kLog2e;
             out[n_pad] = ok ? acc : 0.f;
-            // the same as accumulator start values for the key-outer pass: S - LSE/scale and
-            // dP - Delta come straight out of the matrix instructions
-            float* outk = ldk + (int64_t)h * 2 * n_pad + row;
-            outk[0] = -l * inv_scale;
+            float* outk = p.ldk + (int64_t)h * 2 * n_pad + row;
+            outk[0] = -l * p.inv_scale;
             outk[n_pad] = ok ? -acc : 0.f;
             if (h == 0) {
-                uint32_t* info = (uint32_t*)(ld + (int64_t)Hq * 2 * n_pad) + row;
                 uint32_t ss = 0u, ca = 0u;
                 int64_t pos = 0;
                 if (ok) {
                     pos = row_pos_checked(p.blocks, p.block, p.n_seq_blocks, row);
-                    const uint64_t w = bits[pos];
+                    const uint64_t w = p.bits[pos];
                     ss = word_ss(w);
                     ca = word_att(w);
                 }
-                info[0] = ss;
-                info[n_pad] = ca;
-                info[2 * n_pad] = (uint32_t)pos;
+                p.info[row] = ss;
+                p.info[n_pad + row] = ca;
+                p.info[2 * n_pad + row] = (uint32_t)pos;
             }
         }
     }
 }
 
-// Everything the backward prepares that depends on nothing but the caller's inputs, in
-// one launch: the workgroups of the two tile maps (query-outer for dQ, key-outer for
-// dK/dV) first, then one that checks the block list, then those of the preparation above.
+// ---------------------------------------------------------------- prologue ---
+// Everything the backward prepares that depends on nothing but the caller's inputs, in one
+// launch: the workgroups of the two tile maps (query-outer for dQ, key-outer for dK/dV),
+// then one that checks the block list, then (large shares only) those of the preparation
+// above.  The tile maps read the caller's list with the same rule for bad entries as the
+// check applies, so nothing in the launch waits for anything else.
 struct BwdPrologue {
     TileMapJobs maps;
     uint32_t n_map_wgs;
@@ -202,7 +203,7 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
            const ushort_t* __restrict__ V, const ushort_t* __restrict__ dOh,
            const uint64_t* __restrict__ bits, const int32_t* __restrict__ blocks, int32_t block,
            int64_t n_loc, int64_t n_pad, int64_t S, int32_t Hq, int32_t Hkv, float scale,
-           float scale_log2, const float* __restrict__ ld_g, const float* __restrict__ ldk_g,
+           float scale_log2, const uint32_t* __restrict__ info_g, const float* __restrict__ ldk_g,
            TilePlanT plan, KvChunking ch, const int32_t* __restrict__ err,
            ushort_t* __restrict__ dK, ushort_t* __restrict__ dV, float* __restrict__ pool) {
     constexpr int NDS = D / 16, NDB = D / 32;
@@ -298,7 +299,6 @@ dkv_kernel(const ushort_t* __restrict__ Qh, const ushort_t* __restrict__ K,
     const uint32_t lds_d = lds_addr_of(sm.d[0]) + (wave * NI) * 1024;
     const uint32_t lds_ld = lds_addr_of(sm.ld[0][0]);
     const uint32_t lds_info = lds_addr_of(sm.info[0][0]);
-    const uint32_t* info_g = (const uint32_t*)(ld_g + (int64_t)Hq * 2 * n_pad);
     // Tile addresses are kept as running pointers (the head's base advances by one head
     // stride when the walk reaches the next head), so that issuing a step's transfers costs
     // a shift and an add per tensor: a wave issues one instruction every four cycles, and
@@ -789,9 +789,11 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
           const ushort_t* __restrict__ V, const ushort_t* __restrict__ dO,
           const uint64_t* __restrict__ bits, const int32_t* __restrict__ blocks, int32_t block,
           int64_t n_loc, int64_t n_pad, int64_t S, int32_t Hq, int32_t Hkv, float scale,
-          float scale_log2, const float* __restrict__ ld_g,
-          TilePlan plan, FwdSplit split, const int32_t* __restrict__ err,
-          ushort_t* __restrict__ dQ, float* __restrict__ dQpart) {
+          float scale_log2, const ushort_t* __restrict__ O, const float* __restrict__ lse,
+          const float* __restrict__ ld_g, TilePlan plan, FwdSplit split, const int32_t* __restrict__ err,
+          ushort_t* __restrict__ dQ, float* __restrict__ dQpart,
+          ushort_t* __restrict__ qh, ushort_t* __restrict__ doh, float* __restrict__ ldk,
+          uint32_t* __restrict__ info) {
     constexpr int NDS = D / 16, NDB = D / 32;
     constexpr int NW = 4 * HPW;
     constexpr int RB = D * 2;
@@ -839,11 +841,18 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
     const bool row_ok = row < n_loc;
     int64_t q_pos = 0;
     uint32_t q_ss = 0, q_causal = 0;
-    // +inf on padding rows; a row that sees no key has LSE = -inf and all its scores masked
-    // (-inf): taking +inf for it as well makes every probability 0 instead of exp2(-inf + inf)
-    const float lse2_raw = ld_g[(int64_t)h * 2 * n_pad + row];
-    const float my_lse2 = lse2_raw == -INFINITY ? INFINITY : lse2_raw;
-    const float my_delta = ld_g[((int64_t)h * 2 + 1) * n_pad + row];
+    // LSE in base-2 units: +inf on padding rows; a row that sees no key has LSE = -inf and all
+    // its scores masked (-inf): taking +inf for it as well makes every probability 0 instead
+    // of exp2(-inf + inf).  Delta = rowsum(dO o O) comes from the preparation (ld_g given) or
+    // is formed here from the row's O and dO (this lane's 64 head-dim values, then the other
+    // half-wave's).
+    const bool own_delta = ld_g == nullptr;             // kernel argument: uniform
+    float my_lse2 = INFINITY, my_delta = 0.f;
+    if (!own_delta) {
+        const float l2 = ld_g[(int64_t)h * 2 * n_pad + row];
+        my_lse2 = l2 == -INFINITY ? INFINITY : l2;
+        my_delta = ld_g[((int64_t)h * 2 + 1) * n_pad + row];
+    }
     bf16x8 qf[NDS], dof[NDS];
 #pragma unroll
     for (int ds = 0; ds < NDS; ++ds) {
@@ -861,7 +870,20 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
             qf[ds] = __builtin_bit_cast(bf16x8, *(const u32x4*)(Q + off + ds * 16));
             dof[ds] = __builtin_bit_cast(bf16x8, *(const u32x4*)(dO + off + ds * 16));
         }
+        if (own_delta) {
+            const float l2 = lse[(int64_t)h * n_loc + row] * kLog2e;
+            my_lse2 = l2 == -INFINITY ? INFINITY : l2;
+            bf16x8 of[NDS];
+#pragma unroll
+            for (int ds = 0; ds < NDS; ++ds)
+                of[ds] = __builtin_bit_cast(bf16x8, *(const u32x4*)(O + off + ds * 16));
+#pragma unroll
+            for (int ds = 0; ds < NDS; ++ds)
+#pragma unroll
+                for (int u = 0; u < 8; ++u) my_delta += (float)of[ds][u] * (float)dof[ds][u];
+        }
     }
+    if (own_delta) my_delta += __shfl_xor(my_delta, 32);
     // entries past the list's length, inside the q-tile's row of the list array, are read
     // but never used
     uint32_t list_chunk = chunk * csz + lane < plan.nk ? klist[lane] : 0u;
@@ -1115,6 +1137,29 @@ dq_kernel(const ushort_t* __restrict__ Q, const ushort_t* __restrict__ K,
         phase_dq(st * kStageBytes);
     });
 
+    // When this pass runs ahead of the key-outer pass (qh given), the workgroup that holds a
+    // row's Q and dO anyway (the first slice of a split list) leaves that pass its inputs: the
+    // head-major copies, the start values of its accumulators and, once per row, the mask
+    // inputs (see bwd_prep_body).  All rows below n_pad are written (padding rows: zeros).
+    if (qh != nullptr && chunk == 0) {
+        ushort_t* qd = qh + ((int64_t)h * n_pad + row) * D + hh * 8;
+        ushort_t* dd = doh + ((int64_t)h * n_pad + row) * D + hh * 8;
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) {
+            *(u32x4*)(qd + ds * 16) = __builtin_bit_cast(u32x4, qf[ds]);
+            *(u32x4*)(dd + ds * 16) = __builtin_bit_cast(u32x4, dof[ds]);
+        }
+        if (hh == 0) {
+            const float l = row_ok ? lse[(int64_t)h * n_loc + row] : INFINITY;
+            ldk[(int64_t)h * 2 * n_pad + row] = -l * (1.0f / scale);
+            ldk[((int64_t)h * 2 + 1) * n_pad + row] = -my_delta;
+            if (h == 0) {
+                info[row] = q_ss;
+                info[n_pad + row] = q_causal;
+                info[2 * n_pad + row] = (uint32_t)q_pos;
+            }
+        }
+    }
     if (!row_ok) return;
     if (nchunk > 1) {
         // this slice's partial sum, fp32, summed over the slices by dq_combine_kernel
@@ -1170,7 +1215,7 @@ dq_combine_kernel(TilePlan plan, FwdSplit split, int64_t n_loc, int64_t n_pad, i
 
 // ---------------------------------------------------------------- host -------
 struct BwdLayout {
-    size_t err, clean_blocks, ld, ldk, qh, doh, cls_a, kcount, klist, qorder, cls_b, qcount, qlist,
+    size_t err, clean_blocks, ld, info, ldk, qh, doh, cls_a, kcount, klist, qorder, cls_b, qcount, qlist,
         korder, slicing, pbase, extra, pool, dq_part, total;
     int32_t nq_a, nk_a, nq_b, nk_b, n_extra;
     int64_t n_pad;
@@ -1206,7 +1251,8 @@ static BwdLayout bwd_layout(int64_t S, int64_t n_loc, int32_t n_blocks, int32_t 
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
     L.err = take(256);
     L.clean_blocks = take((size_t)n_blocks * 4);
-    L.ld = take(((size_t)Hq * 2 + 3) * L.n_pad * 4);
+    L.ld = take((size_t)Hq * 2 * L.n_pad * 4);
+    L.info = take((size_t)3 * L.n_pad * 4);
     L.ldk = take((size_t)Hq * 2 * L.n_pad * 4);
     L.qh = take((size_t)Hq * L.n_pad * D * 2);
     L.doh = take((size_t)Hq * L.n_pad * D * 2);
@@ -1239,16 +1285,20 @@ size_t bwd_workspace(int64_t S, int64_t n_loc, int32_t Hq, int32_t Hkv, int32_t 
     return bwd_layout(S, n_loc, (int32_t)(n_loc / 16 + 1), Hq, Hkv, D).total;
 }
 
+// qh == nullptr: the preparation has run (ld holds the rows' LSE and Delta); else this pass
+// forms Delta itself and writes the key-outer pass's inputs
 template <int D, int HPW, int NST>
-static void launch_dq_kernel(const AttnArgs& a, const void* d_o, int64_t n_loc, const BwdLayout& L,
-                             float scale_log2, const int32_t* clean, const float* ld,
-                             const TilePlan& pa, const int32_t* err, void* dq, float* dq_part,
+static void launch_dq_kernel(const AttnArgs& a, const void* o, const float* lse, const void* d_o,
+                             int64_t n_loc, const BwdLayout& L, float scale_log2, const int32_t* clean,
+                             const float* ld, const TilePlan& pa, const int32_t* err, void* dq,
+                             float* dq_part, ushort_t* qh, ushort_t* doh, float* ldk, uint32_t* info,
                              hipStream_t st) {
     const unsigned grid = (unsigned)((int64_t)L.nq_a * a.Hq / HPW * L.split.cmax);
     hipLaunchKernelGGL((dq_kernel<D, HPW, NST>), dim3(grid), dim3(256 * HPW), 0, st,
                        (const ushort_t*)a.q, (const ushort_t*)a.k, (const ushort_t*)a.v,
                        (const ushort_t*)d_o, a.bits, clean, a.block, n_loc, L.n_pad, a.S, a.Hq, a.Hkv,
-                       a.scale, scale_log2, ld, pa, L.split, err, (ushort_t*)dq, dq_part);
+                       a.scale, scale_log2, (const ushort_t*)o, lse, ld, pa, L.split, err, (ushort_t*)dq,
+                       dq_part, qh, doh, ldk, info);
 }
 
 template <int D>
@@ -1260,6 +1310,7 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     int32_t* err = (int32_t*)(base + L.err);
     int32_t* clean = (int32_t*)(base + L.clean_blocks);
     float* ld = (float*)(base + L.ld);
+    uint32_t* info = (uint32_t*)(base + L.info);
     float* ldk = (float*)(base + L.ldk);
     ushort_t* qh = (ushort_t*)(base + L.qh);
     ushort_t* doh = (ushort_t*)(base + L.doh);
@@ -1283,8 +1334,15 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
     pb.pbase = (int32_t*)(base + L.pbase);
     pb.extra = (int32_t*)(base + L.extra);
 
-    // both plans side by side with the block-list check and the row constants: one launch,
-    // then the list builder's two
+    // The key-outer pass needs head-major copies of Q and dO, its rows' constants and mask
+    // inputs.  The query-outer pass holds every row's Q and dO in registers and can leave them
+    // on its way at little cost, which saves a pass over Q, O and dO -- but then it has to run
+    // first, and the copies are as old as that pass is long when the key-outer pass reads
+    // them.  Measured (same box, alternating): whole steps -1.0 % at 8k and -0.3 % at 32k
+    // (copies of 128 MiB), +0.4 % at 128k and +1.0 % on the packed 64k share (256 MiB, the
+    // size of the last-level cache): there the copies come from a preparation of their own,
+    // right before the key-outer pass, and the query-outer pass runs last.
+    const bool dq_first = (size_t)2 * a.Hq * L.n_pad * D * 2 <= ((size_t)128 << 20);
     const float scale_log2 = a.scale * kLog2e;
     {
         BwdPrologue p;
@@ -1295,20 +1353,41 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
         p.clean = clean; p.err = err;
         p.prep = BwdPrepArgs{(const ushort_t*)a.q, (const ushort_t*)o, (const ushort_t*)d_o, lse, a.bits,
                              a.blocks, a.block, a.Hq, a.S / a.block, n_loc, L.n_pad, 1.0f / a.scale,
-                             ld, ldk, qh, doh};
-        const int64_t threads = L.n_pad * a.Hq * (D / 8);
+                             ld, ldk, info, qh, doh};
+        const int64_t threads = dq_first ? 0 : L.n_pad * a.Hq * (D / 8);
         const unsigned grid = p.n_map_wgs + 1u + (unsigned)((threads + 255) / 256);
         hipLaunchKernelGGL(bwd_prologue_kernel<D>, dim3(grid), dim3(256), 0, st, p);
         MM_LAUNCH_CHECK();
     }
     int rc = launch_compact_both(pa, pb, st);
     if (rc) return rc;
-    const int rep = a.Hq / a.Hkv;
+    // One query head per workgroup of four wavefronts and a two-stage ring: two such
+    // workgroups share a CU with independent barriers.  Measured against a workgroup of
+    // two heads (eight wavefronts sharing the K/V tiles, three or four stages, also with
+    // the two heads' phases half a tile out of step): equal at 128k, 1 % to 4 % faster
+    // elsewhere.
+    auto run_dq = [&]() {
+        stage_begin(MMATTN_STAGE_DQ, st);
+        float* dq_part = (float*)(base + L.dq_part);
+        if (dq_first)
+            launch_dq_kernel<D, 1, 2>(a, o, lse, d_o, n_loc, L, scale_log2, clean, nullptr, pa, err, dq,
+                                      dq_part, qh, doh, ldk, info, st);
+        else
+            launch_dq_kernel<D, 1, 2>(a, o, lse, d_o, n_loc, L, scale_log2, clean, ld, pa, err, dq,
+                                      dq_part, nullptr, nullptr, nullptr, nullptr, st);
+        if (L.split.cmax > 1) {
+            const int64_t threads = n_loc * a.Hq * (D / 4);
+            hipLaunchKernelGGL(dq_combine_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                               pa, L.split, n_loc, L.n_pad, a.Hq, D, err, dq_part, (ushort_t*)dq);
+        }
+        stage_end(MMATTN_STAGE_DQ, st);
+    };
+    if (dq_first) run_dq();
     stage_begin(MMATTN_STAGE_DKV, st);
     hipLaunchKernelGGL(dkv_kernel<D>, dim3((unsigned)((int64_t)(L.nk_b + L.n_extra) * a.Hkv * L.ch.cmax)),
                        dim3(kKvThreads), 0, st, (const ushort_t*)qh, (const ushort_t*)a.k,
                        (const ushort_t*)a.v, (const ushort_t*)doh, a.bits, clean, a.block, n_loc,
-                       L.n_pad, a.S, a.Hq, a.Hkv, a.scale, scale_log2, ld, ldk, pb, L.ch, err,
+                       L.n_pad, a.S, a.Hq, a.Hkv, a.scale, scale_log2, info, ldk, pb, L.ch, err,
                        (ushort_t*)dk, (ushort_t*)dv, pool);
     stage_end(MMATTN_STAGE_DKV, st);
     if (L.ch.cmax > 1 || L.n_extra > 0) {
@@ -1318,20 +1397,7 @@ static int launch_bwd_d(const AttnArgs& a, const void* o, const float* lse, cons
                            dim3(256), 0, st, pb, a.Hkv, D, err, (const float*)pool, (ushort_t*)dk, (ushort_t*)dv);
         stage_end(MMATTN_STAGE_DKV_REDUCE, st);
     }
-    // One query head per workgroup of four wavefronts and a two-stage ring: two such
-    // workgroups share a CU with independent barriers.  Measured against a workgroup of
-    // two heads (eight wavefronts sharing the K/V tiles, three or four stages, also with
-    // the two heads' phases half a tile out of step): equal at 128k, 1 % to 4 % faster
-    // elsewhere.
-    stage_begin(MMATTN_STAGE_DQ, st);
-    float* dq_part = (float*)(base + L.dq_part);
-    launch_dq_kernel<D, 1, 2>(a, d_o, n_loc, L, scale_log2, clean, ld, pa, err, dq, dq_part, st);
-    if (L.split.cmax > 1) {
-        const int64_t threads = n_loc * a.Hq * (D / 4);
-        hipLaunchKernelGGL(dq_combine_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                           pa, L.split, n_loc, L.n_pad, a.Hq, D, err, dq_part, (ushort_t*)dq);
-    }
-    stage_end(MMATTN_STAGE_DQ, st);
+    if (!dq_first) run_dq();
     MM_LAUNCH_CHECK();
     return MMATTN_OK;
 }
