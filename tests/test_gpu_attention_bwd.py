@@ -249,6 +249,20 @@ def test_workload2_full_sequence():
     sampled_dq_and_dv_sums(w, blocks, t, outs, heads=(0, 13, 31))
 
 
+def test_large_share_keeps_its_own_preparation():
+    """Shares whose head-major copies of Q and dO exceed 128 MiB (here 8192 rows x 48 heads x
+    128: 192 MiB) take the backward's other launch order: the inputs of the key-outer pass
+    come from a preparation of their own and the query-outer pass runs last.  Whole KV
+    group against the oracle, element by element (also the only full-size case with six
+    query heads per KV head)."""
+    w2 = wl.workload(2)
+    w = wl.Workload("vlm_8k_48_heads", w2.layout, 48, 8, 128, w2.N_B, 1, 2102)
+    blocks = list(range(w.layout.S // w.N_B))
+    t = make_tensors(w.tensor_seed, w.layout.S, w.layout.S, w.Hq, w.Hkv, w.D)
+    outs = gpu_fwd_bwd(w.layout, blocks, w.N_B, t)
+    group_check(w, blocks, t, outs, g=2)
+
+
 def key_range_check(w, blocks, t, outs, g, k_lo, k_hi, max_rows):
     """dK and dV of the keys [k_lo, k_hi) of KV head g, element by element: the
     oracle runs on exactly the share's rows that see any of these keys (the
