@@ -271,7 +271,9 @@ int mmattn_bwd(const void* q_loc, const void* k, const void* v, const uint64_t* 
  * before and ev_stop just after that stage's main kernel on the call's stream,
  * so a harness can time one kernel inside a multi-launch call (FWD and DQ
  * include the aggregation launch when lists are split; DKV_REDUCE is the
- * partial-sum launch after the dK/dV kernel, recorded only when it runs).  Pass
+ * partial-sum launch after the dK/dV kernel, recorded only when it runs; a
+ * complete pair for DKV travels with the kernel's dispatch instead and carries
+ * the kernel's own begin and end times).  Pass
  * nulls to clear.  stage: MMATTN_STAGE_*.  The only process-wide state in the library;
  * not thread-safe.  Returns MMATTN_ERR_SHAPE for an unknown stage. */
 enum { MMATTN_STAGE_FWD = 0, MMATTN_STAGE_DKV = 1, MMATTN_STAGE_DQ = 2, MMATTN_STAGE_DKV_REDUCE = 3,
