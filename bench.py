@@ -299,9 +299,9 @@ STAGE_KERNEL = {"fwd": "fwd_kernel", "dkv": "dkv_kernel", "dq": "dq_kernel"}
 
 def measure(sh, steps, warmup, all_stage_events=False, after_warmup=None):
     """Warm up, then time exactly `steps` steps between two synchronisations (mean),
-    with one event per step for the median and the minimum, and the dominant kernel
-    (dK/dV) bracketed by events inside the timed region; then a short second pass with
-    events around all four main kernels and around the two attention calls."""
+    with the median and the minimum of the step period beside it, and the dominant kernel
+    (dK/dV) timed by events inside the timed region; then a second pass with events
+    around the two attention calls and around all four main kernels."""
     import torch
     from paper_2503_11367_amd import binding as mb
     w = sh.w
@@ -315,13 +315,11 @@ def measure(sh, steps, warmup, all_stage_events=False, after_warmup=None):
     # HIP events recorded by the library around each main kernel, one pair per step
     stages = {"fwd": mb.STAGE_FWD, "dkv": mb.STAGE_DKV, "dkv_reduce": mb.STAGE_DKV_REDUCE,
               "dq": mb.STAGE_DQ}
-    evs = {n: [(ev(), ev()) for _ in range(steps)] for n in stages}
-    marks = [ev() for _ in range(steps + 1)]
+    n2 = min(steps, 20)                        # steps of each half of the second pass
+    evs = {n: [(ev(), ev()) for _ in range(steps if (all_stage_events or n == "dkv") else n2)] for n in stages}
     for n in stages:
         for a, b in evs[n]:
             a.record(); b.record()             # materialise the handles
-    for m in marks:
-        m.record()
     torch.cuda.synchronize()
 
     # Timed region: only the dominant kernel (the key-outer backward pass, 8 of the 14
@@ -332,23 +330,31 @@ def measure(sh, steps, warmup, all_stage_events=False, after_warmup=None):
     for i in range(steps):
         for n, sid in timed.items():
             mb.stage_events(sid, evs[n][i][0].cuda_event, evs[n][i][1].cuda_event)
-        marks[i].record()
         sh.step()
-    marks[steps].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for sid in stages.values():
         mb.stage_events(sid, 0, 0)
     ms_per_step = (t1 - t0) * 1e3 / steps
-    # step i as the stream saw it: from its first launch to the next step's first launch
-    per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+    # A step as the stream saw it, for the median and the minimum: the period between the
+    # dominant kernel's begin times of consecutive steps (the events that kernel carries
+    # anyway; no event records of their own between the steps).  steps - 1 periods.
+    begins = [a for a, _ in evs["dkv"]]
+    per_step = [begins[i].elapsed_time(begins[i + 1]) for i in range(steps - 1)] or [ms_per_step]
     kern = {n: [a.elapsed_time(b) for a, b in evs[n]] for n in timed}
-    n2 = min(steps, 5)
+    # Second pass, straight behind a run of untimed steps (after the pause above the chip's
+    # clock needs tens of milliseconds to come back): first steps with events around the
+    # two attention calls only, then steps with events around the main kernels, so that
+    # the whole-call times do not contain the kernels' event records.
     calls = [(ev(), ev(), ev(), ev()) for _ in range(n2)]
+    for _ in range(min(steps, 100)):
+        sh.step()
+    for i in range(n2):
+        sh.step(calls[i])
     for i in range(n2):
         for n, sid in stages.items():
             mb.stage_events(sid, evs[n][i][0].cuda_event, evs[n][i][1].cuda_event)
-        sh.step(calls[i])
+        sh.step()
     torch.cuda.synchronize()
     for sid in stages.values():
         mb.stage_events(sid, 0, 0)
@@ -384,8 +390,11 @@ def measure(sh, steps, warmup, all_stage_events=False, after_warmup=None):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default: about 2.5 s of timed work on the 8k workload, 1000 "
+                         "steps, 40 on the others; a run of 20 steps, 50 ms, ends before the chip's "
+                         "clock has settled and reads 2 %% low)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps first (default 20, 5 on the others)")
     ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2, the metric's config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path-only", action="store_true",
@@ -398,6 +407,10 @@ def main():
                     help="also run one 256 MiB device-to-device copy (a known-size kernel "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 1000 if args.workload == 2 else 40
+    if args.warmup is None:
+        args.warmup = 20 if args.workload == 2 else 5
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path "
               "(run with --gpus 1)", file=sys.stderr)
@@ -474,8 +487,8 @@ def main():
                            groups, sh.pairs)
 
     if not args.path_only:
-        # the other balanced workloads (heaviest rank's share, whole steps): 3 warm-up and 5
-        # timed steps each; the headline stays the workload above
+        # the other balanced workloads (heaviest rank's share, whole steps): 5 warm-up steps and
+        # about a second of timed steps each; the headline stays the workload above
         del sh
         torch.cuda.empty_cache()
         others = {}
@@ -484,7 +497,9 @@ def main():
                 continue
             wo = wl.workload(c)
             so = Share(wo, device)
-            mo = measure(so, 5, 3)
+            # about a second of timed work each (a few steps of tens of milliseconds end
+            # before the clock has settled, like the short default run above)
+            mo = measure(so, {3: 100, 4: 15, 5: 200}[c], 5)
             others[wo.name] = {"n_loc": so.n_loc, "S": wo.layout.S, "Hq": wo.Hq, "Hkv": wo.Hkv,
                                "P": wo.P, "pairs": so.pairs, "ms_per_step": mo["ms_per_step"],
                                "ms_per_step_median": mo["ms_per_step_median"],
