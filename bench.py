@@ -360,7 +360,7 @@ def measure(sh, steps, warmup, all_stage_events=False, after_warmup=None):
     # two attention calls only, then steps with events around the main kernels, so that
     # the whole-call times do not contain the kernels' event records.
     calls = [(ev(), ev(), ev(), ev()) for _ in range(n2)]
-    for _ in range(min(steps, 100)):
+    for _ in range(max(settle, 20)):
         sh.step()
     for i in range(n2):
         sh.step(calls[i])
